@@ -1,0 +1,182 @@
+"""CPU oracle for spherical attention -- TEST INFRASTRUCTURE, not the product.
+
+Only the tests, the smoke check and the benchmark's CPU-baseline leg may import
+this package.  It shares no code with the HIP library and never imports it.
+
+The arithmetic lives in ``sphattn_oracle.c`` (plain fp64 C, two passes per query
+row, straight from the paper's definition of a normalized contraction in
+Appendix A.1 with a1 = id, a2 = square, b = sqrt; Section 3).  This module only
+compiles that file with gcc and marshals numpy arrays into it.
+
+Stored formats understood for the inputs ("kind"):
+    "f64", "f32"  -- numpy float64 / float32 arrays
+    "bf16"        -- numpy uint16 arrays holding bfloat16 bit patterns
+    "e4m3fn"      -- numpy uint8 arrays holding OCP E4M3 (finite-only) bytes
+All are widened exactly to fp64 inside the C code.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sphattn_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_sphattn.so")
+
+_KINDS = {"f64": 0, "f32": 1, "bf16": 2, "e4m3fn": 3}
+_KIND_DTYPES = {"f64": np.float64, "f32": np.float32, "bf16": np.uint16, "e4m3fn": np.uint8}
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, OpenMP, no fast-math). Returns the .so path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        vp, ip, dp = ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double)
+        lib.oracle_attention_fwd.restype = ip
+        lib.oracle_attention_fwd.argtypes = [ip, vp, ip, vp, ip, vp, ip, dp, dp, dp, ip, ip, ip, ip]
+        lib.oracle_attention_rows.restype = ip
+        lib.oracle_attention_rows.argtypes = [ip, vp, ip, vp, ip, vp, ip, dp, ip, ip, ip, ip, ip,
+                                              ctypes.POINTER(ctypes.c_int), ip]
+        lib.oracle_spherical_streamed.restype = ip
+        lib.oracle_spherical_streamed.argtypes = [dp, dp, dp, dp, ip, ip, ip, ip, ip]
+        lib.oracle_widen.restype = None
+        lib.oracle_widen.argtypes = [vp, ip, ctypes.c_size_t, ctypes.c_size_t, dp]
+        lib.oracle_num_threads.restype = ip
+        lib.oracle_num_threads.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _kind_of(a: np.ndarray, kind: str | None) -> str:
+    if kind is None:
+        if a.dtype == np.float64:
+            kind = "f64"
+        elif a.dtype == np.float32:
+            kind = "f32"
+        else:
+            raise TypeError("kind must be given for arrays that are not float32/float64")
+    if kind not in _KINDS:
+        raise ValueError(f"unknown kind {kind!r}")
+    if a.dtype != _KIND_DTYPES[kind]:
+        raise TypeError(f"kind {kind!r} needs dtype {_KIND_DTYPES[kind]}, got {a.dtype}")
+    return kind
+
+
+def _prep(a, kind):
+    a = np.ascontiguousarray(a)
+    kind = _kind_of(a, kind)
+    if a.ndim != 4:
+        raise ValueError("expected a [B,H,N,d] array")
+    return a, kind
+
+
+def _dptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def num_threads() -> int:
+    """Threads the OpenMP loops will use."""
+    return int(_load().oracle_num_threads())
+
+
+def widen(a: np.ndarray, kind: str | None = None) -> np.ndarray:
+    """Exact fp64 values of a stored array (any shape)."""
+    a = np.ascontiguousarray(a)
+    kind = _kind_of(a, kind)
+    out = np.empty(a.shape, dtype=np.float64)
+    _load().oracle_widen(a.ctypes.data_as(ctypes.c_void_p), _KINDS[kind], 0, a.size, _dptr(out))
+    return out
+
+
+def _fwd(mode, Q, K, V, kinds, want_weights, want_z):
+    kq, kk, kv = kinds if kinds is not None else (None, None, None)
+    Q, kq = _prep(Q, kq)
+    K, kk = _prep(K, kk)
+    V, kv = _prep(V, kv)
+    if not (Q.shape == K.shape == V.shape):
+        raise ValueError("Q, K, V must share the shape [B,H,N,d]")
+    B, H, N, d = Q.shape
+    O = np.empty((B, H, N, d), dtype=np.float64)
+    W = np.empty((B, H, N, N), dtype=np.float64) if want_weights else None
+    Z = np.empty((B, H, N), dtype=np.float64) if want_z else None
+    rc = _load().oracle_attention_fwd(
+        mode, Q.ctypes.data_as(ctypes.c_void_p), _KINDS[kq],
+        K.ctypes.data_as(ctypes.c_void_p), _KINDS[kk],
+        V.ctypes.data_as(ctypes.c_void_p), _KINDS[kv],
+        _dptr(O), _dptr(W) if W is not None else None, _dptr(Z) if Z is not None else None,
+        B, H, N, d)
+    if rc != 0:
+        raise RuntimeError(f"oracle_attention_fwd failed with {rc}")
+    return O, W, Z
+
+
+def spherical_attention(Q, K, V, kinds=None) -> np.ndarray:
+    """O = (S V) / ||S row||_2 with S = Q K^T, fp64, [B,H,N,d]."""
+    return _fwd(0, Q, K, V, kinds, False, False)[0]
+
+
+def spherical_attention_full(Q, K, V, kinds=None):
+    """(O, W, Z): output, normalized weights [B,H,N,N], squared row norms [B,H,N]."""
+    return _fwd(0, Q, K, V, kinds, True, True)
+
+
+def softmax_attention(Q, K, V, kinds=None) -> np.ndarray:
+    """Comparison twin: softmax(Q K^T / sqrt(d)) V, fp64."""
+    return _fwd(1, Q, K, V, kinds, False, False)[0]
+
+
+def _rows(mode, Q, K, V, bh, rows, kinds):
+    kq, kk, kv = kinds if kinds is not None else (None, None, None)
+    Q, kq = _prep(Q, kq)
+    K, kk = _prep(K, kk)
+    V, kv = _prep(V, kv)
+    B, H, N, d = Q.shape
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    out = np.empty((rows.size, d), dtype=np.float64)
+    rc = _load().oracle_attention_rows(
+        mode, Q.ctypes.data_as(ctypes.c_void_p), _KINDS[kq],
+        K.ctypes.data_as(ctypes.c_void_p), _KINDS[kk],
+        V.ctypes.data_as(ctypes.c_void_p), _KINDS[kv],
+        _dptr(out), B, H, N, d, int(bh),
+        rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), int(rows.size))
+    if rc != 0:
+        raise RuntimeError(f"oracle_attention_rows failed with {rc}")
+    return out
+
+
+def spherical_attention_rows(Q, K, V, bh: int, rows, kinds=None) -> np.ndarray:
+    """Output rows `rows` of flattened head index `bh` (= b*H + h): [len(rows), d]."""
+    return _rows(0, Q, K, V, bh, rows, kinds)
+
+
+def softmax_attention_rows(Q, K, V, bh: int, rows, kinds=None) -> np.ndarray:
+    return _rows(1, Q, K, V, bh, rows, kinds)
+
+
+def spherical_attention_streamed(Q, K, V, chunk: int) -> np.ndarray:
+    """Lemma 1's loop: carry (o, z) over key chunks of size `chunk`, then o/sqrt(z)."""
+    Q = np.ascontiguousarray(Q, dtype=np.float64)
+    K = np.ascontiguousarray(K, dtype=np.float64)
+    V = np.ascontiguousarray(V, dtype=np.float64)
+    B, H, N, d = Q.shape
+    O = np.empty_like(Q)
+    rc = _load().oracle_spherical_streamed(_dptr(Q), _dptr(K), _dptr(V), _dptr(O),
+                                           B, H, N, d, int(chunk))
+    if rc != 0:
+        raise RuntimeError(f"oracle_spherical_streamed failed with {rc}")
+    return O

@@ -1,0 +1,300 @@
+/*
+ * CPU oracle for spherical attention (forward).  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain, fp64 statement of what the GPU library must
+ * compute.  It is used by the tests, by the smoke check and by the benchmark's
+ * CPU-baseline leg.  It shares no code with the HIP path and the product never
+ * calls it.
+ *
+ * What is computed (paper, Appendix A.1, definition of a normalized
+ * contraction, with the spherical choice of Section 3: a1(x) = x,
+ * a2(x) = x^2, b = sqrt, i.e. the score row is divided by its L2 norm):
+ *
+ *     s_ij = sum_k Q[b,h,i,k] * K[b,h,j,k]                 (Theorem 1: the Q/K
+ *                                                           contraction feeding
+ *                                                           the normalizer)
+ *     z_i  = sum_j s_ij^2                                   (sum_j a2(x_j))
+ *     O[b,h,i,:] = ( sum_j s_ij * V[b,h,j,:] ) / sqrt(z_i)  (NC(x, y))
+ *
+ * A row with z_i = 0 has an all-zero numerator as well; it is defined as 0
+ * (the paper gives no epsilon, so none is used).
+ *
+ * No score scale (1/sqrt(d) or other) is applied: any positive factor on the
+ * scores cancels between numerator and sqrt(z).
+ *
+ * Inputs are taken exactly as stored (fp64, fp32, bf16 bit patterns or OCP
+ * e4m3fn bytes) and widened exactly to fp64 before any arithmetic.  Layout is
+ * dense row-major [B,H,N,d] with d contiguous.
+ *
+ * The comparison twin (standard SoftMax attention, a1 = a2 = exp, b = id, with
+ * the conventional 1/sqrt(d) score scale) is also given, from its textbook
+ * definition.
+ *
+ * Parity pins (tests/test_oracle_*.py): exact-rational brute force on tiny
+ * inputs, unit-norm weight rows, Cauchy-Schwarz bound, scale/sign invariance,
+ * linearity in V, N = 1 and orthonormal-key closed forms, the Gram-matrix
+ * closed form, and chunk-size / permutation / zero-padding invariance of the
+ * streamed accumulator of Lemma 1.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F64 = 0, ORACLE_F32 = 1, ORACLE_BF16 = 2, ORACLE_E4M3FN = 3 };
+
+/* ---- exact widening of stored formats to fp64 --------------------------- */
+
+/* bfloat16: the upper 16 bits of an IEEE binary32. */
+static double widen_bf16(uint16_t bits)
+{
+    uint32_t u = (uint32_t)bits << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* OCP 8-bit float E4M3 ("fn": finite, no infinities): 1 sign, 4 exponent
+ * (bias 7), 3 mantissa bits; exponent field 0 is subnormal (2^-6 * m/8);
+ * S.1111.111 is NaN; every other code is a finite number, max 448. */
+static double widen_e4m3fn(uint8_t bits)
+{
+    int sign = bits >> 7;
+    int e = (bits >> 3) & 0xF;
+    int m = bits & 0x7;
+    double v;
+    if (e == 0xF && m == 0x7)
+        v = NAN;
+    else if (e == 0)
+        v = ldexp((double)m, -9);              /* m/8 * 2^-6 */
+    else
+        v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+static double load_elem(const void *p, int kind, size_t idx)
+{
+    switch (kind) {
+    case ORACLE_F64: return ((const double *)p)[idx];
+    case ORACLE_F32: return (double)((const float *)p)[idx];
+    case ORACLE_BF16: return widen_bf16(((const uint16_t *)p)[idx]);
+    case ORACLE_E4M3FN: return widen_e4m3fn(((const uint8_t *)p)[idx]);
+    default: return NAN;
+    }
+}
+
+/* Widen `count` stored elements starting at element offset `off`. */
+void oracle_widen(const void *src, int kind, size_t off, size_t count, double *dst)
+{
+    for (size_t t = 0; t < count; ++t)
+        dst[t] = load_elem(src, kind, off + t);
+}
+
+/* ---- one query row, given one head's K and V already widened ------------ */
+
+/* Spherical row: two passes, exactly as the definition reads.
+ * s (length N) is caller-provided scratch and holds the raw scores on return.
+ * w, if not NULL, receives the normalized weights s_j / sqrt(z). */
+static void spherical_row(const double *q, const double *Kh, const double *Vh,
+                          int N, int d, double *s, double *o, double *w, double *z_out)
+{
+    double z = 0.0;
+    for (int j = 0; j < N; ++j) {
+        double acc = 0.0;
+        for (int k = 0; k < d; ++k)
+            acc += q[k] * Kh[(size_t)j * d + k];
+        s[j] = acc;
+        z += acc * acc;
+    }
+    for (int k = 0; k < d; ++k)
+        o[k] = 0.0;
+    for (int j = 0; j < N; ++j)
+        for (int k = 0; k < d; ++k)
+            o[k] += s[j] * Vh[(size_t)j * d + k];
+    double nrm = sqrt(z);
+    for (int k = 0; k < d; ++k)
+        o[k] = (z > 0.0) ? o[k] / nrm : 0.0;
+    if (w)
+        for (int j = 0; j < N; ++j)
+            w[j] = (z > 0.0) ? s[j] / nrm : 0.0;
+    if (z_out)
+        *z_out = z;
+}
+
+/* SoftMax row (comparison twin): p_j = exp(c*s_j - max) / sum, c = 1/sqrt(d). */
+static void softmax_row(const double *q, const double *Kh, const double *Vh,
+                        int N, int d, double *s, double *o)
+{
+    double c = 1.0 / sqrt((double)d);
+    double mx = -INFINITY;
+    for (int j = 0; j < N; ++j) {
+        double acc = 0.0;
+        for (int k = 0; k < d; ++k)
+            acc += q[k] * Kh[(size_t)j * d + k];
+        s[j] = acc * c;
+        if (s[j] > mx)
+            mx = s[j];
+    }
+    double den = 0.0;
+    for (int j = 0; j < N; ++j) {
+        s[j] = exp(s[j] - mx);
+        den += s[j];
+    }
+    for (int k = 0; k < d; ++k)
+        o[k] = 0.0;
+    for (int j = 0; j < N; ++j)
+        for (int k = 0; k < d; ++k)
+            o[k] += s[j] * Vh[(size_t)j * d + k];
+    for (int k = 0; k < d; ++k)
+        o[k] /= den;
+}
+
+/* ---- whole-tensor entry points ------------------------------------------ */
+
+/* mode 0 = spherical, 1 = softmax twin.
+ * Q, K, V: [B,H,N,d] in the stored format named by q_kind/k_kind/v_kind.
+ * O: [B,H,N,d] fp64.  W (may be NULL; spherical only): [B,H,N,N] weights.
+ * Z (may be NULL; spherical only): [B,H,N] squared row norms.
+ * Returns 0, or -1 on bad arguments / allocation failure. */
+int oracle_attention_fwd(int mode, const void *Q, int q_kind, const void *K, int k_kind,
+                         const void *V, int v_kind, double *O, double *W, double *Z,
+                         int B, int H, int N, int d)
+{
+    if (!Q || !K || !V || !O || B <= 0 || H <= 0 || N <= 0 || d <= 0)
+        return -1;
+    size_t head = (size_t)N * d;
+    double *Kh = malloc(head * sizeof *Kh);
+    double *Vh = malloc(head * sizeof *Vh);
+    int status = (Kh && Vh) ? 0 : -1;
+    for (int bh = 0; bh < B * H && status == 0; ++bh) {
+        oracle_widen(K, k_kind, (size_t)bh * head, head, Kh);
+        oracle_widen(V, v_kind, (size_t)bh * head, head, Vh);
+#pragma omp parallel
+        {
+            double *q = malloc((size_t)d * sizeof *q);
+            double *s = malloc((size_t)N * sizeof *s);
+            if (!q || !s) {
+#pragma omp atomic write
+                status = -1;
+            } else {
+#pragma omp for schedule(static)
+                for (int i = 0; i < N; ++i) {
+                    size_t row = (size_t)bh * N + i;
+                    oracle_widen(Q, q_kind, row * d, (size_t)d, q);
+                    if (mode == 0)
+                        spherical_row(q, Kh, Vh, N, d, s, O + row * d,
+                                      W ? W + row * N : NULL, Z ? Z + row : NULL);
+                    else
+                        softmax_row(q, Kh, Vh, N, d, s, O + row * d);
+                }
+            }
+            free(q);
+            free(s);
+        }
+    }
+    free(Kh);
+    free(Vh);
+    return status;
+}
+
+/* Selected query rows of one head only (for full-size workloads, where the
+ * whole tensor would take minutes): rows[r] in [0,N) of head index bh in
+ * [0,B*H).  O_rows: [n_rows, d] fp64. */
+int oracle_attention_rows(int mode, const void *Q, int q_kind, const void *K, int k_kind,
+                          const void *V, int v_kind, double *O_rows,
+                          int B, int H, int N, int d, int bh, const int *rows, int n_rows)
+{
+    if (!Q || !K || !V || !O_rows || !rows || B <= 0 || H <= 0 || N <= 0 || d <= 0 ||
+        bh < 0 || bh >= B * H || n_rows < 0)
+        return -1;
+    for (int r = 0; r < n_rows; ++r)
+        if (rows[r] < 0 || rows[r] >= N)
+            return -1;
+    size_t head = (size_t)N * d;
+    double *Kh = malloc(head * sizeof *Kh);
+    double *Vh = malloc(head * sizeof *Vh);
+    int status = (Kh && Vh) ? 0 : -1;
+    if (status == 0) {
+        oracle_widen(K, k_kind, (size_t)bh * head, head, Kh);
+        oracle_widen(V, v_kind, (size_t)bh * head, head, Vh);
+#pragma omp parallel
+        {
+            double *q = malloc((size_t)d * sizeof *q);
+            double *s = malloc((size_t)N * sizeof *s);
+            if (!q || !s) {
+#pragma omp atomic write
+                status = -1;
+            } else {
+#pragma omp for schedule(static)
+                for (int r = 0; r < n_rows; ++r) {
+                    size_t row = (size_t)bh * N + rows[r];
+                    oracle_widen(Q, q_kind, row * d, (size_t)d, q);
+                    if (mode == 0)
+                        spherical_row(q, Kh, Vh, N, d, s, O_rows + (size_t)r * d, NULL, NULL);
+                    else
+                        softmax_row(q, Kh, Vh, N, d, s, O_rows + (size_t)r * d);
+                }
+            }
+            free(q);
+            free(s);
+        }
+    }
+    free(Kh);
+    free(Vh);
+    return status;
+}
+
+/* Lemma 1 as a loop: the key axis is cut into chunks of `chunk` rows (the last
+ * may be shorter); only (o, z) is carried between chunks, starting from (0,0),
+ * updated by B((o,z),(x,y)) = (o + sum a1(x_i) y_i, z + sum a2(x_i)); the tail
+ * t(o,z) = o / b(z) is applied once at the end.  fp64 inputs only.
+ * Exists so the streaming identity can be tested against the direct form. */
+int oracle_spherical_streamed(const double *Q, const double *K, const double *V, double *O,
+                              int B, int H, int N, int d, int chunk)
+{
+    if (!Q || !K || !V || !O || B <= 0 || H <= 0 || N <= 0 || d <= 0 || chunk <= 0)
+        return -1;
+    size_t head = (size_t)N * d;
+    double *o = malloc((size_t)d * sizeof *o);
+    if (!o)
+        return -1;
+    for (int bh = 0; bh < B * H; ++bh) {
+        const double *Kh = K + (size_t)bh * head, *Vh = V + (size_t)bh * head;
+        for (int i = 0; i < N; ++i) {
+            const double *q = Q + (size_t)bh * head + (size_t)i * d;
+            double z = 0.0;
+            for (int k = 0; k < d; ++k)
+                o[k] = 0.0;
+            for (int j0 = 0; j0 < N; j0 += chunk) {
+                int j1 = j0 + chunk < N ? j0 + chunk : N;
+                double dz = 0.0;
+                for (int j = j0; j < j1; ++j) {
+                    double x = 0.0;
+                    for (int k = 0; k < d; ++k)
+                        x += q[k] * Kh[(size_t)j * d + k];
+                    dz += x * x;
+                    for (int k = 0; k < d; ++k)
+                        o[k] += x * Vh[(size_t)j * d + k];
+                }
+                z += dz;
+            }
+            double *out = O + (size_t)bh * head + (size_t)i * d;
+            for (int k = 0; k < d; ++k)
+                out[k] = (z > 0.0) ? o[k] / sqrt(z) : 0.0;
+        }
+    }
+    free(o);
+    return 0;
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
