@@ -1,0 +1,140 @@
+#!/usr/bin/env python3
+"""Benchmark: spherical-attention forward on one MI355X.
+
+A step is one full forward pass (both N x N contractions, the row-norm
+accumulation and the tail) over one batch of synthetic Gaussian Q/K/V already
+resident in HBM.  Throughput uses the 4*B*H*N^2*d FLOP convention.  Prints one
+JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "fp8qk_bf16v": 2500.0, "f32": 157.3}   # dense MFMA, MI355X
+HBM_PEAK_GBS = 8000.0
+
+
+def time_launches(fn, steps, warmup):
+    """Average and per-launch durations (ms) of `fn`, HIP events on the launch stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record()
+        fn()
+        ends[i].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    per = sorted(s.elapsed_time(e) for s, e in zip(starts, ends))
+    return wall_ms / steps, per
+
+
+def cpu_baseline(w, q, k, v, budget_s=12.0):
+    """The fp64 oracle, as it stands, on a bounded sample of query rows of head 0."""
+    import numpy as np
+    import oracle
+    import synthetic_inputs as si
+    (qb, qk), (kb, kk), (vb, vk) = (si.storage_bits(t) for t in (q, k, v))
+    kinds = (qk, kk, vk)
+    threads = oracle.num_threads()
+    rows = np.arange(min(w.N, 4 * threads), dtype=np.int32)
+    t0 = time.perf_counter()
+    oracle.spherical_attention_rows(qb, kb, vb, 0, rows, kinds)
+    t_probe = time.perf_counter() - t0
+    per_row = max(t_probe / len(rows), 1e-9)
+    n_rows = int(min(w.N, max(len(rows), budget_s / per_row)))
+    n_rows = max(threads, n_rows - n_rows % threads)
+    rows = np.arange(n_rows, dtype=np.int32) % w.N
+    t0 = time.perf_counter()
+    oracle.spherical_attention_rows(qb, kb, vb, 0, rows, kinds)
+    dt = time.perf_counter() - t0
+    flops = 4.0 * n_rows * w.N * w.d
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+        "sample": f"{n_rows} query rows of head 0 of {w.name} (all {w.N} keys), fp64, "
+                  f"{dt:.2f} s; whole workload extrapolates to {dt * w.B * w.H * w.N / n_rows:.0f} s",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C3", help="C1..C5 (default C3: the configuration the target is quoted on)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-twin", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path "
+              "(heads and query tiles shard with no communication); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2505_09326_amd as pkg
+    import synthetic_inputs as si
+
+    pkg.load_library()                       # fail loudly if the HIP library is not built
+    w, (q, k, v) = si.make_workload(args.workload)
+    dev = torch.device("cuda:0")
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    out = torch.empty(qd.shape, dtype=torch.float32 if w.dtype == "f32" else torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+
+    def step():
+        pkg.sphattn_fwd(qd, kd, vd, out, dtype=w.dtype)
+
+    ms_wall, per = time_launches(step, args.steps, args.warmup)
+    ms_kernel = sum(per) / len(per)
+    tflops = w.flops / (ms_wall * 1e-3) / 1e12
+    kern_tflops = w.flops / (ms_kernel * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[w.dtype]
+
+    elt_qk = {"f32": 4, "bf16": 2, "fp8qk_bf16v": 1}[w.dtype]
+    elt_vo = 4 if w.dtype == "f32" else 2
+    n_el = w.B * w.H * w.N * w.d
+    algo_bytes = n_el * (2 * elt_qk + 2 * elt_vo)
+
+    result = {
+        "metric": "spherical-attention fwd TFLOP/s (4*B*H*N^2*d)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_wall, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"bf16": "bf16", "f32": "f32", "fp8qk_bf16v": "fp8"}[w.dtype], "data": "synthetic",
+        "config": {"workload": w.describe(), "B": w.B, "H": w.H, "N": w.N, "d": w.d,
+                   "flop_per_step": w.flops, "min_hbm_bytes_per_step": algo_bytes},
+        "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": peak, "unit": "TFLOP/s",
+                     "frac": kern_tflops / peak, "traffic": None,
+                     "kernel_ms_avg": ms_kernel, "kernel_ms_median": per[len(per) // 2],
+                     "kernel_ms_min": per[0]},
+    }
+
+    if not args.no_twin and w.dtype == "bf16":
+        def twin():
+            pkg.sphattn_softmax_fwd(qd, kd, vd, out, dtype=w.dtype)
+        _, per_t = time_launches(twin, max(10, args.steps // 4), max(5, args.warmup // 4))
+        ms_t = sum(per_t) / len(per_t)
+        result["softmax_twin"] = {"kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12,
+                                  "spherical_speedup": ms_t / ms_kernel}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, q, k, v)
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,85 @@
+/*
+ * sphattn -- spherical attention forward for AMD MI355X (gfx950), C ABI.
+ *
+ * Spherical attention is attention in which the SoftMax over each score row of
+ * Q K^T is replaced by division by that row's L2 norm (paper, Section 3).  In the
+ * paper's terms it is the normalized contraction of Appendix A.1 (Definition 2)
+ * with a1(x) = x, a2(x) = x^2, b = sqrt, lifted to attention by Theorem 1:
+ *
+ *     s_ij       = sum_k Q[b,h,i,k] * K[b,h,j,k]
+ *     z_i        = sum_j s_ij^2
+ *     O[b,h,i,:] = ( sum_j s_ij * V[b,h,j,:] ) / sqrt(z_i)        (0 if z_i == 0)
+ *
+ * No score scale and no epsilon are applied (any positive scale cancels).  The
+ * library evaluates this by streaming K/V tiles and carrying only the running
+ * pair (o, z) per query row (Lemma 1), never materialising the N x N scores.
+ *
+ * All pointers are DEVICE pointers owned by the caller.  The library allocates
+ * nothing, keeps no state and is re-entrant.  Work is enqueued on `stream`
+ * (a hipStream_t passed as void*; NULL is the default stream) and the call
+ * returns without synchronising.
+ */
+#ifndef SPHATTN_H
+#define SPHATTN_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Storage formats.  Arithmetic is MFMA with fp32 accumulation in every case. */
+typedef enum {
+    SPHATTN_F32 = 0,         /* Q,K,V,O fp32, fp32 matrix-core arithmetic */
+    SPHATTN_BF16 = 1,        /* Q,K,V,O bfloat16 */
+    SPHATTN_FP8QK_BF16V = 2  /* Q,K OCP E4M3 (finite-only) bytes; V,O bfloat16 */
+} sphattn_dtype;
+
+/* Return codes. */
+enum {
+    SPHATTN_OK = 0,
+    SPHATTN_ERR_NULL = -1,        /* a required pointer is NULL */
+    SPHATTN_ERR_SHAPE = -2,       /* B, H or N not positive, or B*H*N*d overflows */
+    SPHATTN_ERR_HEAD_DIM = -3,    /* d is not 64 or 128 */
+    SPHATTN_ERR_DTYPE = -4,       /* dtype is not a sphattn_dtype value */
+    SPHATTN_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned */
+    SPHATTN_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch */
+    SPHATTN_ERR_ALIAS = -7        /* O overlaps Q, K or V */
+};
+
+/*
+ * Spherical attention forward (paper, Section 3; Definition 2 and Lemma 1 of
+ * Appendix A.1; Theorem 1), non-causal self-attention.
+ *
+ *   Q, K, V : [B,H,N,d] dense row-major, d contiguous, in the format `dtype` names.
+ *   O       : [B,H,N,d] dense row-major, written in full; must not overlap Q, K, V.
+ *   B, H, N : positive; N need not be a multiple of any tile size.
+ *   d       : 64 or 128.
+ *   dtype   : a sphattn_dtype value.
+ *   stream  : hipStream_t to enqueue on.
+ *
+ * Returns SPHATTN_OK or a negative SPHATTN_ERR_* code; on error nothing is
+ * enqueued and O is untouched.  Never throws or aborts.
+ */
+int sphattn_fwd(const void* Q, const void* K, const void* V, void* O,
+                int B, int H, int N, int d, int dtype, void* stream);
+
+/*
+ * Comparison twin on the same tiling skeleton: standard SoftMax attention,
+ * O = softmax(Q K^T / sqrt(d)) V, i.e. the same normalized contraction with
+ * a1 = a2 = exp, b = id, computed with the usual running-maximum rescaling.
+ * It exists to measure what the exponential costs (paper, Section 1).
+ * Same arguments, layout, ownership and error behaviour as sphattn_fwd;
+ * dtype must be SPHATTN_BF16.
+ */
+int sphattn_softmax_fwd(const void* Q, const void* K, const void* V, void* O,
+                        int B, int H, int N, int d, int dtype, void* stream);
+
+/* Human-readable text for a return code (static storage, never NULL). */
+const char* sphattn_strerror(int code);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int sphattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPHATTN_H */

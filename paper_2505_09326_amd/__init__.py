@@ -1,0 +1,102 @@
+"""Spherical attention forward for AMD MI355X: thin binding over libsphattn.so.
+
+Every step of the computation runs in the HIP kernels behind the C ABI of
+include/sphattn.h; this module only marshals torch tensors (device memory and
+streams) into that ABI.  There is no fallback: if the library has not been
+built, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from ._build import LIB_PATH, build_library
+
+SPHATTN_F32 = 0
+SPHATTN_BF16 = 1
+SPHATTN_FP8QK_BF16V = 2
+
+_DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN_FP8QK_BF16V}
+
+EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_softmax_fwd", "sphattn_strerror", "sphattn_version")
+
+_lib = None
+
+
+class SphattnError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"sphattn error {code}: {text}")
+        self.code = code
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library; raise if it is missing (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, ip = ctypes.c_void_p, ctypes.c_int
+        for name in ("sphattn_fwd", "sphattn_softmax_fwd"):
+            fn = getattr(lib, name)
+            fn.restype = ip
+            fn.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_strerror.restype = ctypes.c_char_p
+        lib.sphattn_strerror.argtypes = [ip]
+        lib.sphattn_version.restype = ip
+        lib.sphattn_version.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def sphattn_strerror(code: int) -> str:
+    return load_library().sphattn_strerror(int(code)).decode()
+
+
+def sphattn_version() -> int:
+    return int(load_library().sphattn_version())
+
+
+def _dtype_code(dtype) -> int:
+    if isinstance(dtype, str):
+        return _DTYPE_NAMES[dtype]
+    return int(dtype)
+
+
+def _call(fn_name, Q, K, V, O, dtype, stream):
+    import torch
+    lib = load_library()
+    code = _dtype_code(dtype)
+    for t in (Q, K, V, O):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("Q, K, V, O must be contiguous device tensors")
+    B, H, N, d = Q.shape
+    if stream is None:
+        stream = torch.cuda.current_stream(Q.device).cuda_stream
+    rc = getattr(lib, fn_name)(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                               B, H, N, d, code, ctypes.c_void_p(stream))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return O
+
+
+def _alloc_out(Q, V, dtype):
+    import torch
+    code = _dtype_code(dtype)
+    return torch.empty(Q.shape, dtype=torch.float32 if code == SPHATTN_F32 else torch.bfloat16,
+                       device=Q.device)
+
+
+def sphattn_fwd(Q, K, V, O=None, dtype="bf16", stream=None):
+    """O = (Q K^T) V with each score row divided by its L2 norm; tensors are [B,H,N,d]."""
+    if O is None:
+        O = _alloc_out(Q, V, dtype)
+    return _call("sphattn_fwd", Q, K, V, O, dtype, stream)
+
+
+def sphattn_softmax_fwd(Q, K, V, O=None, dtype="bf16", stream=None):
+    """Comparison twin: softmax(Q K^T / sqrt(d)) V on the same tiling."""
+    if O is None:
+        O = _alloc_out(Q, V, dtype)
+    return _call("sphattn_softmax_fwd", Q, K, V, O, dtype, stream)

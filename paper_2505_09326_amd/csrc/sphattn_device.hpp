@@ -1,0 +1,328 @@
+// Device code for spherical attention forward on gfx950 (CDNA4, 64-wide wavefronts).
+//
+// One workgroup = 4 wavefronts = one tile of BR = 4*32*QB query rows of one (b,h).
+// The key axis is streamed in tiles of BC rows (Theorem 1: the query axis is
+// partitioned, the key axis is streamed); the only state carried between key
+// tiles is the pair (o, z) of Lemma 1, held in fp32 registers:
+//
+//     o_i += sum_j s_ij * v_j        z_i += sum_j s_ij^2        tail: O_i = o_i / sqrt(z_i)
+//
+// Matrix-core mapping.  Scores are produced TRANSPOSED, S^T = K Q^T, with
+// v_mfma_f32_32x32x16_bf16 (A = 32 keys x 16, B = 16 x 32 queries).  In the
+// accumulator layout of that instruction lane l owns query column (l & 31) and,
+// in register 4g+t, key row 8g + 4(l>>5) + t.  Eight consecutive accumulator
+// registers are therefore exactly one B operand (8 k-slots of one query column)
+// of the second contraction O^T += V^T P^T, so the scores never leave their
+// registers: they are squared and summed into z in place (plain fp32 FMAs),
+// rounded to bf16 in place, and fed straight back to the matrix cores.  The
+// A operand V^T comes from the row-major V tile in LDS through the transposing
+// read ds_read_b64_tr_b16.  z is a per-lane partial sum; the two lanes that
+// share a query (l and l^32) are combined once, in the tail.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sphattn {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+#define SPH_LDS __attribute__((address_space(3)))
+
+constexpr int kWaves = 4;          // wavefronts per workgroup, one per SIMD
+constexpr int kThreads = 64 * kWaves;
+constexpr int kXcds = 8;           // accelerator complex dies, each with its own L2
+
+// Workgroup ids are dealt round-robin to the 8 XCDs.  Remap so that each XCD
+// works through a contiguous range of (head, query-tile) pairs: the query tiles
+// that run together on one XCD then stream the same K/V through one L2.
+__device__ __forceinline__ int xcd_contiguous_id(int wg, int n_wg)
+{
+    int xcd = wg % kXcds, idx = wg / kXcds;
+    int base = n_wg / kXcds, rem = n_wg % kXcds;
+    int start = xcd * base + (xcd < rem ? xcd : rem);
+    return start + idx;
+}
+
+// 16-byte chunk slot of chunk c in row r of a tile whose rows hold CH chunks.
+// Chosen so that 16 lanes reading one chunk column of 16 consecutive rows
+// (the matrix-core A-operand pattern) touch 16 different 16-byte bank groups.
+template <int CH>
+__device__ __forceinline__ int kswz(int r, int c)
+{
+    if (CH >= 16) return c ^ (r & 15);
+    return c ^ ((r >> 1) & 7);        // CH == 8: two rows share one 256-byte bank line
+}
+
+// V tile swizzle for the transposing read: the 16 lanes of a read block touch
+// 4 consecutive rows x 32 bytes; spread the 4 rows over different 64-byte groups.
+template <int CH>
+__device__ __forceinline__ int vswz(int r, int c)
+{
+    if (CH >= 16) return c ^ ((r & 3) << 2);
+    return c ^ ((r & 1) << 2) ^ ((r >> 1) & 1) * 2;
+}
+
+__device__ __forceinline__ bf16x8 lds_read_b128(const SPH_LDS unsigned char* p)
+{
+    return *reinterpret_cast<const SPH_LDS bf16x8*>(p);
+}
+
+__device__ __forceinline__ bf16x4 lds_read_tr64(const SPH_LDS unsigned char* p)
+{
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (SPH_LDS s16x4*)const_cast<SPH_LDS unsigned char*>(p));
+    return __builtin_bit_cast(bf16x4, v);
+}
+
+__device__ __forceinline__ bf16x2 cvt2(float a, float b)
+{
+    f32x2 v = {a, b};
+    return __builtin_convertvector(v, bf16x2);   // v_cvt_pk_bf16_f32, round to nearest even
+}
+
+enum class Norm { Spherical, Softmax };
+
+// ---------------------------------------------------------------------------
+// bf16 Q/K/V/O kernel.
+//   D   head dimension (64 or 128)
+//   QB  32-query blocks per wavefront (rows per workgroup = 128*QB)
+//   BC  key rows per LDS tile (multiple of 32)
+// LDS: 2 buffers x (K tile + V tile), each BC x D bf16, 16-byte chunks swizzled.
+// ---------------------------------------------------------------------------
+template <int D, int QB, int BC, Norm NORM>
+__global__ __launch_bounds__(kThreads, 1)
+void fwd_bf16_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K,
+                     const __bf16* __restrict__ V, __bf16* __restrict__ O,
+                     int N, int n_qtiles, int n_wg, float softmax_scale_log2)
+{
+    constexpr int BR = kWaves * 32 * QB;
+    constexpr int CH = D * 2 / 16;                 // 16-byte chunks per row
+    constexpr int TILE_BYTES = BC * D * 2;
+    constexpr int CHUNKS = BC * CH;                // per tile
+    constexpr int LD_PER_THREAD = CHUNKS / kThreads;
+    static_assert(CHUNKS % kThreads == 0, "tile must divide over the workgroup");
+    constexpr int KSTEPS = D / 16;                 // MFMA k-steps in Q K^T
+    constexpr int DB = D / 32;                     // 32-wide blocks of the head dimension
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
+    // buffer b: K at b*2*TILE_BYTES, V at b*2*TILE_BYTES + TILE_BYTES
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+
+    const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
+    const int bh = lid / n_qtiles, qt = lid % n_qtiles;
+    const size_t head_off = (size_t)bh * N * D;
+    const __bf16* Qh = Q + head_off;
+    const __bf16* Kh = K + head_off;
+    const __bf16* Vh = V + head_off;
+    __bf16* Oh = O + head_off;
+    const int q0 = qt * BR + wave * 32 * QB;
+
+    // ---- Q fragments: B operands of S^T = K Q^T, held for the whole kernel
+    bf16x8 qf[QB][KSTEPS];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        int row = q0 + qb * 32 + l32;
+        row = row < N ? row : N - 1;               // rows past the end are computed and dropped
+        const __bf16* src = Qh + (size_t)row * D + 8 * h;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk)
+            qf[qb][kk] = *reinterpret_cast<const bf16x8*>(src + kk * 16);
+    }
+
+    f32x16 oacc[DB][QB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
+    float zacc[QB];      // spherical: sum of squares; softmax: running denominator
+    float mrun[QB];      // softmax only: running maximum (in scaled log2 units)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) { zacc[qb] = 0.f; mrun[qb] = -INFINITY; }
+
+    // ---- global -> register -> LDS staging of one K tile and one V tile
+    i32x4 kreg[LD_PER_THREAD], vreg[LD_PER_THREAD];
+    auto load_tile = [&](int j0) {
+#pragma unroll
+        for (int i = 0; i < LD_PER_THREAD; ++i) {
+            int id = tid + i * kThreads;
+            int r = id / CH, c = id % CH;
+            int key = j0 + r;
+            if (key < N) {
+                size_t off = (size_t)key * D + c * 8;
+                kreg[i] = *reinterpret_cast<const i32x4*>(Kh + off);
+                vreg[i] = *reinterpret_cast<const i32x4*>(Vh + off);
+            } else {                               // zero keys add nothing to o or z
+                kreg[i] = i32x4{0, 0, 0, 0};
+                vreg[i] = i32x4{0, 0, 0, 0};
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+        SPH_LDS unsigned char* kb = smem + buf * 2 * TILE_BYTES;
+        SPH_LDS unsigned char* vb = kb + TILE_BYTES;
+#pragma unroll
+        for (int i = 0; i < LD_PER_THREAD; ++i) {
+            int id = tid + i * kThreads;
+            int r = id / CH, c = id % CH;
+            *reinterpret_cast<SPH_LDS i32x4*>(kb + r * (D * 2) + 16 * kswz<CH>(r, c)) = kreg[i];
+            *reinterpret_cast<SPH_LDS i32x4*>(vb + r * (D * 2) + 16 * vswz<CH>(r, c)) = vreg[i];
+        }
+    };
+
+    const int n_tiles = (N + BC - 1) / BC;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int jt = 0; jt < n_tiles; ++jt) {
+        const int buf = jt & 1;
+        const bool more = jt + 1 < n_tiles;
+        if (more) load_tile((jt + 1) * BC);
+
+        const SPH_LDS unsigned char* kb = smem + buf * 2 * TILE_BYTES;
+        const SPH_LDS unsigned char* vb = kb + TILE_BYTES;
+
+#pragma unroll
+        for (int sub = 0; sub < BC / 32; ++sub) {
+            // ---- S^T (32 keys x 32*QB queries) = K_sub Q^T
+            f32x16 s[QB];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[qb][r] = 0.f;
+            const int krow = sub * 32 + l32;
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) {
+                bf16x8 kf = lds_read_b128(kb + krow * (D * 2) + 16 * kswz<CH>(krow, 2 * kk + h));
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], s[qb], 0, 0, 0);
+            }
+
+            // ---- normaliser on the accumulator registers, then round to bf16 in place
+            bf16x8 p[QB][2];
+            if (NORM == Norm::Spherical) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    float z0 = 0.f, z1 = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2) {
+                        z0 = __builtin_fmaf(s[qb][r], s[qb][r], z0);
+                        z1 = __builtin_fmaf(s[qb][r + 1], s[qb][r + 1], z1);
+                    }
+                    zacc[qb] += z0 + z1;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                        for (int e = 0; e < 8; e += 2) {
+                            bf16x2 c2 = cvt2(s[qb][8 * ks + e], s[qb][8 * ks + e + 1]);
+                            p[qb][ks][e] = c2[0];
+                            p[qb][ks][e + 1] = c2[1];
+                        }
+                }
+            } else {
+                // SoftMax twin: running maximum, exponentials, rescale of o.
+                const int key_base = jt * BC + sub * 32 + 4 * h;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        int key = key_base + 8 * (r >> 2) + (r & 3);
+                        float v = s[qb][r] * softmax_scale_log2;
+                        v = key < N ? v : -INFINITY;
+                        s[qb][r] = v;
+                        mx = fmaxf(mx, v);
+                    }
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    float mnew = fmaxf(mrun[qb], mx);
+                    float alpha = __builtin_amdgcn_exp2f(mrun[qb] - mnew);
+                    mrun[qb] = mnew;
+                    float lsum = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        s[qb][r] = __builtin_amdgcn_exp2f(s[qb][r] - mnew);
+                        lsum += s[qb][r];
+                    }
+                    zacc[qb] = zacc[qb] * alpha + lsum;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                        for (int e = 0; e < 8; e += 2) {
+                            bf16x2 c2 = cvt2(s[qb][8 * ks + e], s[qb][8 * ks + e + 1]);
+                            p[qb][ks][e] = c2[0];
+                            p[qb][ks][e + 1] = c2[1];
+                        }
+                }
+            }
+
+            // ---- O^T (D x 32*QB queries) += V_sub^T P^T
+            // k-slot (h, e) of k-step ks is key 16ks + 8(e>>2) + 4h + (e&3): two transposing
+            // reads of 4 keys each.  Within a 16-lane block, lane i supplies the 8-byte piece
+            // row (i>>2), columns 4(i&3)..+3 and receives column i of all 4 rows.
+            const int i16 = lane & 15, blk = (lane >> 4) & 1;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const int colb = (db * 32 + 16 * blk + 4 * (i16 & 3)) * 2;   // byte column
+                    const int r0 = sub * 32 + 16 * ks + 4 * h + (i16 >> 2);
+                    const int r1 = r0 + 8;
+                    bf16x4 lo = lds_read_tr64(vb + r0 * (D * 2) + 16 * vswz<CH>(r0, colb >> 4) + (colb & 15));
+                    bf16x4 hi = lds_read_tr64(vb + r1 * (D * 2) + 16 * vswz<CH>(r1, colb >> 4) + (colb & 15));
+                    bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb)
+                        oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p[qb][ks], oacc[db][qb], 0, 0, 0);
+                }
+            }
+        }
+
+        if (more) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- tail: combine the two partial z of each query, O = o / b(z), store
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        float z = zacc[qb] + __shfl_xor(zacc[qb], 32);
+        float inv;
+        if (NORM == Norm::Spherical)
+            inv = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
+        else
+            inv = 1.0f / z;
+        const int row = q0 + qb * 32 + l32;
+        if (row < N) {
+            __bf16* dst = Oh + (size_t)row * D + 4 * h;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x2 a = cvt2(oacc[db][qb][4 * g] * inv, oacc[db][qb][4 * g + 1] * inv);
+                    bf16x2 b = cvt2(oacc[db][qb][4 * g + 2] * inv, oacc[db][qb][4 * g + 3] * inv);
+                    bf16x4 o4 = {a[0], a[1], b[0], b[1]};
+                    *reinterpret_cast<bf16x4*>(dst + db * 32 + 8 * g) = o4;
+                }
+        }
+    }
+}
+
+}  // namespace sphattn
