@@ -13,6 +13,10 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep hipcc from forming packed-fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # select matrix-core instructions in their VGPR-destination form and let the register
+    # allocator move long-lived accumulators/operands to AGPRs; without it every MFMA result
+    # lands in AGPRs and the score registers must be copied out before the VALU can touch them
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wno-unused-command-line-argument",
 ]
 

@@ -5,6 +5,7 @@
 #include "../../include/sphattn.h"
 
 #include <stdint.h>
+#include <stdlib.h>
 
 namespace {
 
@@ -68,11 +69,49 @@ int launch_bf16(const void* Q, const void* K, const void* V, void* O,
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
+template <int D, int QB>
+int launch_bf16_pipelined(const void* Q, const void* K, const void* V, void* O,
+                          int B, int H, int N, hipStream_t stream)
+{
+    constexpr int BR = kWaves * 32 * QB;
+    constexpr int lds_bytes = 3 * 2 * 64 * D * 2;
+    auto kern = fwd_bf16_pipelined_kernel<D, QB>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                lds_bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return SPHATTN_ERR_LAUNCH;
+        }
+        configured = true;
+    }
+    const int n_qtiles = (N + BR - 1) / BR;
+    const int n_wg = B * H * n_qtiles;
+    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, stream,
+                       (const __bf16*)Q, (const __bf16*)K, (const __bf16*)V, (__bf16*)O,
+                       N, n_qtiles, n_wg);
+    return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
+}
+
+int variant()
+{
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("SPHATTN_VARIANT");
+        v = e ? atoi(e) : 1;
+    }
+    return v;
+}
+
 template <Norm NORM>
 int dispatch(const void* Q, const void* K, const void* V, void* O,
              int B, int H, int N, int d, int dtype, hipStream_t stream)
 {
     if (dtype == SPHATTN_BF16) {
+        if (NORM == Norm::Spherical && variant() == 1) {
+            if (d == 128) return launch_bf16_pipelined<128, 2>(Q, K, V, O, B, H, N, stream);
+            return launch_bf16_pipelined<64, 2>(Q, K, V, O, B, H, N, stream);
+        }
         if (d == 128) return launch_bf16<128, 2, 64, NORM>(Q, K, V, O, B, H, N, stream);
         return launch_bf16<64, 2, 64, NORM>(Q, K, V, O, B, H, N, stream);
     }

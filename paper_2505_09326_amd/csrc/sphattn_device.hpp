@@ -325,4 +325,281 @@ void fwd_bf16_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K,
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Software-pipelined bf16 kernel (spherical normaliser only).
+//
+// The key axis advances in sub-steps of 32 keys.  Three stages of three
+// consecutive sub-steps are in flight at once in every wavefront, so that the
+// matrix pipe, the vector ALU and the LDS all stay busy with one wave per SIMD:
+//     A(t+1)  S^T = K Q^T            matrix cores -> score registers (next)
+//     B(t)    z += s^2, P = bf16(s)  plain fp32 VALU on score registers (current)
+//     C(t-1)  O^T += V^T P^T         matrix cores <- P registers (previous)
+// K/V tiles of BC = 64 keys rotate through three LDS buffers (tile j being read
+// for A, tile j-1 for C, tile j+1 being written), with one workgroup barrier per
+// tile.  Global loads go through buffer descriptors whose range check returns
+// zeros past the end of the head: a zero key contributes nothing to o or z, so
+// ragged N needs no masking.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+
+template <int D, int QB>
+__global__ __launch_bounds__(kThreads, 1)
+void fwd_bf16_pipelined_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K,
+                               const __bf16* __restrict__ V, __bf16* __restrict__ O,
+                               int N, int n_qtiles, int n_wg)
+{
+    constexpr int BC = 64;
+    constexpr int BR = kWaves * 32 * QB;
+    constexpr int ROWB = D * 2;                    // bytes per tile row
+    constexpr int CH = ROWB / 16;
+    constexpr int TILE_BYTES = BC * ROWB;          // one K or V tile
+    constexpr int BUF_BYTES = 2 * TILE_BYTES;      // K tile then V tile
+    constexpr int NBUF = 3;
+    constexpr int CHUNKS = BC * CH;
+    constexpr int LD = CHUNKS / kThreads;          // 16-byte loads per thread per tensor per tile
+    constexpr int KSTEPS = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int NFRAG = 2 * DB;                  // V^T fragments per sub-step (2 k-steps x DB)
+    static_assert(CH == 16 || CH == 8, "head dimension 128 or 64");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int i16 = lane & 15, blk = (lane >> 4) & 1;
+
+    const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
+    const int bh = lid / n_qtiles, qt = lid % n_qtiles;
+    const size_t head_off = (size_t)bh * N * D;
+    const __bf16* Qh = Q + head_off;
+    __bf16* Oh = O + head_off;
+    const uint32_t head_bytes = (uint32_t)N * ROWB;
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(K + head_off, head_bytes);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(V + head_off, head_bytes);
+    const int q0 = qt * BR + wave * 32 * QB;
+
+    // ---- per-lane LDS byte offsets inside a tile
+    // K fragment (sub, kk): row sub*32 + l32, chunk (2kk+h) ^ swizzle(row)
+    int koff[KSTEPS];
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk)
+        koff[kk] = l32 * ROWB + 16 * kswz<CH>(l32, 2 * kk + h);
+    // V fragment (sub, ks, db): rows sub*32 + 16ks + 4h + (i16>>2) [+8], 8 bytes at column
+    // db*32 + 16*blk + 4*(i16&3)
+    int voff[DB];
+    {
+        const int r = 4 * h + (i16 >> 2);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int colb = (db * 32 + 16 * blk + 4 * (i16 & 3)) * 2;
+            voff[db] = r * ROWB + 16 * vswz<CH>(r, colb >> 4) + (colb & 15);
+        }
+    }
+    // staging: chunk id = tid + i*256 -> row id/CH, chunk id%CH
+    int st_k[LD], st_v[LD], ld_off[LD];
+#pragma unroll
+    for (int i = 0; i < LD; ++i) {
+        const int id = tid + i * kThreads;
+        const int r = id / CH, c = id % CH;
+        st_k[i] = r * ROWB + 16 * kswz<CH>(r, c);
+        st_v[i] = TILE_BYTES + r * ROWB + 16 * vswz<CH>(r, c);
+        ld_off[i] = r * ROWB + c * 16;
+    }
+
+    // ---- Q fragments (B operands of S^T = K Q^T)
+    bf16x8 qf[QB][KSTEPS];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        int row = q0 + qb * 32 + l32;
+        row = row < N ? row : N - 1;
+        const __bf16* src = Qh + (size_t)row * D + 8 * h;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk)
+            qf[qb][kk] = *reinterpret_cast<const bf16x8*>(src + kk * 16);
+    }
+
+    f32x16 oacc[DB][QB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
+    float zacc[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) zacc[qb] = 0.f;
+
+    i32x4 kreg[LD], vreg[LD];
+    auto gload = [&](int tile) {
+        const uint32_t base = (uint32_t)tile * TILE_BYTES;   // byte offset of the tile in the head
+#pragma unroll
+        for (int i = 0; i < LD; ++i) {
+            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, base + ld_off[i], 0, 0);
+            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, base + ld_off[i], 0, 0);
+        }
+    };
+    auto lstore = [&](int buf) {
+        SPH_LDS unsigned char* b = smem + buf * BUF_BYTES;
+#pragma unroll
+        for (int i = 0; i < LD; ++i) {
+            *reinterpret_cast<SPH_LDS i32x4*>(b + st_k[i]) = kreg[i];
+            *reinterpret_cast<SPH_LDS i32x4*>(b + st_v[i]) = vreg[i];
+        }
+    };
+
+    // One pipelined half-step.  kb: K tile for stage A (sub-step ksub of it), vb: V tile for
+    // stage C (sub-step vsub).  Sn <- A, (Sc -> Pc, z) = B, O += C(Pp).
+    auto half = [&](f32x16 (&Sn)[QB], f32x16 (&Sc)[QB], bf16x8 (&Pc)[QB][2], bf16x8 (&Pp)[QB][2],
+                    const SPH_LDS unsigned char* kb, int ksub,
+                    const SPH_LDS unsigned char* vb, int vsub) {
+        const SPH_LDS unsigned char* kp = kb + ksub * 32 * ROWB;
+        const SPH_LDS unsigned char* vp = vb + vsub * 32 * ROWB;
+        constexpr int SLOTS = KSTEPS > NFRAG ? KSTEPS : NFRAG;   // both are 8 (D=128) or 4 (D=64)
+        static_assert(KSTEPS == NFRAG, "slot plan assumes equal counts");
+        bf16x8 kf[SLOTS], vf[SLOTS];
+        auto read_k = [&](int i) { kf[i] = lds_read_b128(kp + koff[i]); };
+        auto read_v = [&](int i) {
+            const int ks = i / DB, db = i % DB;
+            const SPH_LDS unsigned char* a = vp + (16 * ks) * ROWB + voff[db];
+            bf16x4 lo = lds_read_tr64(a);
+            bf16x4 hi = lds_read_tr64(a + 8 * ROWB);
+            vf[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        };
+        float z[QB][2];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) z[qb][0] = z[qb][1] = 0.f;
+
+        read_v(0);
+        read_k(0);
+        if (SLOTS > 1) { read_v(1); read_k(1); }
+#pragma unroll
+        for (int i = 0; i < SLOTS; ++i) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + 2 < SLOTS) { read_v(i + 2); read_k(i + 2); }
+            // C: fragment i of V^T against the previous sub-step's P
+            {
+                const int ks = i / DB, db = i % DB;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], Pp[qb][ks], oacc[db][qb], 0, 0, 0);
+            }
+            // A: k-step i of the next sub-step's scores
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                if (i == 0) {
+                    f32x16 zero = {0};
+                    Sn[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[qb][i], zero, 0, 0, 0);
+                } else {
+                    Sn[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[qb][i], Sn[qb], 0, 0, 0);
+                }
+            }
+            // B: a slice of the current sub-step's scores: 16*QB/SLOTS registers per slot
+            constexpr int PER = 16 * QB / SLOTS;
+#pragma unroll
+            for (int u = 0; u < PER; u += 2) {
+                const int idx = i * PER + u;          // 0 .. 16*QB-1
+                const int qb = idx / 16, r = idx % 16;
+                const float a = Sc[qb][r], b = Sc[qb][r + 1];
+                z[qb][0] = __builtin_fmaf(a, a, z[qb][0]);
+                z[qb][1] = __builtin_fmaf(b, b, z[qb][1]);
+                bf16x2 c2 = cvt2(a, b);
+                Pc[qb][r / 8][r % 8] = c2[0];
+                Pc[qb][r / 8][r % 8 + 1] = c2[1];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) zacc[qb] += z[qb][0] + z[qb][1];
+    };
+
+    const int n_tiles = (N + BC - 1) / BC;
+
+    // ---- prologue: zero buffer 2 (it plays "tile -1" for the first stage C), tile 0 -> buffer 0
+    {
+        const i32x4 zero4 = {0, 0, 0, 0};
+        for (int i = tid; i < BUF_BYTES / 16; i += kThreads)
+            *reinterpret_cast<SPH_LDS i32x4*>(smem + 2 * BUF_BYTES + i * 16) = zero4;
+    }
+    gload(0);
+    lstore(0);
+    gload(1);
+    __syncthreads();
+
+    f32x16 S0[QB], S1[QB];
+    bf16x8 P0[QB][2], P1[QB][2];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { S0[qb][r] = 0.f; S1[qb][r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { P0[qb][ks][e] = (__bf16)0.f; P1[qb][ks][e] = (__bf16)0.f; }
+    }
+    // S0 = scores of sub-step 0
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        bf16x8 kf = lds_read_b128(smem + koff[kk]);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+            S0[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], S0[qb], 0, 0, 0);
+    }
+
+    int cur = 0, prv = 2, nxt = 1;        // LDS buffers of tiles j, j-1, j+1
+    for (int j = 0; j < n_tiles; ++j) {
+        const SPH_LDS unsigned char* bcur = smem + cur * BUF_BYTES;
+        const SPH_LDS unsigned char* bprv = smem + prv * BUF_BYTES;
+        const SPH_LDS unsigned char* bnxt = smem + nxt * BUF_BYTES;
+        // first half: A on K_j sub 1, B on S0, C on V_{j-1} sub 1; tile j+1 goes to LDS
+        half(S1, S0, P0, P1, bcur, 1, bprv + TILE_BYTES, 1);
+        lstore(nxt);
+        __syncthreads();
+        // second half: A on K_{j+1} sub 0, B on S1, C on V_j sub 0; tile j+2 leaves HBM/L2
+        gload(j + 2);
+        half(S0, S1, P1, P0, bnxt, 0, bcur + TILE_BYTES, 0);
+        const int t = prv; prv = cur; cur = nxt; nxt = t;
+    }
+    // ---- drain: stage C of the last sub-step (V of the last tile, sub 1, now in `prv`)
+    {
+        const SPH_LDS unsigned char* vp = smem + prv * BUF_BYTES + TILE_BYTES + 32 * ROWB;
+#pragma unroll
+        for (int i = 0; i < NFRAG; ++i) {
+            const int ks = i / DB, db = i % DB;
+            const SPH_LDS unsigned char* a = vp + (16 * ks) * ROWB + voff[db];
+            bf16x4 lo = lds_read_tr64(a);
+            bf16x4 hi = lds_read_tr64(a + 8 * ROWB);
+            bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+                oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, P1[qb][ks], oacc[db][qb], 0, 0, 0);
+        }
+    }
+
+    // ---- tail: O = o / sqrt(z)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float z = zacc[qb] + __shfl_xor(zacc[qb], 32);
+        const float inv = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
+        const int row = q0 + qb * 32 + l32;
+        if (row < N) {
+            __bf16* dst = Oh + (size_t)row * D + 4 * h;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x2 a = cvt2(oacc[db][qb][4 * g] * inv, oacc[db][qb][4 * g + 1] * inv);
+                    bf16x2 b = cvt2(oacc[db][qb][4 * g + 2] * inv, oacc[db][qb][4 * g + 3] * inv);
+                    bf16x4 o4 = {a[0], a[1], b[0], b[1]};
+                    *reinterpret_cast<bf16x4*>(dst + db * 32 + 8 * g) = o4;
+                }
+        }
+    }
+}
+
 }  // namespace sphattn
