@@ -74,7 +74,7 @@ int launch_bf16_pipelined(const void* Q, const void* K, const void* V, void* O,
                           int B, int H, int N, hipStream_t stream)
 {
     constexpr int BR = kWaves * 32 * QB;
-    constexpr int lds_bytes = 3 * 2 * 64 * D * 2;
+    constexpr int lds_bytes = 4 * 2 * 64 * D * 2;
     auto kern = fwd_bf16_pipelined_kernel<D, QB>;
     static bool configured = false;
     if (!configured) {

@@ -335,11 +335,13 @@ void fwd_bf16_kernel(const __bf16* __restrict__ Q, const __bf16* __restrict__ K,
 //     A(t+1)  S^T = K Q^T            matrix cores -> score registers (next)
 //     B(t)    z += s^2, P = bf16(s)  plain fp32 VALU on score registers (current)
 //     C(t-1)  O^T += V^T P^T         matrix cores <- P registers (previous)
-// K/V tiles of BC = 64 keys rotate through three LDS buffers (tile j being read
-// for A, tile j-1 for C, tile j+1 being written), with one workgroup barrier per
-// tile.  Global loads go through buffer descriptors whose range check returns
-// zeros past the end of the head: a zero key contributes nothing to o or z, so
-// ragged N needs no masking.
+// A sub-step is cut into SLOTS slots (one K fragment + one V^T fragment each);
+// LDS fragment reads run PD slots ahead of their use, across sub-step and tile
+// boundaries.  K/V tiles of BC = 64 keys rotate through four LDS buffers: in
+// iteration j tile j and j+1 feed stage A, tiles j-1 and j feed stage C, and
+// tile j+2 is written, with one workgroup barrier per tile.  Global loads go
+// through buffer descriptors whose range check returns zeros past the end of the
+// head: a zero key contributes nothing to o or z, so ragged N needs no masking.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes)
 {
@@ -358,16 +360,25 @@ void fwd_bf16_pipelined_kernel(const __bf16* __restrict__ Q, const __bf16* __res
     constexpr int CH = ROWB / 16;
     constexpr int TILE_BYTES = BC * ROWB;          // one K or V tile
     constexpr int BUF_BYTES = 2 * TILE_BYTES;      // K tile then V tile
-    constexpr int NBUF = 3;
+    constexpr int NBUF = 4;
     constexpr int CHUNKS = BC * CH;
     constexpr int LD = CHUNKS / kThreads;          // 16-byte loads per thread per tensor per tile
     constexpr int KSTEPS = D / 16;
     constexpr int DB = D / 32;
-    constexpr int NFRAG = 2 * DB;                  // V^T fragments per sub-step (2 k-steps x DB)
+    constexpr int SLOTS = KSTEPS;                  // slots per sub-step
+    constexpr int PD = 2;                          // LDS prefetch distance in slots
+    constexpr int RING = 4;                        // fragment registers in rotation
+    constexpr int VALU_PER_MFMA = 3;
     static_assert(CH == 16 || CH == 8, "head dimension 128 or 64");
+    static_assert(2 * DB == SLOTS, "one V^T fragment per slot");
+    static_assert(2 * LD == SLOTS, "one staged chunk per slot of the second half");
+    static_assert((2 * SLOTS) % RING == 0 && PD < RING, "ring indices must repeat every iteration");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
+#ifdef SPHATTN_CLOCK_PROBE
+    const long long probe_t0 = clock64(), probe_w0 = wall_clock64();
+#endif
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -390,7 +401,7 @@ void fwd_bf16_pipelined_kernel(const __bf16* __restrict__ Q, const __bf16* __res
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk)
         koff[kk] = l32 * ROWB + 16 * kswz<CH>(l32, 2 * kk + h);
-    // V fragment (sub, ks, db): rows sub*32 + 16ks + 4h + (i16>>2) [+8], 8 bytes at column
+    // V^T fragment (sub, ks, db): rows sub*32 + 16ks + 4h + (i16>>2) [+8], 8 bytes at column
     // db*32 + 16*blk + 4*(i16&3)
     int voff[DB];
     {
@@ -401,14 +412,14 @@ void fwd_bf16_pipelined_kernel(const __bf16* __restrict__ Q, const __bf16* __res
             voff[db] = r * ROWB + 16 * vswz<CH>(r, colb >> 4) + (colb & 15);
         }
     }
-    // staging: chunk id = tid + i*256 -> row id/CH, chunk id%CH
-    int st_k[LD], st_v[LD], ld_off[LD];
+    // staging: chunk id = tid + i*256 -> row id/CH, chunk id%CH; chunks 0..LD-1 are K, LD..2LD-1 V
+    int st_off[2 * LD], ld_off[LD];
 #pragma unroll
     for (int i = 0; i < LD; ++i) {
         const int id = tid + i * kThreads;
         const int r = id / CH, c = id % CH;
-        st_k[i] = r * ROWB + 16 * kswz<CH>(r, c);
-        st_v[i] = TILE_BYTES + r * ROWB + 16 * vswz<CH>(r, c);
+        st_off[i] = r * ROWB + 16 * kswz<CH>(r, c);
+        st_off[LD + i] = TILE_BYTES + r * ROWB + 16 * vswz<CH>(r, c);
         ld_off[i] = r * ROWB + c * 16;
     }
 
@@ -431,104 +442,38 @@ void fwd_bf16_pipelined_kernel(const __bf16* __restrict__ Q, const __bf16* __res
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
-    float zacc[QB];
+    float zacc[QB][2];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) zacc[qb] = 0.f;
+    for (int qb = 0; qb < QB; ++qb) zacc[qb][0] = zacc[qb][1] = 0.f;
 
-    i32x4 kreg[LD], vreg[LD];
-    auto gload = [&](int tile) {
-        const uint32_t base = (uint32_t)tile * TILE_BYTES;   // byte offset of the tile in the head
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, base + ld_off[i], 0, 0);
-            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, base + ld_off[i], 0, 0);
-        }
+    i32x4 stage[2 * LD];
+    auto gload_chunk = [&](int c, int tile) {
+        const uint32_t off = (uint32_t)tile * TILE_BYTES + ld_off[c % LD];
+        stage[c] = __builtin_amdgcn_raw_buffer_load_b128(c < LD ? krs : vrs, off, 0, 0);
     };
-    auto lstore = [&](int buf) {
-        SPH_LDS unsigned char* b = smem + buf * BUF_BYTES;
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            *reinterpret_cast<SPH_LDS i32x4*>(b + st_k[i]) = kreg[i];
-            *reinterpret_cast<SPH_LDS i32x4*>(b + st_v[i]) = vreg[i];
-        }
-    };
-
-    // One pipelined half-step.  kb: K tile for stage A (sub-step ksub of it), vb: V tile for
-    // stage C (sub-step vsub).  Sn <- A, (Sc -> Pc, z) = B, O += C(Pp).
-    auto half = [&](f32x16 (&Sn)[QB], f32x16 (&Sc)[QB], bf16x8 (&Pc)[QB][2], bf16x8 (&Pp)[QB][2],
-                    const SPH_LDS unsigned char* kb, int ksub,
-                    const SPH_LDS unsigned char* vb, int vsub) {
-        const SPH_LDS unsigned char* kp = kb + ksub * 32 * ROWB;
-        const SPH_LDS unsigned char* vp = vb + vsub * 32 * ROWB;
-        constexpr int SLOTS = KSTEPS > NFRAG ? KSTEPS : NFRAG;   // both are 8 (D=128) or 4 (D=64)
-        static_assert(KSTEPS == NFRAG, "slot plan assumes equal counts");
-        bf16x8 kf[SLOTS], vf[SLOTS];
-        auto read_k = [&](int i) { kf[i] = lds_read_b128(kp + koff[i]); };
-        auto read_v = [&](int i) {
-            const int ks = i / DB, db = i % DB;
-            const SPH_LDS unsigned char* a = vp + (16 * ks) * ROWB + voff[db];
-            bf16x4 lo = lds_read_tr64(a);
-            bf16x4 hi = lds_read_tr64(a + 8 * ROWB);
-            vf[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        };
-        float z[QB][2];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) z[qb][0] = z[qb][1] = 0.f;
-
-        read_v(0);
-        read_k(0);
-        if (SLOTS > 1) { read_v(1); read_k(1); }
-#pragma unroll
-        for (int i = 0; i < SLOTS; ++i) {
-            __builtin_amdgcn_sched_barrier(0);
-            if (i + 2 < SLOTS) { read_v(i + 2); read_k(i + 2); }
-            // C: fragment i of V^T against the previous sub-step's P
-            {
-                const int ks = i / DB, db = i % DB;
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], Pp[qb][ks], oacc[db][qb], 0, 0, 0);
-            }
-            // A: k-step i of the next sub-step's scores
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                if (i == 0) {
-                    f32x16 zero = {0};
-                    Sn[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[qb][i], zero, 0, 0, 0);
-                } else {
-                    Sn[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[qb][i], Sn[qb], 0, 0, 0);
-                }
-            }
-            // B: a slice of the current sub-step's scores: 16*QB/SLOTS registers per slot
-            constexpr int PER = 16 * QB / SLOTS;
-#pragma unroll
-            for (int u = 0; u < PER; u += 2) {
-                const int idx = i * PER + u;          // 0 .. 16*QB-1
-                const int qb = idx / 16, r = idx % 16;
-                const float a = Sc[qb][r], b = Sc[qb][r + 1];
-                z[qb][0] = __builtin_fmaf(a, a, z[qb][0]);
-                z[qb][1] = __builtin_fmaf(b, b, z[qb][1]);
-                bf16x2 c2 = cvt2(a, b);
-                Pc[qb][r / 8][r % 8] = c2[0];
-                Pc[qb][r / 8][r % 8 + 1] = c2[1];
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) zacc[qb] += z[qb][0] + z[qb][1];
+    auto lstore_chunk = [&](int c, SPH_LDS unsigned char* buf) {
+        *reinterpret_cast<SPH_LDS i32x4*>(buf + st_off[c]) = stage[c];
     };
 
     const int n_tiles = (N + BC - 1) / BC;
 
-    // ---- prologue: zero buffer 2 (it plays "tile -1" for the first stage C), tile 0 -> buffer 0
+    // ---- prologue: buffer 3 plays "tile -1" (zeros) for the first stage C; tiles 0 and 1 go
+    // to buffers 0 and 1; tile 2 waits in registers
     {
         const i32x4 zero4 = {0, 0, 0, 0};
         for (int i = tid; i < BUF_BYTES / 16; i += kThreads)
-            *reinterpret_cast<SPH_LDS i32x4*>(smem + 2 * BUF_BYTES + i * 16) = zero4;
+            *reinterpret_cast<SPH_LDS i32x4*>(smem + 3 * BUF_BYTES + i * 16) = zero4;
     }
-    gload(0);
-    lstore(0);
-    gload(1);
+#pragma unroll
+    for (int c = 0; c < 2 * LD; ++c) gload_chunk(c, 0);
+#pragma unroll
+    for (int c = 0; c < 2 * LD; ++c) lstore_chunk(c, smem);
+#pragma unroll
+    for (int c = 0; c < 2 * LD; ++c) gload_chunk(c, 1);
+#pragma unroll
+    for (int c = 0; c < 2 * LD; ++c) lstore_chunk(c, smem + BUF_BYTES);
+#pragma unroll
+    for (int c = 0; c < 2 * LD; ++c) gload_chunk(c, 2);
     __syncthreads();
 
     f32x16 S0[QB], S1[QB];
@@ -545,46 +490,142 @@ void fwd_bf16_pipelined_kernel(const __bf16* __restrict__ Q, const __bf16* __res
     // S0 = scores of sub-step 0
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
-        bf16x8 kf = lds_read_b128(smem + koff[kk]);
+        bf16x8 kfr = lds_read_b128(smem + koff[kk]);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
-            S0[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], S0[qb], 0, 0, 0);
+            S0[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, qf[qb][kk], S0[qb], 0, 0, 0);
     }
 
-    int cur = 0, prv = 2, nxt = 1;        // LDS buffers of tiles j, j-1, j+1
-    for (int j = 0; j < n_tiles; ++j) {
-        const SPH_LDS unsigned char* bcur = smem + cur * BUF_BYTES;
-        const SPH_LDS unsigned char* bprv = smem + prv * BUF_BYTES;
-        const SPH_LDS unsigned char* bnxt = smem + nxt * BUF_BYTES;
-        // first half: A on K_j sub 1, B on S0, C on V_{j-1} sub 1; tile j+1 goes to LDS
-        half(S1, S0, P0, P1, bcur, 1, bprv + TILE_BYTES, 1);
-        lstore(nxt);
-        __syncthreads();
-        // second half: A on K_{j+1} sub 0, B on S1, C on V_j sub 0; tile j+2 leaves HBM/L2
-        gload(j + 2);
-        half(S0, S1, P1, P0, bnxt, 0, bcur + TILE_BYTES, 0);
-        const int t = prv; prv = cur; cur = nxt; nxt = t;
-    }
-    // ---- drain: stage C of the last sub-step (V of the last tile, sub 1, now in `prv`)
-    {
-        const SPH_LDS unsigned char* vp = smem + prv * BUF_BYTES + TILE_BYTES + 32 * ROWB;
+    bf16x8 kf[RING], vf[RING];
+    // Fragment reads for slot u of an iteration whose tiles j-1, j, j+1 sit at bprv, bcur, bnxt:
+    //   u in [0,SLOTS)        first half : K_j sub 1,     V_{j-1} sub 1
+    //   u in [SLOTS,2SLOTS)   second half: K_{j+1} sub 0, V_j sub 0
+    //   u >= 2SLOTS           next iteration's first half: K_{j+1} sub 1, V_j sub 1
+    auto issue_reads = [&](int u, const SPH_LDS unsigned char* bprv, const SPH_LDS unsigned char* bcur,
+                           const SPH_LDS unsigned char* bnxt) {
+        const int hh = u / SLOTS, i = u % SLOTS;
+        const SPH_LDS unsigned char* kp = hh == 0 ? bcur + 32 * ROWB : hh == 1 ? bnxt : bnxt + 32 * ROWB;
+        const SPH_LDS unsigned char* vp = (hh == 0 ? bprv + 32 * ROWB : hh == 1 ? bcur : bcur + 32 * ROWB) + TILE_BYTES;
+        kf[u % RING] = lds_read_b128(kp + koff[i]);
+        const int ks = i / DB, db = i % DB;
+        const SPH_LDS unsigned char* a = vp + (16 * ks) * ROWB + voff[db];
+        bf16x4 lo = lds_read_tr64(a);
+        bf16x4 hi = lds_read_tr64(a + 8 * ROWB);
+        vf[u % RING] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    // buffers of tiles j-1, j, j+1, j+2
+    SPH_LDS unsigned char* bprv = smem + 3 * BUF_BYTES;
+    SPH_LDS unsigned char* bcur = smem;
+    SPH_LDS unsigned char* bnxt = smem + BUF_BYTES;
+    SPH_LDS unsigned char* bnn = smem + 2 * BUF_BYTES;
 #pragma unroll
-        for (int i = 0; i < NFRAG; ++i) {
+    for (int u = 0; u < PD; ++u) issue_reads(u, bprv, bcur, bnxt);
+
+    for (int j = 0; j < n_tiles; ++j) {
+#pragma unroll
+        for (int s = 0; s < 2 * SLOTS; ++s) {
+            const int hf = s / SLOTS, i = s % SLOTS;
+            f32x16 (&Sn)[QB] = hf == 0 ? S1 : S0;
+            f32x16 (&Sc)[QB] = hf == 0 ? S0 : S1;
+            bf16x8 (&Pc)[QB][2] = hf == 0 ? P0 : P1;
+            bf16x8 (&Pp)[QB][2] = hf == 0 ? P1 : P0;
+            __builtin_amdgcn_sched_barrier(0);
+            // The one barrier per tile: everything written to LDS in the previous iteration
+            // (tile j+1) becomes visible before its first read, which is the prefetch below;
+            // and every wave has finished the previous iteration, whose first half was the
+            // last reader of the buffer that this iteration's second half overwrites.
+            if (s == SLOTS - PD) {
+                // LDS operations complete in issue order.  At most OUT of them have been issued
+                // since this wave's last staging write of the previous iteration, so once no
+                // more than OUT are outstanding that write has landed.  No full drain: the
+                // fragment reads already in flight keep flying across the barrier.
+                constexpr int OUT = 3 * (SLOTS - PD) < 15 ? 3 * (SLOTS - PD) : 15;
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0xC07F | (OUT << 8));
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
+            issue_reads(s + PD, bprv, bcur, bnxt);
+            // A: k-step i of the next sub-step's scores
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                if (i == 0) {
+                    f32x16 zero = {0};
+                    Sn[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s % RING], qf[qb][i], zero, 0, 0, 0);
+                } else {
+                    Sn[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s % RING], qf[qb][i], Sn[qb], 0, 0, 0);
+                }
+            }
+            // C: V^T fragment i against the previous sub-step's P
+            {
+                const int ks = i / DB, db = i % DB;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s % RING], Pp[qb][ks], oacc[db][qb], 0, 0, 0);
+            }
+            // B: a slice of the current sub-step's scores, 16*QB/SLOTS registers per slot
+            constexpr int PER = 16 * QB / SLOTS;
+#pragma unroll
+            for (int u = 0; u < PER; u += 2) {
+                const int idx = i * PER + u;
+                const int qb = idx / 16, r = idx % 16;
+                const float a = Sc[qb][r], b = Sc[qb][r + 1];
+                zacc[qb][0] = __builtin_fmaf(a, a, zacc[qb][0]);
+                zacc[qb][1] = __builtin_fmaf(b, b, zacc[qb][1]);
+                bf16x2 c2 = cvt2(a, b);
+                Pc[qb][r / 8][r % 8] = c2[0];
+                Pc[qb][r / 8][r % 8 + 1] = c2[1];
+            }
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)     // keep the running sums where they were computed
+                asm volatile("" : "+v"(zacc[qb][0]), "+v"(zacc[qb][1]));
+            // staging, second half only: tile j+2 into LDS, tile j+3 out of HBM/L2
+            if (hf == 1) {
+                lstore_chunk(i, bnn);
+                gload_chunk(i, j + 3);
+            }
+            // issue order inside the slot: after each matrix instruction, one LDS read and a
+            // few VALU instructions, so that the matrix pipe never waits on the issue port
+#pragma unroll
+            for (int m = 0; m < 2 * QB; ++m) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+                __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);   // VALU
+                if (hf == 1 && m == 2) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
+                if (hf == 1 && m == 3) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
+            }
+        }
+        SPH_LDS unsigned char* t = bprv; bprv = bcur; bcur = bnxt; bnxt = bnn; bnn = t;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- drain: stage C of the last sub-step (V of the last tile, sub 1, now at bprv)
+    {
+        const SPH_LDS unsigned char* vp = bprv + TILE_BYTES + 32 * ROWB;
+#pragma unroll
+        for (int i = 0; i < SLOTS; ++i) {
             const int ks = i / DB, db = i % DB;
             const SPH_LDS unsigned char* a = vp + (16 * ks) * ROWB + voff[db];
             bf16x4 lo = lds_read_tr64(a);
             bf16x4 hi = lds_read_tr64(a + 8 * ROWB);
-            bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            bf16x8 vfr = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
-                oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, P1[qb][ks], oacc[db][qb], 0, 0, 0);
+                oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr, P1[qb][ks], oacc[db][qb], 0, 0, 0);
         }
     }
 
+#ifdef SPHATTN_CLOCK_PROBE
+    if (tid == 0 && blockIdx.x == 0 && bh == 0)
+        printf("clock probe: %lld shader clocks, %lld x10ns, %d tiles\n", clock64() - probe_t0,
+               wall_clock64() - probe_w0, n_tiles);
+#endif
     // ---- tail: O = o / sqrt(z)
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float z = zacc[qb] + __shfl_xor(zacc[qb], 32);
+        const float zl = zacc[qb][0] + zacc[qb][1];
+        const float z = zl + __shfl_xor(zl, 32);
         const float inv = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
         const int row = q0 + qb * 32 + l32;
         if (row < N) {
