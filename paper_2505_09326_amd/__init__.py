@@ -33,10 +33,11 @@ def load_library() -> ctypes.CDLL:
     """Load the built library; raise if it is missing (no CPU fallback exists)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        path = os.environ.get("SPHATTN_LIBRARY", LIB_PATH)   # another build of the same library
+        if not os.path.exists(path):
             raise ImportError(
-                f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
-        lib = ctypes.CDLL(LIB_PATH)
+                f"{path} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(path)
         vp, ip = ctypes.c_void_p, ctypes.c_int
         for name in ("sphattn_fwd", "sphattn_softmax_fwd"):
             fn = getattr(lib, name)

@@ -5,7 +5,6 @@
 #include "../../include/sphattn.h"
 
 #include <stdint.h>
-#include <stdlib.h>
 
 namespace {
 
@@ -32,6 +31,8 @@ int check_args(const void* Q, const void* K, const void* V, void* O,
     if (elems > ((unsigned __int128)1 << 40)) return SPHATTN_ERR_SHAPE;
     if ((unsigned __int128)B * H * (((unsigned __int128)N + 127) / 128) > 0x7fffffff)
         return SPHATTN_ERR_SHAPE;
+    // one head of one tensor is addressed through a 32-bit buffer range
+    if ((unsigned __int128)N * d * 4 > 0x7fffffff) return SPHATTN_ERR_SHAPE;
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return SPHATTN_ERR_ALIGN;
     size_t n = (size_t)elems;
     size_t qk = dtype == SPHATTN_F32 ? 4 : dtype == SPHATTN_BF16 ? 2 : 1;
@@ -44,63 +45,50 @@ int check_args(const void* Q, const void* K, const void* V, void* O,
     return SPHATTN_OK;
 }
 
-template <int D, int QB, int BC, Norm NORM>
-int launch_bf16(const void* Q, const void* K, const void* V, void* O,
-                int B, int H, int N, hipStream_t stream)
+template <typename Kern>
+bool raise_lds_limit(Kern kern, int lds_bytes)
+{
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            lds_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return true;
+}
+
+template <int D, int QB, QKType QKT, Norm NORM>
+int launch_pipelined(const void* Q, const void* K, const void* V, void* O,
+                     int B, int H, int N, hipStream_t stream)
 {
     constexpr int BR = kWaves * 32 * QB;
-    constexpr int lds_bytes = 4 * BC * D * 2;
-    auto kern = fwd_bf16_kernel<D, QB, BC, NORM>;
-    static bool configured = false;          // raising the LDS limit is idempotent
-    if (!configured) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                lds_bytes) != hipSuccess) {
-            (void)hipGetLastError();
-            return SPHATTN_ERR_LAUNCH;
-        }
-        configured = true;
-    }
+    constexpr int EQ = QKT == QKType::Fp8 ? 1 : 2;
+    constexpr int lds_bytes = kNBuf * kBC * D * (EQ + 2);
+    auto kern = fwd_pipelined_kernel<D, QB, QKT, NORM>;
+    static const bool configured = raise_lds_limit(kern, lds_bytes);   // once per process
+    if (!configured) return SPHATTN_ERR_LAUNCH;
     const int n_qtiles = (N + BR - 1) / BR;
     const int n_wg = B * H * n_qtiles;
     const float scale_log2 = 1.4426950408889634f / __builtin_sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, stream,
-                       (const __bf16*)Q, (const __bf16*)K, (const __bf16*)V, (__bf16*)O,
-                       N, n_qtiles, n_wg, scale_log2);
+                       Q, K, (const __bf16*)V, (__bf16*)O, N, n_qtiles, n_wg, scale_log2);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
-template <int D, int QB>
-int launch_bf16_pipelined(const void* Q, const void* K, const void* V, void* O,
-                          int B, int H, int N, hipStream_t stream)
+template <int D>
+int launch_f32(const void* Q, const void* K, const void* V, void* O,
+               int B, int H, int N, hipStream_t stream)
 {
-    constexpr int BR = kWaves * 32 * QB;
-    constexpr int lds_bytes = 4 * 2 * 64 * D * 2;
-    auto kern = fwd_bf16_pipelined_kernel<D, QB>;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                lds_bytes) != hipSuccess) {
-            (void)hipGetLastError();
-            return SPHATTN_ERR_LAUNCH;
-        }
-        configured = true;
-    }
+    constexpr int BR = kWaves * 32;
+    constexpr int lds_bytes = 2 * 2 * 32 * (D + 4) * 4;
+    auto kern = fwd_f32_kernel<D>;
+    static const bool configured = raise_lds_limit(kern, lds_bytes);
+    if (!configured) return SPHATTN_ERR_LAUNCH;
     const int n_qtiles = (N + BR - 1) / BR;
     const int n_wg = B * H * n_qtiles;
     hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, stream,
-                       (const __bf16*)Q, (const __bf16*)K, (const __bf16*)V, (__bf16*)O,
+                       (const float*)Q, (const float*)K, (const float*)V, (float*)O,
                        N, n_qtiles, n_wg);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
-}
-
-int variant()
-{
-    static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("SPHATTN_VARIANT");
-        v = e ? atoi(e) : 1;
-    }
-    return v;
 }
 
 template <Norm NORM>
@@ -108,12 +96,18 @@ int dispatch(const void* Q, const void* K, const void* V, void* O,
              int B, int H, int N, int d, int dtype, hipStream_t stream)
 {
     if (dtype == SPHATTN_BF16) {
-        if (NORM == Norm::Spherical && variant() == 1) {
-            if (d == 128) return launch_bf16_pipelined<128, 2>(Q, K, V, O, B, H, N, stream);
-            return launch_bf16_pipelined<64, 2>(Q, K, V, O, B, H, N, stream);
+        if (d == 128) return launch_pipelined<128, 2, QKType::Bf16, NORM>(Q, K, V, O, B, H, N, stream);
+        return launch_pipelined<64, 2, QKType::Bf16, NORM>(Q, K, V, O, B, H, N, stream);
+    }
+    if constexpr (NORM == Norm::Spherical) {
+        if (dtype == SPHATTN_FP8QK_BF16V) {
+            if (d == 128) return launch_pipelined<128, 2, QKType::Fp8, NORM>(Q, K, V, O, B, H, N, stream);
+            return launch_pipelined<64, 2, QKType::Fp8, NORM>(Q, K, V, O, B, H, N, stream);
         }
-        if (d == 128) return launch_bf16<128, 2, 64, NORM>(Q, K, V, O, B, H, N, stream);
-        return launch_bf16<64, 2, 64, NORM>(Q, K, V, O, B, H, N, stream);
+        if (dtype == SPHATTN_F32) {
+            if (d == 128) return launch_f32<128>(Q, K, V, O, B, H, N, stream);
+            return launch_f32<64>(Q, K, V, O, B, H, N, stream);
+        }
     }
     return SPHATTN_ERR_DTYPE;
 }
@@ -157,5 +151,6 @@ const char* sphattn_strerror(int code)
 }
 
 int sphattn_version(void) { return kVersion; }
+
 
 }  // extern "C"

@@ -59,6 +59,42 @@ def test_bf16_small_full_compare(pkg, oracle, B, H, N, d):
     assert _rel_err(got, ref) <= TOL["bf16"]
 
 
+FP8_SHAPES = [(1, 1, 1, 128), (1, 2, 33, 128), (2, 2, 300, 64), (1, 3, 257, 128), (1, 1, 1000, 64),
+              (1, 2, 2048, 128), (2, 1, 512, 64)]
+
+
+@pytest.mark.parametrize("B,H,N,d", FP8_SHAPES)
+def test_fp8qk_small_full_compare(pkg, oracle, B, H, N, d):
+    """Q, K stored as OCP E4M3 bytes (per-tensor scaled), V and O bf16."""
+    print(f"case fp8qk B={B} H={H} N={N} d={d}", flush=True)
+    q, k, v = si.make_qkv(B, H, N, d, "fp8qk_bf16v", seed=300 + N + d)
+    got = _gpu(pkg, q, k, v, "fp8qk_bf16v").to(torch.float64).numpy()
+    bits, kinds = _kinds(q, k, v)
+    ref = oracle.spherical_attention(*bits, kinds=kinds)
+    assert np.all(np.isfinite(got))
+    err = _rel_err(got, ref)
+    print(f"fp8qk max|err|/rms={err:.3e}", flush=True)
+    assert err <= TOL["fp8qk_bf16v"]
+
+
+F32_SHAPES = [(1, 1, 1, 64), (1, 1, 256, 64), (1, 2, 33, 128), (2, 2, 300, 64), (1, 1, 257, 128),
+              (1, 2, 700, 128)]
+
+
+@pytest.mark.parametrize("B,H,N,d", F32_SHAPES)
+def test_f32_small_full_compare(pkg, oracle, B, H, N, d):
+    """fp32 storage and fp32 matrix arithmetic; (1,1,256,64) is workload C1."""
+    print(f"case f32 B={B} H={H} N={N} d={d}", flush=True)
+    seed = si.WORKLOADS["C1"].seed if (B, H, N, d) == (1, 1, 256, 64) else 400 + N + d
+    q, k, v = si.make_qkv(B, H, N, d, "f32", seed=seed)
+    got = _gpu(pkg, q, k, v, "f32").to(torch.float64).numpy()
+    bits, kinds = _kinds(q, k, v)
+    ref = oracle.spherical_attention(*bits, kinds=kinds)
+    err = _rel_err(got, ref)
+    print(f"f32 max|err|/rms={err:.3e}", flush=True)
+    assert err <= TOL["f32"]
+
+
 def test_c2_full_compare(pkg, oracle):
     """Workload C2 (B=4,H=8,N=2048,d=64) in full."""
     print("case C2 full", flush=True)
@@ -82,7 +118,7 @@ def _gram_reference(q, k, v):
     return ((Q @ KtV) / z.sqrt()).numpy()
 
 
-@pytest.mark.parametrize("name", ["C3", "C4"])
+@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
 def test_full_size_sampled_rows_and_gram(pkg, oracle, name):
     """Full-size workloads in the benchmark's launch configuration: oracle on sampled query
     rows of every head, plus the Gram-matrix closed form on the whole tensor."""
@@ -95,7 +131,7 @@ def test_full_size_sampled_rows_and_gram(pkg, oracle, name):
     worst = 0.0
     for bh in range(w.B * w.H):
         b, h = divmod(bh, w.H)
-        n_rows = 64 if bh else 512
+        n_rows = (64 if bh else 512) if name != "C5" else (24 if bh else 256)
         rows = np.sort(rng.choice(w.N, size=n_rows, replace=False)).astype(np.int32)
         rows[0], rows[-1] = 0, w.N - 1
         ref = oracle.spherical_attention_rows(*bits, bh, rows, kinds)
@@ -146,7 +182,8 @@ def test_does_not_write_outside_output(pkg):
     assert torch.all(buf[B * H * N * d:] == 7.0)
 
 
-@pytest.mark.parametrize("B,H,N,d", [(1, 2, 300, 64), (1, 1, 257, 128), (2, 1, 1024, 128)])
+@pytest.mark.parametrize("B,H,N,d", [(1, 2, 300, 64), (1, 1, 257, 128), (2, 1, 1024, 128), (1, 1, 20, 64),
+                                     (1, 2, 2048, 64), (1, 1, 4096, 128), (1, 1, 33, 128)])
 def test_softmax_twin_parity(pkg, oracle, B, H, N, d):
     print(f"case softmax twin B={B} H={H} N={N} d={d}", flush=True)
     q, k, v = si.make_qkv(B, H, N, d, "bf16", seed=200 + N)
