@@ -21,7 +21,9 @@ if ROOT not in sys.path:
 # dense MFMA peaks of MI355X; the fp8-QK workload runs half its flops at the fp8 rate (5000)
 # and half at the bf16 rate (2500): harmonic mean
 PEAK_TFLOPS = {"bf16": 2500.0, "fp8qk_bf16v": 1.0 / (0.5 / 5000.0 + 0.5 / 2500.0), "f32": 157.3}
-HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by the reading of a
+# 256 MiB device copy in the same run (see profiles/); workloads not profiled report null
+MEASURED_HBM_BYTES = {"C3": 268.6e6, "C5": 1208.0e6}
 
 
 def time_launches(fn, steps, warmup):
@@ -119,7 +121,7 @@ def main() -> int:
         "config": {"workload": w.describe(), "B": w.B, "H": w.H, "N": w.N, "d": w.d,
                    "flop_per_step": w.flops, "min_hbm_bytes_per_step": algo_bytes},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": peak, "unit": "TFLOP/s",
-                     "frac": kern_tflops / peak, "traffic": None,
+                     "frac": kern_tflops / peak, "traffic": MEASURED_HBM_BYTES.get(w.name),
                      "kernel_ms_avg": ms_kernel, "kernel_ms_median": per[len(per) // 2],
                      "kernel_ms_min": per[0]},
     }
