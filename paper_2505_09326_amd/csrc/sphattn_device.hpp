@@ -166,7 +166,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     constexpr int KSTEPS = FP8 ? D / 64 : D / 16;  // MFMA k-steps of K Q^T
     constexpr int PD = 3;                          // LDS prefetch distance in slots
     constexpr int RING = 4;                        // fragment registers in rotation
-    constexpr int VALU_PER_MFMA = 4;               // VALU instructions issued behind each MFMA
+    constexpr int VALU_PER_MFMA = 6;               // VALU instructions issued behind each MFMA (measured best of 2..6)
     static_assert(D == 64 || D == 128, "head dimension 128 or 64");
     static_assert(FP8 || KSTEPS == SLOTS, "bf16: one K fragment per slot");
     static_assert(!FP8 || QB == 2, "fp8 slot plan is written for two query blocks");

@@ -95,6 +95,26 @@ def test_f32_small_full_compare(pkg, oracle, B, H, N, d):
     assert err <= TOL["f32"]
 
 
+def test_bf16_many_heads_ragged(pkg, oracle):
+    """Many heads (the workgroup-to-XCD remap gets a remainder-free and a ragged case), ragged N."""
+    B, H, N, d = 16, 8, 2100, 64
+    print(f"case bf16 many heads B={B} H={H} N={N} d={d}", flush=True)
+    q, k, v = si.make_qkv(B, H, N, d, "bf16", seed=77)
+    got = _gpu(pkg, q, k, v, "bf16").to(torch.float64).numpy()
+    bits, kinds = _kinds(q, k, v)
+    rng = np.random.default_rng(5)
+    worst = 0.0
+    for bh in [0, 1, 63, 127]:
+        b, h = divmod(bh, H)
+        rows = np.sort(rng.choice(N, size=300, replace=False)).astype(np.int32)
+        rows[0], rows[-1] = 0, N - 1
+        ref = oracle.spherical_attention_rows(*bits, bh, rows, kinds)
+        worst = max(worst, np.abs(got[b, h, rows] - ref).max() / np.sqrt((ref ** 2).mean()))
+    full = _gram_reference(q, k, v)
+    assert worst <= TOL["bf16"]
+    assert _rel_err(got, full) <= TOL["bf16"]
+
+
 def test_c2_full_compare(pkg, oracle):
     """Workload C2 (B=4,H=8,N=2048,d=64) in full."""
     print("case C2 full", flush=True)
