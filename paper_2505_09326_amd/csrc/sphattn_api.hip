@@ -62,7 +62,7 @@ int launch_pipelined(const void* Q, const void* K, const void* V, void* O,
 {
     constexpr int BR = kWaves * 32 * QB;
     constexpr int EQ = QKT == QKType::Fp8 ? 1 : 2;
-    constexpr int lds_bytes = kNBuf * kBC * D * (EQ + 2);
+    constexpr int lds_bytes = kNBuf * kBC * (D * EQ + kKPad + D * 2 + kVPad);
     auto kern = fwd_pipelined_kernel<D, QB, QKT, NORM>;
     static const bool configured = raise_lds_limit(kern, lds_bytes);   // once per process
     if (!configured) return SPHATTN_ERR_LAUNCH;

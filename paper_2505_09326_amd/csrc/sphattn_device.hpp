@@ -57,25 +57,15 @@ __device__ __forceinline__ int xcd_contiguous_id(int wg, int n_wg)
     return start + idx;
 }
 
-// 16-byte chunk slot of chunk c in row r of a K tile whose rows hold CH chunks.
-// 16 lanes reading one chunk column of 16 consecutive rows (the matrix-core
-// A-operand pattern) must touch 16 different 16-byte bank groups of the 256-byte
-// LDS line: rows that share a line get different slots.
-template <int CH>
-__device__ __forceinline__ int kswz(int r, int c)
-{
-    constexpr int RPL = 16 / CH;                   // rows per 256-byte line
-    return c ^ ((r / RPL) & (CH - 1));
-}
-
-// V tile swizzle for the transposing read: the 16 lanes of a read block touch
-// 4 consecutive rows x 32 bytes; spread the 4 rows over different 64-byte groups.
-template <int CH>
-__device__ __forceinline__ int vswz(int r, int c)
-{
-    if (CH >= 16) return c ^ ((r & 3) << 2);
-    return c ^ ((r & 1) << 2) ^ (((r >> 1) & 1) * 2);
-}
+// LDS rows are padded instead of swizzled, so that every fragment address is one per-lane
+// register plus an instruction immediate:
+//   K rows: +16 bytes.  16 lanes reading the same column of 16 consecutive rows (the
+//           matrix-core A-operand pattern, ds_read_b128) then hit 16 different 16-byte groups
+//           of the 256-byte LDS line.
+//   V rows: +64 bytes.  The 16 lanes of a transposing-read block touch 4 consecutive rows x
+//           32 bytes; consecutive rows land in different 64-byte groups.
+constexpr int kKPad = 16;
+constexpr int kVPad = 64;
 
 __device__ __forceinline__ i32x4 lds_read_b128(const SPH_LDS unsigned char* p)
 {
@@ -155,9 +145,11 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     constexpr int BC = kBC;
     constexpr int BR = kWaves * 32 * QB;
     constexpr int EQ = FP8 ? 1 : 2;                // bytes per Q/K element
-    constexpr int KROWB = D * EQ, KCH = KROWB / 16, KTILE = BC * KROWB;
+    constexpr int KROWB = D * EQ, KCH = KROWB / 16, KTILE = BC * KROWB;   // as stored in HBM
     constexpr int VROWB = D * 2, VCH = VROWB / 16, VTILE = BC * VROWB;
-    constexpr int BUF_BYTES = KTILE + VTILE;       // K tile then V tile
+    constexpr int KSTR = KROWB + kKPad, VSTR = VROWB + kVPad;             // LDS row strides
+    constexpr int KLDS = BC * KSTR;                                        // K tile in LDS
+    constexpr int BUF_BYTES = KLDS + BC * VSTR;    // K tile then V tile
     constexpr int LDK = BC * KCH / kThreads;       // 16-byte chunks per thread per K tile
     constexpr int LDV = BC * VCH / kThreads;
     constexpr int NST = LDK + LDV;                 // staged chunks per thread per tile
@@ -192,44 +184,19 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     const __amdgpu_buffer_rsrc_t vrs = make_rsrc(V + head_off, (uint32_t)N * VROWB);
     const int q0 = qt * BR + wave * 32 * QB;
 
-    // ---- per-lane LDS byte offsets inside a tile
-    // K fragment, bf16 (sub, kk): row sub*32 + l32, 16-byte chunk 2kk + h
-    // K fragment, fp8  (sub, kk): row sub*32 + l32, chunks 4kk + 2h and 4kk + 2h + 1
-    constexpr int NKOFF = FP8 ? 2 * KSTEPS : KSTEPS;
-    int koff[NKOFF];
-#pragma unroll
-    for (int x = 0; x < NKOFF; ++x) {
-        const int c = FP8 ? 4 * (x / 2) + 2 * h + (x & 1) : 2 * x + h;
-        koff[x] = l32 * KROWB + 16 * kswz<KCH>(l32, c);
-    }
+    // ---- per-lane LDS byte offsets inside a tile; everything else is an immediate
+    // K fragment, bf16 (sub, kk): row sub*32 + l32, bytes 32kk + 16h .. +15
+    // K fragment, fp8  (sub, kk): row sub*32 + l32, bytes 64kk + 32h .. +31 (two 16-byte reads)
+    const int klane = l32 * KSTR + (FP8 ? 32 : 16) * h;
     // V^T fragment (sub, ks, db): rows sub*32 + 16ks + 4h + (i16>>2) [+8], 8 bytes at column
     // db*32 + 16*blk + 4*(i16&3).  Within a 16-lane block, lane i supplies the 8-byte piece
     // row (i>>2), columns 4(i&3)..+3 and receives column i of all 4 rows.
-    int voff[DB];
-    {
-        const int r = 4 * h + (i16 >> 2);
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            const int colb = (db * 32 + 16 * blk + 4 * (i16 & 3)) * 2;
-            voff[db] = KTILE + r * VROWB + 16 * vswz<VCH>(r, colb >> 4) + (colb & 15);
-        }
-    }
-    // staging: chunks 0..LDK-1 are K, LDK..NST-1 are V; chunk id = tid + i*256 of its tile
-    int st_off[NST], ld_off[NST];
-#pragma unroll
-    for (int c = 0; c < NST; ++c) {
-        const bool isk = c < LDK;
-        const int id = tid + (isk ? c : c - LDK) * kThreads;
-        if (isk) {
-            const int r = id / KCH, cc = id % KCH;
-            st_off[c] = r * KROWB + 16 * kswz<KCH>(r, cc);
-            ld_off[c] = r * KROWB + cc * 16;
-        } else {
-            const int r = id / VCH, cc = id % VCH;
-            st_off[c] = KTILE + r * VROWB + 16 * vswz<VCH>(r, cc);
-            ld_off[c] = r * VROWB + cc * 16;
-        }
-    }
+    const int vlane = KLDS + (4 * h + (i16 >> 2)) * VSTR + (16 * blk + 4 * (i16 & 3)) * 2;
+    // staging: chunks 0..LDK-1 are K, LDK..NST-1 are V; chunk id = tid + i*256 of its tile,
+    // i.e. row tid/CH + i*(256/CH), 16-byte column tid%CH
+    const int kst_lane = (tid / KCH) * KSTR + (tid % KCH) * 16;
+    const int vst_lane = KLDS + (tid / VCH) * VSTR + (tid % VCH) * 16;
+    const int kld_lane = tid * 16, vld_lane = tid * 16;      // tiles are contiguous in HBM
 
     // ---- Q fragments (B operands of S^T = K Q^T), held for the whole kernel.  The k index
     // that a (lane half, element) slot stands for is the same for A and B operands, so any
@@ -275,11 +242,15 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
 
     i32x4 stage[NST];
     auto gload_chunk = [&](int c, int tile) {
-        const uint32_t off = (uint32_t)tile * (c < LDK ? KTILE : VTILE) + ld_off[c];
-        stage[c] = __builtin_amdgcn_raw_buffer_load_b128(c < LDK ? krs : vrs, off, 0, 0);
+        if (c < LDK)
+            stage[c] = __builtin_amdgcn_raw_buffer_load_b128(krs, kld_lane, tile * KTILE + c * kThreads * 16, 0);
+        else
+            stage[c] = __builtin_amdgcn_raw_buffer_load_b128(vrs, vld_lane, tile * VTILE + (c - LDK) * kThreads * 16, 0);
     };
     auto lstore_chunk = [&](int c, SPH_LDS unsigned char* buf) {
-        *reinterpret_cast<SPH_LDS i32x4*>(buf + st_off[c]) = stage[c];
+        const int off = c < LDK ? kst_lane + c * (kThreads / KCH) * KSTR
+                                : vst_lane + (c - LDK) * (kThreads / VCH) * VSTR;
+        *reinterpret_cast<SPH_LDS i32x4*>(buf + off) = stage[c];
     };
 
     const int n_tiles = (N + BC - 1) / BC;
@@ -328,11 +299,11 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     for (int kk = 0; kk < KSTEPS; ++kk) {
         qfrag_t kfr;
         if constexpr (FP8) {
-            const i32x4 lo = lds_read_b128(smem + koff[2 * kk]);
-            const i32x4 hi = lds_read_b128(smem + koff[2 * kk + 1]);
+            const i32x4 lo = lds_read_b128(smem + klane + 64 * kk);
+            const i32x4 hi = lds_read_b128(smem + klane + 64 * kk + 16);
             kfr = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         } else {
-            kfr = lds_read_b128(smem + koff[kk]);
+            kfr = lds_read_b128(smem + klane + 32 * kk);
         }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) S0[qb] = mfma_qk(kfr, qf[qb][kk], S0[qb]);
@@ -351,19 +322,21 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     auto issue_reads = [&](int u, const SPH_LDS unsigned char* bprv, const SPH_LDS unsigned char* bcur,
                            const SPH_LDS unsigned char* bnxt) {
         const int hh = u / SLOTS, i = u % SLOTS;
-        const SPH_LDS unsigned char* kp = hh == 0 ? bcur + 32 * KROWB : hh == 1 ? bnxt : bnxt + 32 * KROWB;
-        const SPH_LDS unsigned char* vp = hh == 0 ? bprv + 32 * VROWB : hh == 1 ? bcur : bcur + 32 * VROWB;
+        const SPH_LDS unsigned char* kp = hh == 0 ? bcur + 32 * KSTR : hh == 1 ? bnxt : bnxt + 32 * KSTR;
+        const SPH_LDS unsigned char* vp = hh == 0 ? bprv + 32 * VSTR : hh == 1 ? bcur : bcur + 32 * VSTR;
+        // V first, K last: LDS returns in order, so the one wait in front of the slot's first
+        // matrix instruction (which needs K) covers all three reads
+        const int ks = i / DB, db = i % DB;
+        const SPH_LDS unsigned char* a = vp + vlane + (16 * ks) * VSTR + db * 64;
+        const bf16x4 lo = lds_read_tr64(a);
+        const bf16x4 hi = lds_read_tr64(a + 8 * VSTR);
+        vf[u % RING] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         if constexpr (FP8) {
             const int kk = i / (2 * QB), part = i % (2 * QB);
-            if (kk < KSTEPS && part < 2) kf8[hh & 1][kk][part] = lds_read_b128(kp + koff[2 * kk + part]);
+            if (kk < KSTEPS && part < 2) kf8[hh & 1][kk][part] = lds_read_b128(kp + klane + 64 * kk + 16 * part);
         } else {
-            kf[u % RING] = lds_read_b128(kp + koff[i]);
+            kf[u % RING] = lds_read_b128(kp + klane + 32 * i);
         }
-        const int ks = i / DB, db = i % DB;
-        const SPH_LDS unsigned char* a = vp + (16 * ks) * VROWB + voff[db];
-        const bf16x4 lo = lds_read_tr64(a);
-        const bf16x4 hi = lds_read_tr64(a + 8 * VROWB);
-        vf[u % RING] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
     // buffers of tiles j-1, j, j+1, j+2
@@ -535,13 +508,13 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
 #pragma unroll
                     for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= apend[qb];
         }
-        const SPH_LDS unsigned char* vp = bprv + 32 * VROWB;
+        const SPH_LDS unsigned char* vp = bprv + 32 * VSTR;
 #pragma unroll
         for (int i = 0; i < SLOTS; ++i) {
             const int ks = i / DB, db = i % DB;
-            const SPH_LDS unsigned char* a = vp + (16 * ks) * VROWB + voff[db];
+            const SPH_LDS unsigned char* a = vp + vlane + (16 * ks) * VSTR + db * 64;
             const bf16x4 lo = lds_read_tr64(a);
-            const bf16x4 hi = lds_read_tr64(a + 8 * VROWB);
+            const bf16x4 hi = lds_read_tr64(a + 8 * VSTR);
             const bf16x8 vfr = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
