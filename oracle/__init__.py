@@ -52,6 +52,11 @@ def _load():
         lib.oracle_attention_rows.restype = ip
         lib.oracle_attention_rows.argtypes = [ip, vp, ip, vp, ip, vp, ip, dp, ip, ip, ip, ip, ip,
                                               ctypes.POINTER(ctypes.c_int), ip]
+        lib.oracle_attention_fwd_grn.restype = ip
+        lib.oracle_attention_fwd_grn.argtypes = [ip, vp, ip, vp, ip, vp, ip, dp, dp, dp, dp, ip, ip, ip, ip, ip]
+        lib.oracle_attention_rows_grn.restype = ip
+        lib.oracle_attention_rows_grn.argtypes = [ip, vp, ip, vp, ip, vp, ip, dp, dp, ip, ip, ip, ip, ip, ip,
+                                                  ctypes.POINTER(ctypes.c_int), ip]
         lib.oracle_spherical_streamed.restype = ip
         lib.oracle_spherical_streamed.argtypes = [dp, dp, dp, dp, ip, ip, ip, ip, ip]
         lib.oracle_widen.restype = None
@@ -180,3 +185,55 @@ def spherical_attention_streamed(Q, K, V, chunk: int) -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"oracle_spherical_streamed failed with {rc}")
     return O
+
+
+def _prep_mult(mult, B, N):
+    if mult is None:
+        return None
+    m = np.ascontiguousarray(mult, dtype=np.float64)
+    if m.shape != (B, N):
+        raise ValueError("mult must have shape [B, N]")
+    return m
+
+
+def grn_attention(Q, K, V, mult=None, kinds=None) -> np.ndarray:
+    """Gene-regulatory-network variant: s_ij = q_i . (m_j k_j) with per-cell multiplicities
+    mult[B,N] (None = all ones) and grouped K/V heads (K, V are [B,H_kv,N,d], H % H_kv == 0)."""
+    kq, kk, kv = kinds if kinds is not None else (None, None, None)
+    Q, kq = _prep(Q, kq)
+    K, kk = _prep(K, kk)
+    V, kv = _prep(V, kv)
+    B, H, N, d = Q.shape
+    if K.shape != V.shape or K.shape[0] != B or K.shape[2:] != (N, d):
+        raise ValueError("K, V must be [B,H_kv,N,d]")
+    H_kv = K.shape[1]
+    m = _prep_mult(mult, B, N)
+    O = np.empty((B, H, N, d), dtype=np.float64)
+    rc = _load().oracle_attention_fwd_grn(
+        0, Q.ctypes.data_as(ctypes.c_void_p), _KINDS[kq], K.ctypes.data_as(ctypes.c_void_p), _KINDS[kk],
+        V.ctypes.data_as(ctypes.c_void_p), _KINDS[kv], _dptr(m) if m is not None else None,
+        _dptr(O), None, None, B, H, H_kv, N, d)
+    if rc != 0:
+        raise RuntimeError(f"oracle_attention_fwd_grn failed with {rc}")
+    return O
+
+
+def grn_attention_rows(Q, K, V, mult, bh: int, rows, kinds=None) -> np.ndarray:
+    """Rows `rows` of query head `bh` (= b*H + h) of the GRN variant: [len(rows), d]."""
+    kq, kk, kv = kinds if kinds is not None else (None, None, None)
+    Q, kq = _prep(Q, kq)
+    K, kk = _prep(K, kk)
+    V, kv = _prep(V, kv)
+    B, H, N, d = Q.shape
+    H_kv = K.shape[1]
+    m = _prep_mult(mult, B, N)
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    out = np.empty((rows.size, d), dtype=np.float64)
+    rc = _load().oracle_attention_rows_grn(
+        0, Q.ctypes.data_as(ctypes.c_void_p), _KINDS[kq], K.ctypes.data_as(ctypes.c_void_p), _KINDS[kk],
+        V.ctypes.data_as(ctypes.c_void_p), _KINDS[kv], _dptr(m) if m is not None else None,
+        _dptr(out), B, H, H_kv, N, d, int(bh),
+        rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), int(rows.size))
+    if rc != 0:
+        raise RuntimeError(f"oracle_attention_rows_grn failed with {rc}")
+    return out

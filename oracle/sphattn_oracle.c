@@ -26,6 +26,11 @@
  * e4m3fn bytes) and widened exactly to fp64 before any arithmetic.  Layout is
  * dense row-major [B,H,N,d] with d contiguous.
  *
+ * Gene-regulatory-network variant (paper, Section 3.1 and Appendix A.2): the key of
+ * gene j is multiplied by that gene's multiplicity m_j before the scores are formed,
+ * s_ij = sum_k Q[b,h,i,k] * (m[b,j] * K[b,g,j,k]), and K/V heads may be shared by
+ * groups of query heads (grouped-query attention): g = h / (H / H_kv).
+ *
  * The comparison twin (standard SoftMax attention, a1 = a2 = exp, b = id, with
  * the conventional 1/sqrt(d) score scale) is also given, from its textbook
  * definition.
@@ -98,14 +103,14 @@ void oracle_widen(const void *src, int kind, size_t off, size_t count, double *d
 /* Spherical row: two passes, exactly as the definition reads.
  * s (length N) is caller-provided scratch and holds the raw scores on return.
  * w, if not NULL, receives the normalized weights s_j / sqrt(z). */
-static void spherical_row(const double *q, const double *Kh, const double *Vh,
+static void spherical_row(const double *q, const double *Kh, const double *Vh, const double *m,
                           int N, int d, double *s, double *o, double *w, double *z_out)
 {
     double z = 0.0;
     for (int j = 0; j < N; ++j) {
         double acc = 0.0;
         for (int k = 0; k < d; ++k)
-            acc += q[k] * Kh[(size_t)j * d + k];
+            acc += q[k] * (m ? m[j] * Kh[(size_t)j * d + k] : Kh[(size_t)j * d + k]);
         s[j] = acc;
         z += acc * acc;
     }
@@ -159,19 +164,25 @@ static void softmax_row(const double *q, const double *Kh, const double *Vh,
  * O: [B,H,N,d] fp64.  W (may be NULL; spherical only): [B,H,N,N] weights.
  * Z (may be NULL; spherical only): [B,H,N] squared row norms.
  * Returns 0, or -1 on bad arguments / allocation failure. */
-int oracle_attention_fwd(int mode, const void *Q, int q_kind, const void *K, int k_kind,
-                         const void *V, int v_kind, double *O, double *W, double *Z,
-                         int B, int H, int N, int d)
+int oracle_attention_fwd_grn(int mode, const void *Q, int q_kind, const void *K, int k_kind,
+                             const void *V, int v_kind, const double *mult,
+                             double *O, double *W, double *Z,
+                             int B, int H, int H_kv, int N, int d)
 {
-    if (!Q || !K || !V || !O || B <= 0 || H <= 0 || N <= 0 || d <= 0)
+    if (!Q || !K || !V || !O || B <= 0 || H <= 0 || H_kv <= 0 || H % H_kv || N <= 0 || d <= 0)
+        return -1;
+    if (mode != 0 && mult)
         return -1;
     size_t head = (size_t)N * d;
     double *Kh = malloc(head * sizeof *Kh);
     double *Vh = malloc(head * sizeof *Vh);
     int status = (Kh && Vh) ? 0 : -1;
     for (int bh = 0; bh < B * H && status == 0; ++bh) {
-        oracle_widen(K, k_kind, (size_t)bh * head, head, Kh);
-        oracle_widen(V, v_kind, (size_t)bh * head, head, Vh);
+        const int b = bh / H, h = bh % H;
+        const size_t kvh = (size_t)b * H_kv + h / (H / H_kv);   /* K/V head of this query head */
+        const double *m = mult ? mult + (size_t)b * N : NULL;    /* multiplicities of this cell */
+        oracle_widen(K, k_kind, kvh * head, head, Kh);
+        oracle_widen(V, v_kind, kvh * head, head, Vh);
 #pragma omp parallel
         {
             double *q = malloc((size_t)d * sizeof *q);
@@ -185,7 +196,7 @@ int oracle_attention_fwd(int mode, const void *Q, int q_kind, const void *K, int
                     size_t row = (size_t)bh * N + i;
                     oracle_widen(Q, q_kind, row * d, (size_t)d, q);
                     if (mode == 0)
-                        spherical_row(q, Kh, Vh, N, d, s, O + row * d,
+                        spherical_row(q, Kh, Vh, m, N, d, s, O + row * d,
                                       W ? W + row * N : NULL, Z ? Z + row : NULL);
                     else
                         softmax_row(q, Kh, Vh, N, d, s, O + row * d);
@@ -200,15 +211,23 @@ int oracle_attention_fwd(int mode, const void *Q, int q_kind, const void *K, int
     return status;
 }
 
+/* The plain case: no multiplicities, one K/V head per query head. */
+int oracle_attention_fwd(int mode, const void *Q, int q_kind, const void *K, int k_kind,
+                         const void *V, int v_kind, double *O, double *W, double *Z,
+                         int B, int H, int N, int d)
+{
+    return oracle_attention_fwd_grn(mode, Q, q_kind, K, k_kind, V, v_kind, NULL, O, W, Z, B, H, H, N, d);
+}
+
 /* Selected query rows of one head only (for full-size workloads, where the
  * whole tensor would take minutes): rows[r] in [0,N) of head index bh in
  * [0,B*H).  O_rows: [n_rows, d] fp64. */
-int oracle_attention_rows(int mode, const void *Q, int q_kind, const void *K, int k_kind,
-                          const void *V, int v_kind, double *O_rows,
-                          int B, int H, int N, int d, int bh, const int *rows, int n_rows)
+int oracle_attention_rows_grn(int mode, const void *Q, int q_kind, const void *K, int k_kind,
+                              const void *V, int v_kind, const double *mult, double *O_rows,
+                              int B, int H, int H_kv, int N, int d, int bh, const int *rows, int n_rows)
 {
-    if (!Q || !K || !V || !O_rows || !rows || B <= 0 || H <= 0 || N <= 0 || d <= 0 ||
-        bh < 0 || bh >= B * H || n_rows < 0)
+    if (!Q || !K || !V || !O_rows || !rows || B <= 0 || H <= 0 || H_kv <= 0 || H % H_kv ||
+        N <= 0 || d <= 0 || bh < 0 || bh >= B * H || n_rows < 0 || (mode != 0 && mult))
         return -1;
     for (int r = 0; r < n_rows; ++r)
         if (rows[r] < 0 || rows[r] >= N)
@@ -218,8 +237,10 @@ int oracle_attention_rows(int mode, const void *Q, int q_kind, const void *K, in
     double *Vh = malloc(head * sizeof *Vh);
     int status = (Kh && Vh) ? 0 : -1;
     if (status == 0) {
-        oracle_widen(K, k_kind, (size_t)bh * head, head, Kh);
-        oracle_widen(V, v_kind, (size_t)bh * head, head, Vh);
+        const size_t kvh = (size_t)(bh / H) * H_kv + (bh % H) / (H / H_kv);
+        const double *m = mult ? mult + (size_t)(bh / H) * N : NULL;
+        oracle_widen(K, k_kind, kvh * head, head, Kh);
+        oracle_widen(V, v_kind, kvh * head, head, Vh);
 #pragma omp parallel
         {
             double *q = malloc((size_t)d * sizeof *q);
@@ -233,7 +254,7 @@ int oracle_attention_rows(int mode, const void *Q, int q_kind, const void *K, in
                     size_t row = (size_t)bh * N + rows[r];
                     oracle_widen(Q, q_kind, row * d, (size_t)d, q);
                     if (mode == 0)
-                        spherical_row(q, Kh, Vh, N, d, s, O_rows + (size_t)r * d, NULL, NULL);
+                        spherical_row(q, Kh, Vh, m, N, d, s, O_rows + (size_t)r * d, NULL, NULL);
                     else
                         softmax_row(q, Kh, Vh, N, d, s, O_rows + (size_t)r * d);
                 }
@@ -245,6 +266,14 @@ int oracle_attention_rows(int mode, const void *Q, int q_kind, const void *K, in
     free(Kh);
     free(Vh);
     return status;
+}
+
+int oracle_attention_rows(int mode, const void *Q, int q_kind, const void *K, int k_kind,
+                          const void *V, int v_kind, double *O_rows,
+                          int B, int H, int N, int d, int bh, const int *rows, int n_rows)
+{
+    return oracle_attention_rows_grn(mode, Q, q_kind, K, k_kind, V, v_kind, NULL, O_rows,
+                                     B, H, H, N, d, bh, rows, n_rows);
 }
 
 /* Lemma 1 as a loop: the key axis is cut into chunks of `chunk` rows (the last

@@ -268,3 +268,65 @@ def test_softmax_twin_against_library(oracle):
     rows = [3, 44]
     np.testing.assert_allclose(oracle.softmax_attention_rows(Q, K, V, 3, rows), O[1, 1, rows],
                                rtol=1e-13)
+
+
+# ---------------------------------------------------------------- GRN variant (Section 3.1)
+def _grn_numpy(Q, K, V, mult, H_kv):
+    """The same definition written with numpy primitives: keys scaled by multiplicity, K/V heads
+    repeated over their query-head groups."""
+    B, H, N, d = Q.shape
+    rep = H // H_kv
+    Kx = np.repeat(K, rep, axis=1)
+    Vx = np.repeat(V, rep, axis=1)
+    if mult is not None:
+        Kx = Kx * mult[:, None, :, None]
+    S = np.einsum("bhik,bhjk->bhij", Q, Kx)
+    W = S / np.sqrt((S ** 2).sum(-1, keepdims=True))
+    return np.matmul(W, Vx)
+
+
+@pytest.mark.parametrize("H,H_kv", [(4, 4), (4, 2), (6, 1), (3, 3)])
+def test_grn_variant_against_numpy_definition(oracle, H, H_kv):
+    """Catches a wrong group index (h % H_kv instead of h // group), multiplicities applied per
+    query instead of per key, or to the wrong batch row."""
+    B, N, d = 2, 23, 5
+    Q = _rand((B, H, N, d), 60)
+    K = _rand((B, H_kv, N, d), 61)
+    V = _rand((B, H_kv, N, d), 62)
+    mult = np.random.default_rng(63).integers(0, 6, size=(B, N)).astype(np.float64)
+    mult[:, 0] = 3.0
+    np.testing.assert_allclose(oracle.grn_attention(Q, K, V, mult), _grn_numpy(Q, K, V, mult, H_kv),
+                               rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(oracle.grn_attention(Q, K, V, None), _grn_numpy(Q, K, V, None, H_kv),
+                               rtol=1e-12, atol=1e-14)
+    rows = [0, 22, 9]
+    for bh in range(B * H):
+        b, h = divmod(bh, H)
+        np.testing.assert_allclose(oracle.grn_attention_rows(Q, K, V, mult, bh, rows),
+                                   _grn_numpy(Q, K, V, mult, H_kv)[b, h, rows], rtol=1e-12, atol=1e-14)
+
+
+def test_grn_multiplicity_brute_force_rationals(oracle):
+    """Exact rationals: s_ij = m_j (q_i . k_j); a gene with multiplicity 0 drops out, integer
+    multiplicity m equals m copies of the key only through the score scale (not the bag size)."""
+    rng = np.random.default_rng(64)
+    N, d = 6, 3
+    Qi, Ki, Vi = (rng.integers(-5, 6, size=(N, d)) for _ in range(3))
+    m = [2, 0, 1, 3, 1, 5]
+    Qf = [[Fraction(int(x), 2) for x in r] for r in Qi]
+    Kf = [[Fraction(int(x)) * m[j] for x in r] for j, r in enumerate(Ki)]
+    Vf = [[Fraction(int(x), 4) for x in r] for r in Vi]
+    o_raw, z = _brute_force_exact(Qf, Kf, Vf)
+    O = oracle.grn_attention((Qi / 2.0).reshape(1, 1, N, d), Ki.astype(np.float64).reshape(1, 1, N, d),
+                             (Vi / 4.0).reshape(1, 1, N, d), np.array([m], dtype=np.float64))
+    for i in range(N):
+        for c in range(d):
+            want = 0.0 if z[i] == 0 else float(o_raw[i][c]) / math.sqrt(float(z[i]))
+            assert O[0, 0, i, c] == pytest.approx(want, rel=4e-16, abs=1e-300)
+
+
+def test_grn_uniform_multiplicity_cancels(oracle):
+    """A constant multiplicity is a positive scale on K and cancels in the normalisation."""
+    Q, K, V = (_rand((1, 2, 17, 4), s) for s in (65, 66, 67))
+    np.testing.assert_allclose(oracle.grn_attention(Q, K, V, np.full((1, 17), 7.0)),
+                               oracle.spherical_attention(Q, K, V), rtol=1e-12, atol=1e-14)
