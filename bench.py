@@ -78,6 +78,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C3", help="C1..C5 (default C3: the configuration the target is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-twin", action="store_true")
+    ap.add_argument("--grn", type=int, default=0, metavar="H_KV",
+                    help="also time the gene-regulatory-network entry point on the same shape with "
+                         "H_KV shared K/V heads and Poisson(1.5) multiplicities")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run a plain 256 MiB device copy (untimed), as the known-size "
                          "reference that HBM byte counters are scaled by when profiling")
@@ -133,6 +136,18 @@ def main() -> int:
         ms_t = sum(per_t) / len(per_t)
         result["softmax_twin"] = {"kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12,
                                   "spherical_speedup": ms_t / ms_kernel}
+
+    if args.grn:
+        g = torch.Generator(device="cpu").manual_seed(w.seed + 1000)
+        mult = torch.poisson(torch.full((w.B, w.N), 1.5), generator=g).to(torch.float32).to(dev)
+        kg, vg = kd[:, :args.grn].contiguous(), vd[:, :args.grn].contiguous()
+
+        def grn():
+            pkg.sphattn_grn_fwd(qd, kg, vg, mult, out, dtype=w.dtype)
+        _, per_g = time_launches(grn, max(10, args.steps // 4), max(5, args.warmup // 4))
+        ms_g = sum(per_g) / len(per_g)
+        result["grn_variant"] = {"H_kv": args.grn, "multiplicities": "Poisson(1.5)", "kernel_ms_avg": ms_g,
+                                 "tflops": w.flops / (ms_g * 1e-3) / 1e12}
 
     if args.copy_reference:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)

@@ -37,7 +37,7 @@ typedef enum {
 enum {
     SPHATTN_OK = 0,
     SPHATTN_ERR_NULL = -1,        /* a required pointer is NULL */
-    SPHATTN_ERR_SHAPE = -2,       /* B, H or N not positive, or B*H*N*d overflows */
+    SPHATTN_ERR_SHAPE = -2,       /* B, H, N (or H_kv) not positive, H_kv not dividing H, or sizes overflow */
     SPHATTN_ERR_HEAD_DIM = -3,    /* d is not 64 or 128 */
     SPHATTN_ERR_DTYPE = -4,       /* dtype is not a sphattn_dtype value */
     SPHATTN_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned */
@@ -61,6 +61,23 @@ enum {
  */
 int sphattn_fwd(const void* Q, const void* K, const void* V, void* O,
                 int B, int H, int N, int d, int dtype, void* stream);
+
+/*
+ * Gene-regulatory-network variant (paper, Section 3.1 and Appendix A.2).  Tokens are genes;
+ * the key of gene j is multiplied by that gene's multiplicity in the cell before the scores
+ * are formed, and K/V heads may be shared by groups of query heads (grouped-query attention):
+ *
+ *     s_ij = mult[b,j] * sum_k Q[b,h,i,k] * K[b,g,j,k],      g = h / (H / H_kv)
+ *     O[b,h,i,:] = ( sum_j s_ij * V[b,g,j,:] ) / sqrt( sum_j s_ij^2 )
+ *
+ *   Q, O    : [B,H,N,d];   K, V : [B,H_kv,N,d], H_kv dividing H (H_kv == H: no sharing).
+ *   mult    : [B,N] fp32 device pointer (4-byte aligned), finite values; NULL means all ones,
+ *             which makes this call identical to sphattn_fwd when H_kv == H.
+ * Everything else (layout, dtypes, ownership, stream, error codes) as sphattn_fwd;
+ * SPHATTN_ERR_SHAPE also covers H_kv <= 0 or H % H_kv != 0.
+ */
+int sphattn_grn_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O,
+                    int B, int H, int H_kv, int N, int d, int dtype, void* stream);
 
 /*
  * Comparison twin on the same tiling skeleton: standard SoftMax attention,

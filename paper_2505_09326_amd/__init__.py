@@ -18,7 +18,8 @@ SPHATTN_FP8QK_BF16V = 2
 
 _DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN_FP8QK_BF16V}
 
-EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_softmax_fwd", "sphattn_strerror", "sphattn_version")
+EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_grn_fwd", "sphattn_softmax_fwd", "sphattn_strerror",
+                    "sphattn_version")
 
 _lib = None
 
@@ -43,6 +44,8 @@ def load_library() -> ctypes.CDLL:
             fn = getattr(lib, name)
             fn.restype = ip
             fn.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_grn_fwd.restype = ip
+        lib.sphattn_grn_fwd.argtypes = [vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, vp]
         lib.sphattn_strerror.restype = ctypes.c_char_p
         lib.sphattn_strerror.argtypes = [ip]
         lib.sphattn_version.restype = ip
@@ -94,6 +97,30 @@ def sphattn_fwd(Q, K, V, O=None, dtype="bf16", stream=None):
     if O is None:
         O = _alloc_out(Q, V, dtype)
     return _call("sphattn_fwd", Q, K, V, O, dtype, stream)
+
+
+def sphattn_grn_fwd(Q, K, V, mult=None, O=None, dtype="bf16", stream=None):
+    """Gene-regulatory-network variant: keys scaled by per-gene multiplicity mult[B,N] (fp32 or
+    None) and K, V of shape [B,H_kv,N,d] shared by groups of H/H_kv query heads."""
+    import torch
+    lib = load_library()
+    if O is None:
+        O = _alloc_out(Q, V, dtype)
+    tensors = (Q, K, V, O) + ((mult,) if mult is not None else ())
+    for t in tensors:
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("Q, K, V, O, mult must be contiguous device tensors")
+    if mult is not None and mult.dtype != torch.float32:
+        raise ValueError("mult must be float32")
+    B, H, N, d = Q.shape
+    if stream is None:
+        stream = torch.cuda.current_stream(Q.device).cuda_stream
+    rc = lib.sphattn_grn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                             mult.data_ptr() if mult is not None else None, O.data_ptr(),
+                             B, H, K.shape[1], N, d, _dtype_code(dtype), ctypes.c_void_p(stream))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return O
 
 
 def sphattn_softmax_fwd(Q, K, V, O=None, dtype="bf16", stream=None):

@@ -10,7 +10,7 @@ namespace {
 
 using namespace sphattn;
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 200;   // 0.2.0
 
 bool overlaps(const void* a, size_t an, const void* b, size_t bn)
 {
@@ -18,11 +18,11 @@ bool overlaps(const void* a, size_t an, const void* b, size_t bn)
     return a0 < b0 + bn && b0 < a0 + an;
 }
 
-int check_args(const void* Q, const void* K, const void* V, void* O,
-               int B, int H, int N, int d, int dtype, size_t* qk_bytes, size_t* vo_bytes)
+int check_args(const void* Q, const void* K, const void* V, void* O, const float* mult,
+               int B, int H, int H_kv, int N, int d, int dtype)
 {
     if (!Q || !K || !V || !O) return SPHATTN_ERR_NULL;
-    if (B <= 0 || H <= 0 || N <= 0) return SPHATTN_ERR_SHAPE;
+    if (B <= 0 || H <= 0 || N <= 0 || H_kv <= 0 || H % H_kv != 0) return SPHATTN_ERR_SHAPE;
     if (d != 64 && d != 128) return SPHATTN_ERR_HEAD_DIM;
     if (dtype != SPHATTN_F32 && dtype != SPHATTN_BF16 && dtype != SPHATTN_FP8QK_BF16V)
         return SPHATTN_ERR_DTYPE;
@@ -34,13 +34,13 @@ int check_args(const void* Q, const void* K, const void* V, void* O,
     // one head of one tensor is addressed through a 32-bit buffer range
     if ((unsigned __int128)N * d * 4 > 0x7fffffff) return SPHATTN_ERR_SHAPE;
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return SPHATTN_ERR_ALIGN;
-    size_t n = (size_t)elems;
-    size_t qk = dtype == SPHATTN_F32 ? 4 : dtype == SPHATTN_BF16 ? 2 : 1;
-    size_t vo = dtype == SPHATTN_F32 ? 4 : 2;
-    *qk_bytes = n * qk;
-    *vo_bytes = n * vo;
-    if (overlaps(O, *vo_bytes, Q, *qk_bytes) || overlaps(O, *vo_bytes, K, *qk_bytes) ||
-        overlaps(O, *vo_bytes, V, *vo_bytes))
+    if ((uintptr_t)mult & 3) return SPHATTN_ERR_ALIGN;
+    const size_t n = (size_t)elems, nkv = n / H * H_kv;
+    const size_t qk = dtype == SPHATTN_F32 ? 4 : dtype == SPHATTN_BF16 ? 2 : 1;
+    const size_t vo = dtype == SPHATTN_F32 ? 4 : 2;
+    if (overlaps(O, n * vo, Q, n * qk) || overlaps(O, n * vo, K, nkv * qk) ||
+        overlaps(O, n * vo, V, nkv * vo) ||
+        (mult && overlaps(O, n * vo, mult, (size_t)B * N * 4)))
         return SPHATTN_ERR_ALIAS;
     return SPHATTN_OK;
 }
@@ -56,57 +56,61 @@ bool raise_lds_limit(Kern kern, int lds_bytes)
     return true;
 }
 
-template <int D, int QB, QKType QKT, Norm NORM>
-int launch_pipelined(const void* Q, const void* K, const void* V, void* O,
-                     int B, int H, int N, hipStream_t stream)
+struct Problem {
+    const void* Q; const void* K; const void* V; void* O; const float* mult;
+    int B, H, H_kv, N;
+    hipStream_t stream;
+};
+
+template <int D, int QB, QKType QKT, Norm NORM, bool MULT>
+int launch_pipelined(const Problem& p)
 {
     constexpr int BR = kWaves * 32 * QB;
     constexpr int EQ = QKT == QKType::Fp8 ? 1 : 2;
     constexpr int lds_bytes = kNBuf * kBC * (D * EQ + kKPad + D * 2 + kVPad);
-    auto kern = fwd_pipelined_kernel<D, QB, QKT, NORM>;
+    auto kern = fwd_pipelined_kernel<D, QB, QKT, NORM, MULT>;
     static const bool configured = raise_lds_limit(kern, lds_bytes);   // once per process
     if (!configured) return SPHATTN_ERR_LAUNCH;
-    const int n_qtiles = (N + BR - 1) / BR;
-    const int n_wg = B * H * n_qtiles;
+    const int n_qtiles = (p.N + BR - 1) / BR;
+    const int n_wg = p.B * p.H * n_qtiles;
     const float scale_log2 = 1.4426950408889634f / __builtin_sqrtf((float)D);
-    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, stream,
-                       Q, K, (const __bf16*)V, (__bf16*)O, N, n_qtiles, n_wg, scale_log2);
+    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, p.stream,
+                       p.Q, p.K, (const __bf16*)p.V, (__bf16*)p.O, p.mult,
+                       p.N, p.H, p.H / p.H_kv, n_qtiles, n_wg, scale_log2);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
-template <int D>
-int launch_f32(const void* Q, const void* K, const void* V, void* O,
-               int B, int H, int N, hipStream_t stream)
+template <int D, bool MULT>
+int launch_f32(const Problem& p)
 {
     constexpr int BR = kWaves * 32;
     constexpr int lds_bytes = 2 * 2 * 32 * (D + 4) * 4;
-    auto kern = fwd_f32_kernel<D>;
+    auto kern = fwd_f32_kernel<D, MULT>;
     static const bool configured = raise_lds_limit(kern, lds_bytes);
     if (!configured) return SPHATTN_ERR_LAUNCH;
-    const int n_qtiles = (N + BR - 1) / BR;
-    const int n_wg = B * H * n_qtiles;
-    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, stream,
-                       (const float*)Q, (const float*)K, (const float*)V, (float*)O,
-                       N, n_qtiles, n_wg);
+    const int n_qtiles = (p.N + BR - 1) / BR;
+    const int n_wg = p.B * p.H * n_qtiles;
+    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, p.stream,
+                       (const float*)p.Q, (const float*)p.K, (const float*)p.V, (float*)p.O, p.mult,
+                       p.N, p.H, p.H / p.H_kv, n_qtiles, n_wg);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
-template <Norm NORM>
-int dispatch(const void* Q, const void* K, const void* V, void* O,
-             int B, int H, int N, int d, int dtype, hipStream_t stream)
+template <Norm NORM, bool MULT>
+int dispatch(const Problem& p, int d, int dtype)
 {
     if (dtype == SPHATTN_BF16) {
-        if (d == 128) return launch_pipelined<128, 2, QKType::Bf16, NORM>(Q, K, V, O, B, H, N, stream);
-        return launch_pipelined<64, 2, QKType::Bf16, NORM>(Q, K, V, O, B, H, N, stream);
+        if (d == 128) return launch_pipelined<128, 2, QKType::Bf16, NORM, MULT>(p);
+        return launch_pipelined<64, 2, QKType::Bf16, NORM, MULT>(p);
     }
     if constexpr (NORM == Norm::Spherical) {
         if (dtype == SPHATTN_FP8QK_BF16V) {
-            if (d == 128) return launch_pipelined<128, 2, QKType::Fp8, NORM>(Q, K, V, O, B, H, N, stream);
-            return launch_pipelined<64, 2, QKType::Fp8, NORM>(Q, K, V, O, B, H, N, stream);
+            if (d == 128) return launch_pipelined<128, 2, QKType::Fp8, NORM, MULT>(p);
+            return launch_pipelined<64, 2, QKType::Fp8, NORM, MULT>(p);
         }
         if (dtype == SPHATTN_F32) {
-            if (d == 128) return launch_f32<128>(Q, K, V, O, B, H, N, stream);
-            return launch_f32<64>(Q, K, V, O, B, H, N, stream);
+            if (d == 128) return launch_f32<128, MULT>(p);
+            return launch_f32<64, MULT>(p);
         }
     }
     return SPHATTN_ERR_DTYPE;
@@ -119,20 +123,30 @@ extern "C" {
 int sphattn_fwd(const void* Q, const void* K, const void* V, void* O,
                 int B, int H, int N, int d, int dtype, void* stream)
 {
-    size_t qk, vo;
-    int rc = check_args(Q, K, V, O, B, H, N, d, dtype, &qk, &vo);
+    const int rc = check_args(Q, K, V, O, nullptr, B, H, H, N, d, dtype);
     if (rc != SPHATTN_OK) return rc;
-    return dispatch<Norm::Spherical>(Q, K, V, O, B, H, N, d, dtype, (hipStream_t)stream);
+    const Problem p{Q, K, V, O, nullptr, B, H, H, N, (hipStream_t)stream};
+    return dispatch<Norm::Spherical, false>(p, d, dtype);
+}
+
+int sphattn_grn_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O,
+                    int B, int H, int H_kv, int N, int d, int dtype, void* stream)
+{
+    const int rc = check_args(Q, K, V, O, mult, B, H, H_kv, N, d, dtype);
+    if (rc != SPHATTN_OK) return rc;
+    const Problem p{Q, K, V, O, mult, B, H, H_kv, N, (hipStream_t)stream};
+    return mult ? dispatch<Norm::Spherical, true>(p, d, dtype)
+                : dispatch<Norm::Spherical, false>(p, d, dtype);
 }
 
 int sphattn_softmax_fwd(const void* Q, const void* K, const void* V, void* O,
                         int B, int H, int N, int d, int dtype, void* stream)
 {
-    size_t qk, vo;
-    int rc = check_args(Q, K, V, O, B, H, N, d, dtype, &qk, &vo);
+    const int rc = check_args(Q, K, V, O, nullptr, B, H, H, N, d, dtype);
     if (rc != SPHATTN_OK) return rc;
     if (dtype != SPHATTN_BF16) return SPHATTN_ERR_DTYPE;
-    return dispatch<Norm::Softmax>(Q, K, V, O, B, H, N, d, dtype, (hipStream_t)stream);
+    const Problem p{Q, K, V, O, nullptr, B, H, H, N, (hipStream_t)stream};
+    return dispatch<Norm::Softmax, false>(p, d, dtype);
 }
 
 const char* sphattn_strerror(int code)
@@ -140,7 +154,7 @@ const char* sphattn_strerror(int code)
     switch (code) {
     case SPHATTN_OK: return "success";
     case SPHATTN_ERR_NULL: return "a required pointer is NULL";
-    case SPHATTN_ERR_SHAPE: return "B, H and N must be positive and B*H*N*d must not overflow";
+    case SPHATTN_ERR_SHAPE: return "B, H, N must be positive, H_kv must divide H, and sizes must not overflow";
     case SPHATTN_ERR_HEAD_DIM: return "head dimension d must be 64 or 128";
     case SPHATTN_ERR_DTYPE: return "unsupported dtype for this entry point";
     case SPHATTN_ERR_ALIGN: return "Q, K, V and O must be 16-byte aligned";

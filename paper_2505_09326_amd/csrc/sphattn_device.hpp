@@ -135,11 +135,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 // zeros past the end of the head: a zero key contributes nothing to o or z, so
 // ragged N needs no masking in the spherical case.
 // ---------------------------------------------------------------------------
-template <int D, int QB, QKType QKT, Norm NORM>
+// Gene-regulatory-network options (paper, Section 3.1; Appendix A.2): MULT multiplies the
+// score of key j by that gene's multiplicity mult[b, j] (the key row scaled by a scalar, applied
+// to the fp32 score before it is squared and rounded); kv_group query heads share one K/V head.
+template <int D, int QB, QKType QKT, Norm NORM, bool MULT>
 __global__ __launch_bounds__(kThreads, 1)
 void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv,
                           const __bf16* __restrict__ V, __bf16* __restrict__ O,
-                          int N, int n_qtiles, int n_wg, float scale_log2)
+                          const float* __restrict__ mult,
+                          int N, int H, int kv_group, int n_qtiles, int n_wg, float scale_log2)
 {
     constexpr bool FP8 = QKT == QKType::Fp8;
     constexpr int BC = kBC;
@@ -165,6 +169,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     static_assert(NST <= SLOTS, "one staged chunk per slot of the second half");
     static_assert((2 * SLOTS) % RING == 0 && PD < RING && PD <= SLOTS, "ring indices must repeat");
     static_assert(!(FP8 && NORM == Norm::Softmax), "the SoftMax twin is bf16 only");
+    static_assert(!(MULT && NORM == Norm::Softmax), "multiplicities belong to the spherical variant");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
@@ -177,11 +182,16 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
     const int bh = lid / n_qtiles, qt = lid % n_qtiles;
     const size_t head_off = (size_t)bh * N * D;    // in elements
+    const int bidx = bh / H;
+    const size_t kv_off = (size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * N * D;
     const unsigned char* Qh = (const unsigned char*)Qv + head_off * EQ;
     __bf16* Oh = O + head_off;
     const __amdgpu_buffer_rsrc_t krs =
-        make_rsrc((const unsigned char*)Kv + head_off * EQ, (uint32_t)N * KROWB);
-    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(V + head_off, (uint32_t)N * VROWB);
+        make_rsrc((const unsigned char*)Kv + kv_off * EQ, (uint32_t)N * KROWB);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(V + kv_off, (uint32_t)N * VROWB);
+    // multiplicities of this cell; reads past key N return 0 (those keys are zero anyway)
+    const __amdgpu_buffer_rsrc_t mrs =
+        make_rsrc(MULT ? mult + (size_t)bidx * N : nullptr, MULT ? (uint32_t)N * 4 : 0);
     const int q0 = qt * BR + wave * 32 * QB;
 
     // ---- per-lane LDS byte offsets inside a tile; everything else is an immediate
@@ -240,6 +250,14 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         apend[qb] = anext[qb] = 1.f;
     }
 
+    // multipliers of the lane's 16 keys (8g + 4h + t) of a sub-step, double-buffered by parity
+    f32x4 mreg[MULT ? 2 : 1][4];
+    auto mload = [&](int par, int g, int substep) {
+        if constexpr (MULT)
+            mreg[par][g] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                mrs, (8 * g + 4 * h) * 4, substep * 128, 0));
+    };
+
     i32x4 stage[NST];
     auto gload_chunk = [&](int c, int tile) {
         if (c < LDK)
@@ -272,6 +290,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     for (int c = 0; c < NST; ++c) lstore_chunk(c, smem + BUF_BYTES);
 #pragma unroll
     for (int c = 0; c < NST; ++c) gload_chunk(c, 2);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) mload(0, g, 0);
     __syncthreads();
 
     f32x16 S0[QB], S1[QB];
@@ -422,7 +442,11 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                 for (int u = 0; u < PER; u += 2) {
                     const int idx = i * PER + u;
                     const int qb = idx / 16, r = idx % 16;
-                    const float a = Sc[qb][r], b = Sc[qb][r + 1];
+                    float a = Sc[qb][r], b = Sc[qb][r + 1];
+                    if constexpr (MULT) {
+                        a *= mreg[hf][r / 4][r % 4];
+                        b *= mreg[hf][r / 4][r % 4 + 1];
+                    }
                     zacc[qb][0] = __builtin_fmaf(a, a, zacc[qb][0]);
                     zacc[qb][1] = __builtin_fmaf(b, b, zacc[qb][1]);
                     const bf16x2 c2 = cvt2(a, b);
@@ -475,6 +499,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                     for (int qb = 0; qb < QB; ++qb) apend[qb] = anext[qb];
                 }
             }
+            if (MULT && i < 4) mload(hf ^ 1, i, 2 * j + hf + 1);
             // staging, second half only: tile j+2 into LDS, tile j+3 out of HBM/L2
             if (hf == 1 && i < NST) {
                 lstore_chunk(i, bnn);
@@ -557,11 +582,12 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
 // per 32 query rows, two LDS buffers, no further pipelining: this path serves
 // small fp32 problems where launch latency, not the matrix pipe, is the bound.
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, bool MULT>
 __global__ __launch_bounds__(kThreads, 1)
 void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                     const float* __restrict__ V, float* __restrict__ O,
-                    int N, int n_qtiles, int n_wg)
+                    const float* __restrict__ mult,
+                    int N, int H, int kv_group, int n_qtiles, int n_wg)
 {
     constexpr int BC = 32;
     constexpr int BR = kWaves * 32;
@@ -579,10 +605,13 @@ void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
     const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
     const int bh = lid / n_qtiles, qt = lid % n_qtiles;
     const size_t head_off = (size_t)bh * N * D;
+    const int bidx = bh / H;
+    const size_t kv_off = (size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * N * D;
     const float* Qh = Q + head_off;
-    const float* Kh = K + head_off;
-    const float* Vh = V + head_off;
+    const float* Kh = K + kv_off;
+    const float* Vh = V + kv_off;
     float* Oh = O + head_off;
+    const float* mrow = MULT ? mult + (size_t)bidx * N : nullptr;
     const int q0 = qt * BR + wave * 32;
 
     // Q as B operand of S^T = K Q^T: lane holds Q[q0 + l32][2kk + h]
@@ -642,6 +671,13 @@ void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
 #pragma unroll
         for (int kk = 0; kk < D / 2; ++kk)
             s = __builtin_amdgcn_mfma_f32_32x32x2f32(kb[l32 * ROWF + 2 * kk + h], qf[kk], s, 0, 0, 0);
+        if constexpr (MULT) {                    // s_ij = m_j (q_i . k_j); keys past N are zero
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = jt * BC + 8 * (r >> 2) + 4 * h + (r & 3);
+                s[r] *= key < N ? mrow[key] : 0.f;
+            }
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) z = __builtin_fmaf(s[r], s[r], z);
         // O^T (D x 32 queries) += V^T S^T: k-step r pairs key 8(r>>2) + 4h + (r&3) on both sides

@@ -67,6 +67,20 @@ def test_argument_errors_are_reported_before_any_launch(lib, fn):
     assert _call(lib, fn, O=0x2000000 + 128 * 128 * 2 - 16) == -7  # O overlaps the end of K
 
 
+def test_grn_entry_argument_errors(lib):
+    def call(Q=0x1000, K=0x2000000, V=0x4000000, mult=0x8000000, O=0x6000000,
+             B=1, H=4, H_kv=2, N=128, d=128, dtype=1):
+        return lib.sphattn_grn_fwd(ctypes.c_void_p(Q), ctypes.c_void_p(K), ctypes.c_void_p(V),
+                                   ctypes.c_void_p(mult), ctypes.c_void_p(O), B, H, H_kv, N, d, dtype, None)
+    assert call(K=0) == -1
+    assert call(H_kv=3) == -2
+    assert call(H_kv=0) == -2
+    assert call(d=32) == -3
+    assert call(dtype=7) == -4
+    assert call(mult=0x8000002) == -5
+    assert call(O=0x8000000) == -7            # O is mult
+
+
 def test_softmax_twin_is_bf16_only(lib):
     assert _call(lib, "sphattn_softmax_fwd", dtype=0) == -4
     assert _call(lib, "sphattn_softmax_fwd", dtype=2) == -4

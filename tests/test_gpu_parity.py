@@ -211,3 +211,92 @@ def test_softmax_twin_parity(pkg, oracle, B, H, N, d):
     bits, kinds = _kinds(q, k, v)
     ref = oracle.softmax_attention(*bits, kinds=kinds)
     assert _rel_err(got, ref) <= TOL["bf16"]
+
+
+# ---------------------------------------------------------------- GRN variant (Section 3.1)
+def _multiplicities(B, N, seed):
+    """Gene counts of a cell: mostly small integers, some zeros (genes that are absent)."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return torch.poisson(torch.full((B, N), 1.5), generator=g).to(torch.float32)
+
+
+def _gpu_grn(pkg, q, k, v, mult, dtype):
+    dev = torch.device("cuda:0")
+    out = pkg.sphattn_grn_fwd(q.to(dev), k.to(dev), v.to(dev),
+                              mult.to(dev) if mult is not None else None, dtype=dtype)
+    torch.cuda.synchronize()
+    return out.cpu()
+
+
+GRN_CASES = [
+    # B, H, H_kv, N, d, dtype, with multiplicities
+    (1, 2, 2, 257, 128, "bf16", True), (2, 4, 2, 300, 64, "bf16", True), (1, 6, 1, 1030, 128, "bf16", True),
+    (2, 4, 1, 515, 128, "bf16", False), (1, 4, 2, 333, 128, "fp8qk_bf16v", True),
+    (2, 2, 1, 200, 64, "fp8qk_bf16v", True), (1, 4, 2, 131, 64, "f32", True), (1, 2, 2, 77, 128, "f32", True),
+    (1, 3, 3, 1, 64, "bf16", True),
+]
+
+
+@pytest.mark.parametrize("B,H,H_kv,N,d,dtype,with_mult", GRN_CASES)
+def test_grn_variant_parity(pkg, oracle, B, H, H_kv, N, d, dtype, with_mult):
+    """Per-key multiplicities and grouped K/V heads, element by element (ragged N, N % 4 != 0)."""
+    print(f"case grn B={B} H={H} H_kv={H_kv} N={N} d={d} {dtype} mult={with_mult}", flush=True)
+    q, _, _ = si.make_qkv(B, H, N, d, dtype, seed=500 + N)
+    _, k, v = si.make_qkv(B, H_kv, N, d, dtype, seed=600 + N)
+    mult = _multiplicities(B, N, 700 + N) if with_mult else None
+    if mult is not None:
+        mult[:, 0] = 2.0                                  # never an all-zero row of scores
+    got = _gpu_grn(pkg, q, k, v, mult, dtype).to(torch.float64).numpy()
+    (qb, qk), (kb, kk), (vb, vk) = (si.storage_bits(t) for t in (q, k, v))
+    ref = oracle.grn_attention(qb, kb, vb, mult.numpy() if mult is not None else None, kinds=(qk, kk, vk))
+    assert np.all(np.isfinite(got))
+    err = _rel_err(got, ref)
+    print(f"grn max|err|/rms={err:.3e}", flush=True)
+    assert err <= TOL[dtype]
+
+
+def test_grn_multiplicity_reads_stay_inside_the_tensor(pkg, oracle):
+    """N not a multiple of 4: the vector loads of the last multiplicities must not pick up what
+    lies behind the tensor (here NaNs)."""
+    dev = torch.device("cuda:0")
+    B, H, N, d = 2, 2, 203, 128
+    q, k, v = si.make_qkv(B, H, N, d, "bf16", seed=9)
+    mult = _multiplicities(B, N, 10)
+    mult[:, 0] = 1.0
+    buf = torch.full((B * N + 64,), float("nan"), dtype=torch.float32, device=dev)
+    buf[: B * N] = mult.reshape(-1).to(dev)
+    out = pkg.sphattn_grn_fwd(q.to(dev), k.to(dev), v.to(dev), buf[: B * N].view(B, N), dtype="bf16")
+    torch.cuda.synchronize()
+    got = out.cpu().to(torch.float64).numpy()
+    assert np.all(np.isfinite(got))
+    (qb, qk), (kb, kk), (vb, vk) = (si.storage_bits(t) for t in (q, k, v))
+    ref = oracle.grn_attention(qb, kb, vb, mult.numpy(), kinds=(qk, kk, vk))
+    assert _rel_err(got, ref) <= TOL["bf16"]
+
+
+def test_grn_without_options_equals_plain_call(pkg):
+    q, k, v = si.make_qkv(1, 2, 400, 128, "bf16", seed=11)
+    a = _gpu(pkg, q, k, v, "bf16")
+    b = _gpu_grn(pkg, q, k, v, None, "bf16")
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_grn_full_size_gene_sequence(pkg, oracle):
+    """C3-sized gene-token problem with 4 query heads per K/V head and Poisson multiplicities:
+    sampled rows against the oracle."""
+    B, H, H_kv, N, d = 2, 16, 4, 8192, 128
+    print("case grn full size", flush=True)
+    q, _, _ = si.make_qkv(B, H, N, d, "bf16", seed=21)
+    _, k, v = si.make_qkv(B, H_kv, N, d, "bf16", seed=22)
+    mult = _multiplicities(B, N, 23)
+    got = _gpu_grn(pkg, q, k, v, mult, "bf16").to(torch.float64).numpy()
+    (qb, qk), (kb, kk), (vb, vk) = (si.storage_bits(t) for t in (q, k, v))
+    rng = np.random.default_rng(24)
+    worst = 0.0
+    for bh in range(B * H):
+        b, h = divmod(bh, H)
+        rows = np.sort(rng.choice(N, size=48, replace=False)).astype(np.int32)
+        ref = oracle.grn_attention_rows(qb, kb, vb, mult.numpy(), bh, rows, kinds=(qk, kk, vk))
+        worst = max(worst, np.abs(got[b, h, rows] - ref).max() / np.sqrt((ref ** 2).mean()))
+    print(f"grn full size max|err|/rms={worst:.3e}", flush=True)
+    assert worst <= TOL["bf16"]
