@@ -280,16 +280,24 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         for (int i = tid; i < BUF_BYTES / 16; i += kThreads)
             *reinterpret_cast<SPH_LDS i32x4*>(smem + 3 * BUF_BYTES + i * 16) = zero4;
     }
+    {   // all three tiles are requested before the first is waited for: one memory latency
+        i32x4 first[2][NST];
 #pragma unroll
-    for (int c = 0; c < NST; ++c) gload_chunk(c, 0);
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int c = 0; c < NST; ++c) lstore_chunk(c, smem);
+            for (int c = 0; c < NST; ++c) { gload_chunk(c, t); first[t][c] = stage[c]; }
 #pragma unroll
-    for (int c = 0; c < NST; ++c) gload_chunk(c, 1);
+        for (int c = 0; c < NST; ++c) gload_chunk(c, 2);
 #pragma unroll
-    for (int c = 0; c < NST; ++c) lstore_chunk(c, smem + BUF_BYTES);
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int c = 0; c < NST; ++c) gload_chunk(c, 2);
+            for (int c = 0; c < NST; ++c) {
+                const i32x4 keep = stage[c];
+                stage[c] = first[t][c];
+                lstore_chunk(c, smem + t * BUF_BYTES);
+                stage[c] = keep;
+            }
+    }
 #pragma unroll
     for (int g = 0; g < 4; ++g) mload(0, g, 0);
     __syncthreads();
