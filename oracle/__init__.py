@@ -145,6 +145,19 @@ def softmax_attention(Q, K, V, kinds=None) -> np.ndarray:
     return _fwd(1, Q, K, V, kinds, False, False)[0]
 
 
+NORMALIZERS = {"l2": 0, "softmax": 1, "l1": 2, "sqrelu": 3}
+
+
+def normalized_attention(Q, K, V, normalizer: str, kinds=None) -> np.ndarray:
+    """Attention with the normalizer of Definition 2 named by `normalizer`:
+    "l2" (spherical), "softmax" (with 1/sqrt(d)), "l1" (x / sum|x|), "sqrelu" (relu(x)^2 / sum relu(x)^2)."""
+    return _fwd(NORMALIZERS[normalizer], Q, K, V, kinds, False, False)[0]
+
+
+def normalized_attention_rows(Q, K, V, normalizer: str, bh: int, rows, kinds=None) -> np.ndarray:
+    return _rows(NORMALIZERS[normalizer], Q, K, V, bh, rows, kinds)
+
+
 def _rows(mode, Q, K, V, bh, rows, kinds):
     kq, kk, kv = kinds if kinds is not None else (None, None, None)
     Q, kq = _prep(Q, kq)

@@ -157,9 +157,49 @@ static void softmax_row(const double *q, const double *Kh, const double *Vh,
         o[k] /= den;
 }
 
+/* Other normalizers of Definition 2, N(x)_i = a1(x_i) / b(sum_j a2(x_j)), as examples of
+ * Theorem 1 (any such normalizer gives a streamable attention):
+ *   mode 2  "L1":            a1(x) = x,            a2(x) = |x|,          b = id
+ *   mode 3  "squared ReLU":  a1(x) = max(x,0)^2,   a2(x) = max(x,0)^2,   b = id
+ * No score scale (both are homogeneous, so any positive scale cancels); a row whose
+ * aggregate is 0 gives 0. */
+static double norm_a1(int mode, double x)
+{
+    if (mode == 2) return x;
+    double r = x > 0.0 ? x : 0.0;
+    return r * r;
+}
+
+static double norm_a2(int mode, double x)
+{
+    if (mode == 2) return fabs(x);
+    double r = x > 0.0 ? x : 0.0;
+    return r * r;
+}
+
+static void normalized_row(int mode, const double *q, const double *Kh, const double *Vh,
+                           int N, int d, double *s, double *o)
+{
+    double z = 0.0;
+    for (int j = 0; j < N; ++j) {
+        double x = 0.0;
+        for (int k = 0; k < d; ++k)
+            x += q[k] * Kh[(size_t)j * d + k];
+        s[j] = norm_a1(mode, x);
+        z += norm_a2(mode, x);
+    }
+    for (int k = 0; k < d; ++k)
+        o[k] = 0.0;
+    for (int j = 0; j < N; ++j)
+        for (int k = 0; k < d; ++k)
+            o[k] += s[j] * Vh[(size_t)j * d + k];
+    for (int k = 0; k < d; ++k)
+        o[k] = (z > 0.0) ? o[k] / z : 0.0;          /* b = id */
+}
+
 /* ---- whole-tensor entry points ------------------------------------------ */
 
-/* mode 0 = spherical, 1 = softmax twin.
+/* mode 0 = spherical, 1 = softmax twin, 2 = L1, 3 = squared ReLU.
  * Q, K, V: [B,H,N,d] in the stored format named by q_kind/k_kind/v_kind.
  * O: [B,H,N,d] fp64.  W (may be NULL; spherical only): [B,H,N,N] weights.
  * Z (may be NULL; spherical only): [B,H,N] squared row norms.
@@ -171,7 +211,7 @@ int oracle_attention_fwd_grn(int mode, const void *Q, int q_kind, const void *K,
 {
     if (!Q || !K || !V || !O || B <= 0 || H <= 0 || H_kv <= 0 || H % H_kv || N <= 0 || d <= 0)
         return -1;
-    if (mode != 0 && mult)
+    if (mode < 0 || mode > 3 || (mode != 0 && mult))
         return -1;
     size_t head = (size_t)N * d;
     double *Kh = malloc(head * sizeof *Kh);
@@ -198,8 +238,10 @@ int oracle_attention_fwd_grn(int mode, const void *Q, int q_kind, const void *K,
                     if (mode == 0)
                         spherical_row(q, Kh, Vh, m, N, d, s, O + row * d,
                                       W ? W + row * N : NULL, Z ? Z + row : NULL);
-                    else
+                    else if (mode == 1)
                         softmax_row(q, Kh, Vh, N, d, s, O + row * d);
+                    else
+                        normalized_row(mode, q, Kh, Vh, N, d, s, O + row * d);
                 }
             }
             free(q);
@@ -227,7 +269,8 @@ int oracle_attention_rows_grn(int mode, const void *Q, int q_kind, const void *K
                               int B, int H, int H_kv, int N, int d, int bh, const int *rows, int n_rows)
 {
     if (!Q || !K || !V || !O_rows || !rows || B <= 0 || H <= 0 || H_kv <= 0 || H % H_kv ||
-        N <= 0 || d <= 0 || bh < 0 || bh >= B * H || n_rows < 0 || (mode != 0 && mult))
+        N <= 0 || d <= 0 || bh < 0 || bh >= B * H || n_rows < 0 || mode < 0 || mode > 3 ||
+        (mode != 0 && mult))
         return -1;
     for (int r = 0; r < n_rows; ++r)
         if (rows[r] < 0 || rows[r] >= N)
@@ -255,8 +298,10 @@ int oracle_attention_rows_grn(int mode, const void *Q, int q_kind, const void *K
                     oracle_widen(Q, q_kind, row * d, (size_t)d, q);
                     if (mode == 0)
                         spherical_row(q, Kh, Vh, m, N, d, s, O_rows + (size_t)r * d, NULL, NULL);
-                    else
+                    else if (mode == 1)
                         softmax_row(q, Kh, Vh, N, d, s, O_rows + (size_t)r * d);
+                    else
+                        normalized_row(mode, q, Kh, Vh, N, d, s, O_rows + (size_t)r * d);
                 }
             }
             free(q);

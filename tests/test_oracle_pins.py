@@ -330,3 +330,38 @@ def test_grn_uniform_multiplicity_cancels(oracle):
     Q, K, V = (_rand((1, 2, 17, 4), s) for s in (65, 66, 67))
     np.testing.assert_allclose(oracle.grn_attention(Q, K, V, np.full((1, 17), 7.0)),
                                oracle.spherical_attention(Q, K, V), rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- other normalizers (Theorem 1)
+@pytest.mark.parametrize("name", ["l1", "sqrelu"])
+def test_other_normalizers_against_numpy_definition(oracle, name):
+    """N(x)_i = a1(x_i) / b(sum a2(x_j)) written with numpy; scale invariance; rows entry."""
+    Q, K, V = (_rand((2, 2, 37, 6), s) for s in (70, 71, 72))
+    S = np.einsum("bhik,bhjk->bhij", Q, K)
+    if name == "l1":
+        W = S / np.abs(S).sum(-1, keepdims=True)
+        assert np.allclose(np.abs(W).sum(-1), 1.0)
+    else:
+        R = np.maximum(S, 0.0) ** 2
+        W = R / R.sum(-1, keepdims=True)
+        assert np.allclose(W.sum(-1), 1.0) and W.min() >= 0.0
+    want = np.matmul(W, V)
+    got = oracle.normalized_attention(Q, K, V, name)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(oracle.normalized_attention(3.0 * Q, 0.25 * K, V, name), got, rtol=1e-12, atol=1e-14)
+    rows = [0, 36, 5]
+    np.testing.assert_allclose(oracle.normalized_attention_rows(Q, K, V, name, 3, rows), want[1, 1, rows],
+                               rtol=1e-12, atol=1e-14)
+
+
+def test_normalizer_names_agree_with_the_dedicated_entries(oracle):
+    Q, K, V = (_rand((1, 2, 21, 4), s) for s in (73, 74, 75))
+    np.testing.assert_array_equal(oracle.normalized_attention(Q, K, V, "l2"), oracle.spherical_attention(Q, K, V))
+    np.testing.assert_array_equal(oracle.normalized_attention(Q, K, V, "softmax"), oracle.softmax_attention(Q, K, V))
+
+
+def test_sqrelu_row_without_positive_scores_is_zero(oracle):
+    Q = -np.abs(_rand((1, 1, 5, 3), 76))
+    K = np.abs(_rand((1, 1, 5, 3), 77))
+    V = _rand((1, 1, 5, 3), 78)
+    assert np.all(oracle.normalized_attention(Q, K, V, "sqrelu") == 0.0)
