@@ -42,8 +42,17 @@ enum {
     SPHATTN_ERR_DTYPE = -4,       /* dtype is not a sphattn_dtype value */
     SPHATTN_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned */
     SPHATTN_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch */
-    SPHATTN_ERR_ALIAS = -7        /* O overlaps Q, K or V */
+    SPHATTN_ERR_ALIAS = -7,       /* O overlaps Q, K or V (or mult) */
+    SPHATTN_ERR_NORMALIZER = -8   /* normalizer is not a sphattn_normalizer value */
 };
+
+/* Normalizers N(x)_i = a1(x_i) / b(sum_j a2(x_j)) (paper, Appendix A.1, Definition 2). */
+typedef enum {
+    SPHATTN_NORM_L2 = 0,      /* a1 = x,          a2 = x^2,        b = sqrt : spherical attention */
+    SPHATTN_NORM_SOFTMAX = 1, /* a1 = a2 = exp(x / sqrt(d)),       b = id   : standard attention  */
+    SPHATTN_NORM_L1 = 2,      /* a1 = x,          a2 = |x|,        b = id                          */
+    SPHATTN_NORM_SQRELU = 3   /* a1 = a2 = max(x,0)^2,             b = id                          */
+} sphattn_normalizer;
 
 /*
  * Spherical attention forward (paper, Section 3; Definition 2 and Lemma 1 of
@@ -78,6 +87,17 @@ int sphattn_fwd(const void* Q, const void* K, const void* V, void* O,
  */
 int sphattn_grn_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O,
                     int B, int H, int H_kv, int N, int d, int dtype, void* stream);
+
+/*
+ * Attention with any of the normalizers above in place of the SoftMax (paper, Theorem 1: every
+ * normalized contraction streams the same way; only the per-score functions and the tail
+ * change).  SPHATTN_NORM_L2 is sphattn_fwd, SPHATTN_NORM_SOFTMAX is sphattn_softmax_fwd.
+ * A row whose aggregate sum_j a2(s_ij) is 0 gives 0.  dtype must be SPHATTN_BF16 unless the
+ * normalizer is SPHATTN_NORM_L2.  Other arguments, layout, ownership and errors as sphattn_fwd;
+ * an unknown normalizer returns SPHATTN_ERR_NORMALIZER.
+ */
+int sphattn_normalized_fwd(const void* Q, const void* K, const void* V, void* O,
+                           int B, int H, int N, int d, int dtype, int normalizer, void* stream);
 
 /*
  * Comparison twin on the same tiling skeleton: standard SoftMax attention,

@@ -18,8 +18,10 @@ SPHATTN_FP8QK_BF16V = 2
 
 _DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN_FP8QK_BF16V}
 
-EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_grn_fwd", "sphattn_softmax_fwd", "sphattn_strerror",
-                    "sphattn_version")
+EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_grn_fwd", "sphattn_normalized_fwd", "sphattn_softmax_fwd",
+                    "sphattn_strerror", "sphattn_version")
+
+NORMALIZERS = {"l2": 0, "softmax": 1, "l1": 2, "sqrelu": 3}
 
 _lib = None
 
@@ -46,6 +48,8 @@ def load_library() -> ctypes.CDLL:
             fn.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, vp]
         lib.sphattn_grn_fwd.restype = ip
         lib.sphattn_grn_fwd.argtypes = [vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_normalized_fwd.restype = ip
+        lib.sphattn_normalized_fwd.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, vp]
         lib.sphattn_strerror.restype = ctypes.c_char_p
         lib.sphattn_strerror.argtypes = [ip]
         lib.sphattn_version.restype = ip
@@ -118,6 +122,26 @@ def sphattn_grn_fwd(Q, K, V, mult=None, O=None, dtype="bf16", stream=None):
     rc = lib.sphattn_grn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                              mult.data_ptr() if mult is not None else None, O.data_ptr(),
                              B, H, K.shape[1], N, d, _dtype_code(dtype), ctypes.c_void_p(stream))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return O
+
+
+def sphattn_normalized_fwd(Q, K, V, O=None, dtype="bf16", normalizer="l2", stream=None):
+    """Attention with the normalizer "l2", "softmax", "l1" or "sqrelu" in place of the SoftMax."""
+    import torch
+    lib = load_library()
+    if O is None:
+        O = _alloc_out(Q, V, dtype)
+    for t in (Q, K, V, O):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("Q, K, V, O must be contiguous device tensors")
+    B, H, N, d = Q.shape
+    if stream is None:
+        stream = torch.cuda.current_stream(Q.device).cuda_stream
+    code = NORMALIZERS[normalizer] if isinstance(normalizer, str) else int(normalizer)
+    rc = lib.sphattn_normalized_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                    B, H, N, d, _dtype_code(dtype), code, ctypes.c_void_p(stream))
     if rc != 0:
         raise SphattnError(rc, sphattn_strerror(rc))
     return O

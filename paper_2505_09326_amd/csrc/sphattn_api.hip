@@ -139,6 +139,22 @@ int sphattn_grn_fwd(const void* Q, const void* K, const void* V, const float* mu
                 : dispatch<Norm::Spherical, false>(p, d, dtype);
 }
 
+int sphattn_normalized_fwd(const void* Q, const void* K, const void* V, void* O,
+                           int B, int H, int N, int d, int dtype, int normalizer, void* stream)
+{
+    const int rc = check_args(Q, K, V, O, nullptr, B, H, H, N, d, dtype);
+    if (rc != SPHATTN_OK) return rc;
+    if (normalizer < SPHATTN_NORM_L2 || normalizer > SPHATTN_NORM_SQRELU) return SPHATTN_ERR_NORMALIZER;
+    if (normalizer != SPHATTN_NORM_L2 && dtype != SPHATTN_BF16) return SPHATTN_ERR_DTYPE;
+    const Problem p{Q, K, V, O, nullptr, B, H, H, N, (hipStream_t)stream};
+    switch (normalizer) {
+    case SPHATTN_NORM_L2: return dispatch<Norm::Spherical, false>(p, d, dtype);
+    case SPHATTN_NORM_SOFTMAX: return dispatch<Norm::Softmax, false>(p, d, dtype);
+    case SPHATTN_NORM_L1: return dispatch<Norm::L1, false>(p, d, dtype);
+    default: return dispatch<Norm::SqRelu, false>(p, d, dtype);
+    }
+}
+
 int sphattn_softmax_fwd(const void* Q, const void* K, const void* V, void* O,
                         int B, int H, int N, int d, int dtype, void* stream)
 {
@@ -160,6 +176,7 @@ const char* sphattn_strerror(int code)
     case SPHATTN_ERR_ALIGN: return "Q, K, V and O must be 16-byte aligned";
     case SPHATTN_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
     case SPHATTN_ERR_ALIAS: return "O must not overlap Q, K or V";
+    case SPHATTN_ERR_NORMALIZER: return "normalizer is not a sphattn_normalizer value";
     default: return "unknown sphattn error code";
     }
 }

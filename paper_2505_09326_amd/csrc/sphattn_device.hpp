@@ -43,7 +43,10 @@ constexpr int kXcds = 8;           // accelerator complex dies, each with its ow
 constexpr int kBC = 64;            // key rows per LDS tile
 constexpr int kNBuf = 4;           // LDS tile buffers in rotation
 
-enum class Norm { Spherical, Softmax };
+// Normalizers N(x)_i = a1(x_i) / b(sum_j a2(x_j)) of Appendix A.1, Definition 2:
+//   Spherical (x, x^2, sqrt)   Softmax (exp, exp, id; with running maximum)
+//   L1 (x, |x|, id)            SqRelu (relu(x)^2, relu(x)^2, id)
+enum class Norm { Spherical, Softmax, L1, SqRelu };
 enum class QKType { Bf16, Fp8 };
 
 // Workgroup ids are dealt round-robin to the 8 XCDs.  Remap so that each XCD
@@ -168,8 +171,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     static_assert(!FP8 || QB == 2, "fp8 slot plan is written for two query blocks");
     static_assert(NST <= SLOTS, "one staged chunk per slot of the second half");
     static_assert((2 * SLOTS) % RING == 0 && PD < RING && PD <= SLOTS, "ring indices must repeat");
-    static_assert(!(FP8 && NORM == Norm::Softmax), "the SoftMax twin is bf16 only");
-    static_assert(!(MULT && NORM == Norm::Softmax), "multiplicities belong to the spherical variant");
+    static_assert(!FP8 || NORM == Norm::Spherical, "only the spherical normalizer takes fp8 Q/K");
+    static_assert(!MULT || NORM == Norm::Spherical, "multiplicities belong to the spherical variant");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
@@ -445,7 +448,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             }
             // B: a slice of the current sub-step's scores, 16*QB/SLOTS registers per slot
             constexpr int PER = 16 * QB / SLOTS;
-            if constexpr (NORM == Norm::Spherical) {
+            if constexpr (NORM != Norm::Softmax) {
 #pragma unroll
                 for (int u = 0; u < PER; u += 2) {
                     const int idx = i * PER + u;
@@ -455,8 +458,20 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                         a *= mreg[hf][r / 4][r % 4];
                         b *= mreg[hf][r / 4][r % 4 + 1];
                     }
-                    zacc[qb][0] = __builtin_fmaf(a, a, zacc[qb][0]);
-                    zacc[qb][1] = __builtin_fmaf(b, b, zacc[qb][1]);
+                    if constexpr (NORM == Norm::Spherical) {        // a2 = x^2, a1 = x
+                        zacc[qb][0] = __builtin_fmaf(a, a, zacc[qb][0]);
+                        zacc[qb][1] = __builtin_fmaf(b, b, zacc[qb][1]);
+                    } else if constexpr (NORM == Norm::L1) {        // a2 = |x|, a1 = x
+                        zacc[qb][0] += __builtin_fabsf(a);
+                        zacc[qb][1] += __builtin_fabsf(b);
+                    } else {                                         // a1 = a2 = relu(x)^2
+                        a = fmaxf(a, 0.f);
+                        b = fmaxf(b, 0.f);
+                        a *= a;
+                        b *= b;
+                        zacc[qb][0] += a;
+                        zacc[qb][1] += b;
+                    }
                     const bf16x2 c2 = cvt2(a, b);
                     Pc[qb][r / 8][r % 8] = c2[0];
                     Pc[qb][r / 8][r % 8 + 1] = c2[1];
@@ -515,7 +530,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             }
             // issue order inside the slot: after each matrix instruction, one LDS read and a
             // few VALU instructions, so that the matrix pipe never waits on the issue port
-            if constexpr (NORM == Norm::Spherical) {
+            if constexpr (NORM != Norm::Softmax) {
                 constexpr int NM = FP8 ? QB + 1 : 2 * QB;
 #pragma unroll
                 for (int m = 0; m < NM; ++m) {
@@ -555,15 +570,18 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         }
     }
 
-    // ---- tail t(o, z) = o / b(z): spherical b = sqrt, SoftMax b = id
+    // ---- tail t(o, z) = o / b(z): spherical b = sqrt, the others b = id
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         float inv;
         if constexpr (NORM == Norm::Spherical) {
             const float z = sum_across_halves(zacc[qb][0] + zacc[qb][1]);
             inv = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
-        } else {
+        } else if constexpr (NORM == Norm::Softmax) {
             inv = 1.0f / sum_across_halves(zacc[qb][0]);
+        } else {
+            const float z = sum_across_halves(zacc[qb][0] + zacc[qb][1]);
+            inv = z > 0.f ? 1.0f / z : 0.f;
         }
         const int row = q0 + qb * 32 + l32;
         if (row < N) {

@@ -41,7 +41,7 @@ def test_header_symbols_are_exported(lib):
 def test_version_and_strerror(lib):
     assert lib.sphattn_version() >= 100
     assert lib.sphattn_strerror(0) == b"success"
-    for code in range(-7, 0):
+    for code in range(-8, 0):
         assert b"unknown" not in lib.sphattn_strerror(code)
     assert b"unknown" in lib.sphattn_strerror(-99)
 
@@ -79,6 +79,18 @@ def test_grn_entry_argument_errors(lib):
     assert call(dtype=7) == -4
     assert call(mult=0x8000002) == -5
     assert call(O=0x8000000) == -7            # O is mult
+
+
+def test_normalized_entry_argument_errors(lib):
+    def call(normalizer=0, dtype=1, d=128):
+        return lib.sphattn_normalized_fwd(ctypes.c_void_p(0x1000), ctypes.c_void_p(0x2000000),
+                                          ctypes.c_void_p(0x4000000), ctypes.c_void_p(0x6000000),
+                                          1, 1, 128, d, dtype, normalizer, None)
+    assert call(normalizer=4) == -8
+    assert call(normalizer=-1) == -8
+    assert call(normalizer=2, dtype=2) == -4       # fp8 Q/K only with the L2 normalizer
+    assert call(normalizer=3, dtype=0) == -4
+    assert call(d=100) == -3
 
 
 def test_softmax_twin_is_bf16_only(lib):
