@@ -93,6 +93,13 @@ def test_normalized_entry_argument_errors(lib):
     assert call(d=100) == -3
 
 
+def test_shape_limits_are_rejected_not_truncated(lib):
+    """One head of one tensor must fit a 32-bit buffer range: larger N is an error code."""
+    rc = lib.sphattn_fwd(ctypes.c_void_p(0x1000), ctypes.c_void_p(0x100000000), ctypes.c_void_p(0x200000000),
+                         ctypes.c_void_p(0x300000000), 1, 1, 5_000_000, 128, 1, None)
+    assert rc == -2
+
+
 def test_softmax_twin_is_bf16_only(lib):
     assert _call(lib, "sphattn_softmax_fwd", dtype=0) == -4
     assert _call(lib, "sphattn_softmax_fwd", dtype=2) == -4

@@ -328,3 +328,18 @@ def test_normalizer_family_parity(pkg, oracle, name, B, H, N, d):
         # arithmetic (bf16 weights, fp32 sums).
         rms = np.sqrt((ref ** 2).mean())
         assert np.abs(got - ref).max() <= 2.0 ** -9 * np.abs(ref).max() + 1e-2 * rms
+
+
+def test_one_long_head(pkg, oracle):
+    """A single long, ragged head (N = 70001, d = 64): 32-bit buffer ranges, many key tiles,
+    fewer workgroups than CUs.  Sampled rows against the oracle plus the Gram closed form."""
+    B, H, N, d = 1, 1, 70001, 64
+    print(f"case long head N={N}", flush=True)
+    q, k, v = si.make_qkv(B, H, N, d, "bf16", seed=31)
+    got = _gpu(pkg, q, k, v, "bf16").to(torch.float64).numpy()
+    bits, kinds = _kinds(q, k, v)
+    rows = np.sort(np.random.default_rng(32).choice(N, size=256, replace=False)).astype(np.int32)
+    rows[0], rows[-1] = 0, N - 1
+    ref = oracle.spherical_attention_rows(*bits, 0, rows, kinds)
+    assert np.abs(got[0, 0, rows] - ref).max() / np.sqrt((ref ** 2).mean()) <= TOL["bf16"]
+    assert _rel_err(got, _gram_reference(q, k, v)) <= TOL["bf16"]
