@@ -24,6 +24,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "fp8qk_bf16v": 1.0 / (0.5 / 5000.0 + 0.5 / 2500.0
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by the reading of a
 # 256 MiB device copy in the same run (see profiles/); workloads not profiled report null
 MEASURED_HBM_BYTES = {"C3": 268.6e6, "C5": 1208.0e6}
+HBM_PEAK_GBS = 8000.0
 
 
 def time_launches(fn, steps, warmup):
@@ -127,6 +128,17 @@ def main() -> int:
                      "frac": kern_tflops / peak, "traffic": MEASURED_HBM_BYTES.get(w.name),
                      "kernel_ms_avg": ms_kernel, "kernel_ms_median": per[len(per) // 2],
                      "kernel_ms_min": per[0]},
+    }
+
+    # short problems are bound by launch latency and occupancy, not by the matrix pipes: also
+    # state what the launch achieves against the HBM roofline (algorithmic bytes / time)
+    result["roofline"]["hbm_gbs_algorithmic"] = algo_bytes / (ms_kernel * 1e-3) / 1e9
+    result["roofline"]["hbm_peak_gbs"] = HBM_PEAK_GBS
+    # the paper's own figures, another machine: context only, never the baseline
+    result["paper_context"] = {
+        "hardware": "1x NVIDIA A100 SXM4 80GB, FP16, d=128, N multiple of 13824",
+        "tflops": 200.0, "fraction_of_fp16_tensor_peak": 0.64,
+        "vs_unfused_pytorch": 3.6, "vs_flashattention2": "within 5% at N=41.5K",
     }
 
     if not args.no_twin and w.dtype == "bf16":
