@@ -15,7 +15,8 @@
  * pair (o, z) per query row (Lemma 1), never materialising the N x N scores.
  *
  * All pointers are DEVICE pointers owned by the caller.  The library allocates
- * nothing, keeps no state and is re-entrant.  Work is enqueued on `stream`
+ * nothing, keeps no state between calls (beyond a once-per-device kernel attribute) and is
+ * re-entrant.  Work is enqueued on `stream`
  * (a hipStream_t passed as void*; NULL is the default stream) and the call
  * returns without synchronising.
  */

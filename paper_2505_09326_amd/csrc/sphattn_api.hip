@@ -5,6 +5,9 @@
 #include "../../include/sphattn.h"
 
 #include <stdint.h>
+#include <stdlib.h>
+
+#include <atomic>
 
 namespace {
 
@@ -45,14 +48,24 @@ int check_args(const void* Q, const void* K, const void* V, void* O, const float
     return SPHATTN_OK;
 }
 
+// Kernels that use more than 64 KB of LDS need their limit raised once per device; `done` is
+// that kernel's bit mask of devices already configured (the only state the library keeps).
 template <typename Kern>
-bool raise_lds_limit(Kern kern, int lds_bytes)
+bool raise_lds_limit(Kern kern, int lds_bytes, std::atomic<uint64_t>& done)
 {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return false;
+    }
+    const uint64_t bit = 1ull << dev;
+    if (done.load(std::memory_order_acquire) & bit) return true;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                             lds_bytes) != hipSuccess) {
         (void)hipGetLastError();
         return false;
     }
+    done.fetch_or(bit, std::memory_order_release);
     return true;
 }
 
@@ -69,8 +82,8 @@ int launch_pipelined(const Problem& p)
     constexpr int EQ = QKT == QKType::Fp8 ? 1 : 2;
     constexpr int lds_bytes = kNBuf * kBC * (D * EQ + kKPad + D * 2 + kVPad);
     auto kern = fwd_pipelined_kernel<D, QB, QKT, NORM, MULT>;
-    static const bool configured = raise_lds_limit(kern, lds_bytes);   // once per process
-    if (!configured) return SPHATTN_ERR_LAUNCH;
+    static std::atomic<uint64_t> done{0};
+    if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;
     const int n_qtiles = (p.N + BR - 1) / BR;
     const int n_wg = p.B * p.H * n_qtiles;
     const float scale_log2 = 1.4426950408889634f / __builtin_sqrtf((float)D);
@@ -86,8 +99,8 @@ int launch_f32(const Problem& p)
     constexpr int BR = kWaves * 32;
     constexpr int lds_bytes = 2 * 2 * 32 * (D + 4) * 4;
     auto kern = fwd_f32_kernel<D, MULT>;
-    static const bool configured = raise_lds_limit(kern, lds_bytes);
-    if (!configured) return SPHATTN_ERR_LAUNCH;
+    static std::atomic<uint64_t> done{0};
+    if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;
     const int n_qtiles = (p.N + BR - 1) / BR;
     const int n_wg = p.B * p.H * n_qtiles;
     hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, p.stream,
@@ -96,10 +109,31 @@ int launch_f32(const Problem& p)
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
+// Query rows per workgroup: 256 (64 per wave) is the efficient shape; 128 (32 per wave) reads
+// K/V fragments twice as often per flop (measured 15-25 % slower per row) but doubles the
+// number of workgroups.  It pays when 256-row tiles would leave CUs without any workgroup
+// (measured: B=H=1, N=32768, d=128: 0.46 ms against 0.57 ms); partly filled last rounds do
+// not justify it, because the part is power-bound and idle CUs give their share to the rest.
+bool narrow_tiles_pay(const Problem& p)
+{
+    if (const char* e = getenv("SPHATTN_TILE_ROWS")) {
+        if (e[0] == '1' && e[1] == '2' && e[2] == '8' && !e[3]) return true;
+        if (e[0] == '2' && e[1] == '5' && e[2] == '6' && !e[3]) return false;
+    }
+    constexpr long long kCus = 256;
+    return (long long)p.B * p.H * ((p.N + 255) / 256) < kCus;
+}
+
 template <Norm NORM, bool MULT>
 int dispatch(const Problem& p, int d, int dtype)
 {
     if (dtype == SPHATTN_BF16) {
+        if constexpr (NORM == Norm::Spherical && !MULT) {
+            if (narrow_tiles_pay(p)) {
+                if (d == 128) return launch_pipelined<128, 1, QKType::Bf16, NORM, MULT>(p);
+                return launch_pipelined<64, 1, QKType::Bf16, NORM, MULT>(p);
+            }
+        }
         if (d == 128) return launch_pipelined<128, 2, QKType::Bf16, NORM, MULT>(p);
         return launch_pipelined<64, 2, QKType::Bf16, NORM, MULT>(p);
     }

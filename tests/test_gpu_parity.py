@@ -47,10 +47,13 @@ SMALL_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("tile_rows", ["128", "256"])
 @pytest.mark.parametrize("B,H,N,d", SMALL_SHAPES)
-def test_bf16_small_full_compare(pkg, oracle, B, H, N, d):
-    """Element-by-element over several query/key tiles and ragged tails."""
-    print(f"case bf16 B={B} H={H} N={N} d={d}", flush=True)
+def test_bf16_small_full_compare(pkg, oracle, monkeypatch, B, H, N, d, tile_rows):
+    """Element-by-element over several query/key tiles and ragged tails, for both workgroup
+    shapes (128 and 256 query rows) that the library chooses between."""
+    monkeypatch.setenv("SPHATTN_TILE_ROWS", tile_rows)
+    print(f"case bf16 B={B} H={H} N={N} d={d} tile_rows={tile_rows}", flush=True)
     q, k, v = si.make_qkv(B, H, N, d, "bf16", seed=100 + N + d)
     got = _gpu(pkg, q, k, v, "bf16").to(torch.float64).numpy()
     bits, kinds = _kinds(q, k, v)
