@@ -12,6 +12,7 @@ Stored formats understood for the inputs ("kind"):
     "f64", "f32"  -- numpy float64 / float32 arrays
     "bf16"        -- numpy uint16 arrays holding bfloat16 bit patterns
     "e4m3fn"      -- numpy uint8 arrays holding OCP E4M3 (finite-only) bytes
+    "f16"         -- numpy uint16 arrays holding IEEE binary16 bit patterns
 All are widened exactly to fp64 inside the C code.
 """
 from __future__ import annotations
@@ -26,8 +27,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sphattn_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle_sphattn.so")
 
-_KINDS = {"f64": 0, "f32": 1, "bf16": 2, "e4m3fn": 3}
-_KIND_DTYPES = {"f64": np.float64, "f32": np.float32, "bf16": np.uint16, "e4m3fn": np.uint8}
+_KINDS = {"f64": 0, "f32": 1, "bf16": 2, "e4m3fn": 3, "f16": 4}
+_KIND_DTYPES = {"f64": np.float64, "f32": np.float32, "bf16": np.uint16, "e4m3fn": np.uint8,
+                "f16": np.uint16}
 
 _lib = None
 

@@ -22,7 +22,7 @@
  * No score scale (1/sqrt(d) or other) is applied: any positive factor on the
  * scores cancels between numerator and sqrt(z).
  *
- * Inputs are taken exactly as stored (fp64, fp32, bf16 bit patterns or OCP
+ * Inputs are taken exactly as stored (fp64, fp32, bf16 or fp16 bit patterns, OCP
  * e4m3fn bytes) and widened exactly to fp64 before any arithmetic.  Layout is
  * dense row-major [B,H,N,d] with d contiguous.
  *
@@ -49,7 +49,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F64 = 0, ORACLE_F32 = 1, ORACLE_BF16 = 2, ORACLE_E4M3FN = 3 };
+enum { ORACLE_F64 = 0, ORACLE_F32 = 1, ORACLE_BF16 = 2, ORACLE_E4M3FN = 3, ORACLE_F16 = 4 };
 
 /* ---- exact widening of stored formats to fp64 --------------------------- */
 
@@ -80,6 +80,23 @@ static double widen_e4m3fn(uint8_t bits)
     return sign ? -v : v;
 }
 
+/* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 mantissa bits; exponent field 0 is
+ * subnormal (m * 2^-24), 31 is infinity (m == 0) or NaN. */
+static double widen_f16(uint16_t bits)
+{
+    int sign = bits >> 15;
+    int e = (bits >> 10) & 0x1F;
+    int m = bits & 0x3FF;
+    double v;
+    if (e == 0x1F)
+        v = m ? NAN : INFINITY;
+    else if (e == 0)
+        v = ldexp((double)m, -24);
+    else
+        v = ldexp(1.0 + (double)m / 1024.0, e - 15);
+    return sign ? -v : v;
+}
+
 static double load_elem(const void *p, int kind, size_t idx)
 {
     switch (kind) {
@@ -87,6 +104,7 @@ static double load_elem(const void *p, int kind, size_t idx)
     case ORACLE_F32: return (double)((const float *)p)[idx];
     case ORACLE_BF16: return widen_bf16(((const uint16_t *)p)[idx]);
     case ORACLE_E4M3FN: return widen_e4m3fn(((const uint8_t *)p)[idx]);
+    case ORACLE_F16: return widen_f16(((const uint16_t *)p)[idx]);
     default: return NAN;
     }
 }

@@ -10,7 +10,7 @@ sequence configurations.  Recipe, per workload index c:
     generator = torch.Generator('cpu').manual_seed(20250509 + c)
     Q, K, V   = randn([B,H,N,d]) in fp32, drawn in that order
     transform = optional constant factor, then the cast to the storage format
-                (bf16: round-to-nearest-even; e4m3fn: per-tensor factor
+                (bf16, fp16: round-to-nearest-even; e4m3fn: per-tensor factor
                 448/max|x|, clamp to +-448, round-to-nearest-even)
 """
 from __future__ import annotations
@@ -32,7 +32,7 @@ class Workload:
     H: int
     N: int
     d: int
-    dtype: str          # "f32" | "bf16" | "fp8qk_bf16v"
+    dtype: str          # "f32" | "bf16" | "f16" | "fp8qk_bf16v"
     factor: float = 1.0  # multiplies Q, K and V before the cast
 
     @property
@@ -55,6 +55,8 @@ WORKLOADS = {
     "C3": Workload("C3", 2, 2, 16, 8192, 128, "bf16"),
     "C4": Workload("C4", 3, 1, 8, 32768, 64, "bf16", factor=1.0 / 8.0),
     "C5": Workload("C5", 4, 4, 16, 16384, 128, "fp8qk_bf16v"),
+    # the paper's own benchmark point: FP16, d = 128, N = 3 x 13824 (B and H are not stated)
+    "P1": Workload("P1", 5, 1, 8, 41472, 128, "f16"),
 }
 
 
@@ -83,6 +85,8 @@ def cast_storage(q, k, v, dtype: str):
         return q, k, v
     if dtype == "bf16":
         return q.to(torch.bfloat16), k.to(torch.bfloat16), v.to(torch.bfloat16)
+    if dtype == "f16":
+        return q.to(torch.float16), k.to(torch.float16), v.to(torch.float16)
     if dtype == "fp8qk_bf16v":
         return to_e4m3fn(q), to_e4m3fn(k), v.to(torch.bfloat16)
     raise ValueError(f"unknown dtype {dtype!r}")
@@ -107,6 +111,8 @@ def storage_bits(t: torch.Tensor):
         return t.numpy(), "f64"
     if t.dtype == torch.bfloat16:
         return t.view(torch.int16).numpy().view(np.uint16), "bf16"
+    if t.dtype == torch.float16:
+        return t.view(torch.int16).numpy().view(np.uint16), "f16"
     if t.dtype == torch.float8_e4m3fn:
         return t.view(torch.uint8).numpy(), "e4m3fn"
     raise TypeError(f"unsupported storage dtype {t.dtype}")

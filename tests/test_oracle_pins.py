@@ -365,3 +365,15 @@ def test_sqrelu_row_without_positive_scores_is_zero(oracle):
     K = np.abs(_rand((1, 1, 5, 3), 77))
     V = _rand((1, 1, 5, 3), 78)
     assert np.all(oracle.normalized_attention(Q, K, V, "sqrelu") == 0.0)
+
+
+def test_f16_widening_all_codes(oracle):
+    """All 65536 binary16 codes against numpy's float16, plus landmarks of the format."""
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = oracle.widen(bits, "f16")
+    np.testing.assert_array_equal(np.isnan(got), np.isnan(want))
+    m = ~np.isnan(want)
+    np.testing.assert_array_equal(got[m], want[m])
+    assert got[0x3C00] == 1.0 and got[0x7BFF] == 65504.0 and got[0x0001] == 2.0 ** -24
+    assert got[0x7C00] == np.inf and got[0xFC00] == -np.inf
