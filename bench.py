@@ -20,7 +20,7 @@ if ROOT not in sys.path:
 
 # dense MFMA peaks of MI355X; the fp8-QK workload runs half its flops at the fp8 rate (5000)
 # and half at the bf16 rate (2500): harmonic mean
-PEAK_TFLOPS = {"bf16": 2500.0, "fp8qk_bf16v": 1.0 / (0.5 / 5000.0 + 0.5 / 2500.0), "f32": 157.3}
+PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "fp8qk_bf16v": 1.0 / (0.5 / 5000.0 + 0.5 / 2500.0), "f32": 157.3}
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by the reading of a
 # 256 MiB device copy in the same run (see profiles/); workloads not profiled report null
 MEASURED_HBM_BYTES = {"C3": 268.6e6, "C5": 1208.0e6}
@@ -76,7 +76,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C3", help="C1..C5 (default C3: the configuration the target is quoted on)")
+    ap.add_argument("--workload", default="C3", help="C1..C5, or P1 = the paper's own point (fp16, d=128, N=3x13824); "
+                         "default C3: the configuration the target is quoted on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-twin", action="store_true")
     ap.add_argument("--grn", type=int, default=0, metavar="H_KV",
@@ -100,7 +101,8 @@ def main() -> int:
     w, (q, k, v) = si.make_workload(args.workload)
     dev = torch.device("cuda:0")
     qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
-    out = torch.empty(qd.shape, dtype=torch.float32 if w.dtype == "f32" else torch.bfloat16, device=dev)
+    out_dt = {"f32": torch.float32, "f16": torch.float16}.get(w.dtype, torch.bfloat16)
+    out = torch.empty(qd.shape, dtype=out_dt, device=dev)
     torch.cuda.synchronize()
 
     def step():
@@ -112,7 +114,7 @@ def main() -> int:
     kern_tflops = w.flops / (ms_kernel * 1e-3) / 1e12
     peak = PEAK_TFLOPS[w.dtype]
 
-    elt_qk = {"f32": 4, "bf16": 2, "fp8qk_bf16v": 1}[w.dtype]
+    elt_qk = {"f32": 4, "bf16": 2, "f16": 2, "fp8qk_bf16v": 1}[w.dtype]
     elt_vo = 4 if w.dtype == "f32" else 2
     n_el = w.B * w.H * w.N * w.d
     algo_bytes = n_el * (2 * elt_qk + 2 * elt_vo)
@@ -121,7 +123,7 @@ def main() -> int:
         "metric": "spherical-attention fwd TFLOP/s (4*B*H*N^2*d)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_wall, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {"bf16": "bf16", "f32": "f32", "fp8qk_bf16v": "fp8"}[w.dtype], "data": "synthetic",
+        "dtype": {"bf16": "bf16", "f16": "f16", "f32": "f32", "fp8qk_bf16v": "fp8"}[w.dtype], "data": "synthetic",
         "config": {"workload": w.describe(), "B": w.B, "H": w.H, "N": w.N, "d": w.d,
                    "flop_per_step": w.flops, "min_hbm_bytes_per_step": algo_bytes},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": peak, "unit": "TFLOP/s",

@@ -31,7 +31,8 @@ extern "C" {
 typedef enum {
     SPHATTN_F32 = 0,         /* Q,K,V,O fp32, fp32 matrix-core arithmetic */
     SPHATTN_BF16 = 1,        /* Q,K,V,O bfloat16 */
-    SPHATTN_FP8QK_BF16V = 2  /* Q,K OCP E4M3 (finite-only) bytes; V,O bfloat16 */
+    SPHATTN_FP8QK_BF16V = 2, /* Q,K OCP E4M3 (finite-only) bytes; V,O bfloat16 */
+    SPHATTN_F16 = 3          /* Q,K,V,O IEEE half (the paper's precision); scores must stay below 65504 */
 } sphattn_dtype;
 
 /* Return codes. */

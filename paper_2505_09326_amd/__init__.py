@@ -15,8 +15,10 @@ from ._build import LIB_PATH, build_library
 SPHATTN_F32 = 0
 SPHATTN_BF16 = 1
 SPHATTN_FP8QK_BF16V = 2
+SPHATTN_F16 = 3
 
-_DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN_FP8QK_BF16V}
+_DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN_FP8QK_BF16V,
+                "f16": SPHATTN_F16}
 
 EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_grn_fwd", "sphattn_normalized_fwd", "sphattn_softmax_fwd",
                     "sphattn_strerror", "sphattn_version")
@@ -92,8 +94,8 @@ def _call(fn_name, Q, K, V, O, dtype, stream):
 def _alloc_out(Q, V, dtype):
     import torch
     code = _dtype_code(dtype)
-    return torch.empty(Q.shape, dtype=torch.float32 if code == SPHATTN_F32 else torch.bfloat16,
-                       device=Q.device)
+    dt = {SPHATTN_F32: torch.float32, SPHATTN_F16: torch.float16}.get(code, torch.bfloat16)
+    return torch.empty(Q.shape, dtype=dt, device=Q.device)
 
 
 def sphattn_fwd(Q, K, V, O=None, dtype="bf16", stream=None):

@@ -27,7 +27,8 @@ int check_args(const void* Q, const void* K, const void* V, void* O, const float
     if (!Q || !K || !V || !O) return SPHATTN_ERR_NULL;
     if (B <= 0 || H <= 0 || N <= 0 || H_kv <= 0 || H % H_kv != 0) return SPHATTN_ERR_SHAPE;
     if (d != 64 && d != 128) return SPHATTN_ERR_HEAD_DIM;
-    if (dtype != SPHATTN_F32 && dtype != SPHATTN_BF16 && dtype != SPHATTN_FP8QK_BF16V)
+    if (dtype != SPHATTN_F32 && dtype != SPHATTN_BF16 && dtype != SPHATTN_FP8QK_BF16V &&
+        dtype != SPHATTN_F16)
         return SPHATTN_ERR_DTYPE;
     // B*H*N*d elements must be addressable with 64-bit offsets and B*H*tiles with int
     unsigned __int128 elems = (unsigned __int128)B * H * (unsigned __int128)N * d;
@@ -39,7 +40,7 @@ int check_args(const void* Q, const void* K, const void* V, void* O, const float
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return SPHATTN_ERR_ALIGN;
     if ((uintptr_t)mult & 3) return SPHATTN_ERR_ALIGN;
     const size_t n = (size_t)elems, nkv = n / H * H_kv;
-    const size_t qk = dtype == SPHATTN_F32 ? 4 : dtype == SPHATTN_BF16 ? 2 : 1;
+    const size_t qk = dtype == SPHATTN_F32 ? 4 : dtype == SPHATTN_FP8QK_BF16V ? 1 : 2;
     const size_t vo = dtype == SPHATTN_F32 ? 4 : 2;
     if (overlaps(O, n * vo, Q, n * qk) || overlaps(O, n * vo, K, nkv * qk) ||
         overlaps(O, n * vo, V, nkv * vo) ||
@@ -88,7 +89,7 @@ int launch_pipelined(const Problem& p)
     const int n_wg = p.B * p.H * n_qtiles;
     const float scale_log2 = 1.4426950408889634f / __builtin_sqrtf((float)D);
     hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, p.stream,
-                       p.Q, p.K, (const __bf16*)p.V, (__bf16*)p.O, p.mult,
+                       p.Q, p.K, p.V, p.O, p.mult,
                        p.N, p.H, p.H / p.H_kv, n_qtiles, n_wg, scale_log2);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
@@ -138,6 +139,10 @@ int dispatch(const Problem& p, int d, int dtype)
         return launch_pipelined<64, 2, QKType::Bf16, NORM, MULT>(p);
     }
     if constexpr (NORM == Norm::Spherical) {
+        if (dtype == SPHATTN_F16) {
+            if (d == 128) return launch_pipelined<128, 2, QKType::F16, NORM, MULT>(p);
+            return launch_pipelined<64, 2, QKType::F16, NORM, MULT>(p);
+        }
         if (dtype == SPHATTN_FP8QK_BF16V) {
             if (d == 128) return launch_pipelined<128, 2, QKType::Fp8, NORM, MULT>(p);
             return launch_pipelined<64, 2, QKType::Fp8, NORM, MULT>(p);

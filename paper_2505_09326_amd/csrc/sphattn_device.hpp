@@ -34,6 +34,8 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 
 #define SPH_LDS __attribute__((address_space(3)))
 
@@ -47,7 +49,9 @@ constexpr int kNBuf = 4;           // LDS tile buffers in rotation
 //   Spherical (x, x^2, sqrt)   Softmax (exp, exp, id; with running maximum)
 //   L1 (x, |x|, id)            SqRelu (relu(x)^2, relu(x)^2, id)
 enum class Norm { Spherical, Softmax, L1, SqRelu };
-enum class QKType { Bf16, Fp8 };
+// Storage: Bf16 = Q,K,V,O bfloat16; Fp8 = Q,K OCP E4M3 with V,O bfloat16; F16 = Q,K,V,O IEEE half
+// (the paper's own precision).  The 16-bit type of V and O is also the type P is rounded to.
+enum class QKType { Bf16, Fp8, F16 };
 
 // Workgroup ids are dealt round-robin to the 8 XCDs.  Remap so that each XCD
 // works through a contiguous range of (head, query-tile) pairs: the query tiles
@@ -88,6 +92,25 @@ __device__ __forceinline__ bf16x2 cvt2(float a, float b)
     return __builtin_convertvector(v, bf16x2);   // v_cvt_pk_bf16_f32, round to nearest even
 }
 
+// Two fp32 values rounded (to nearest even) and packed into one register of the 16-bit type.
+template <bool HALF>
+__device__ __forceinline__ int pack2(float a, float b)
+{
+    f32x2 v = {a, b};
+    if constexpr (HALF) return __builtin_bit_cast(int, __builtin_convertvector(v, f16x2));   // v_cvt_pk_f16_f32
+    else return __builtin_bit_cast(int, __builtin_convertvector(v, bf16x2));                 // v_cvt_pk_bf16_f32
+}
+
+// D = A(32 x 16) B(16 x 32) + C on 16-bit operands held as 4 raw registers each.
+template <bool HALF>
+__device__ __forceinline__ f32x16 mfma16(i32x4 a, i32x4 b, f32x16 c)
+{
+    if constexpr (HALF)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
 // v_permlane32_swap exchanges the upper 32 lanes of its first operand with the lower 32 lanes
 // of its second.  Fed two copies of x it leaves x[lane & 31] in the first and
 // x[32 + (lane & 31)] in the second register of every lane: one instruction, no LDS traffic.
@@ -119,7 +142,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 }
 
 // ---------------------------------------------------------------------------
-// Software-pipelined forward kernel: bf16 V/O; Q/K in bf16 or OCP E4M3.
+// Software-pipelined forward kernel: 16-bit V/O (bf16 or fp16); Q/K in the same type or OCP E4M3.
 //
 // The key axis advances in sub-steps of 32 keys.  Three stages of three
 // consecutive sub-steps are in flight at once in every wavefront, so that the
@@ -144,11 +167,12 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 template <int D, int QB, QKType QKT, Norm NORM, bool MULT>
 __global__ __launch_bounds__(kThreads, 1)
 void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv,
-                          const __bf16* __restrict__ V, __bf16* __restrict__ O,
+                          const void* __restrict__ Vv, void* __restrict__ Ov,
                           const float* __restrict__ mult,
                           int N, int H, int kv_group, int n_qtiles, int n_wg, float scale_log2)
 {
     constexpr bool FP8 = QKT == QKType::Fp8;
+    constexpr bool HALF = QKT == QKType::F16;      // 16-bit type of V, O and P
     constexpr int BC = kBC;
     constexpr int BR = kWaves * 32 * QB;
     constexpr int EQ = FP8 ? 1 : 2;                // bytes per Q/K element
@@ -171,7 +195,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     static_assert(!FP8 || QB == 2, "fp8 slot plan is written for two query blocks");
     static_assert(NST <= SLOTS, "one staged chunk per slot of the second half");
     static_assert((2 * SLOTS) % RING == 0 && PD < RING && PD <= SLOTS, "ring indices must repeat");
-    static_assert(!FP8 || NORM == Norm::Spherical, "only the spherical normalizer takes fp8 Q/K");
+    static_assert(QKT == QKType::Bf16 || NORM == Norm::Spherical, "fp8 and fp16 storage: spherical only");
     static_assert(!MULT || NORM == Norm::Spherical, "multiplicities belong to the spherical variant");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -188,7 +212,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     const int bidx = bh / H;
     const size_t kv_off = (size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * N * D;
     const unsigned char* Qh = (const unsigned char*)Qv + head_off * EQ;
-    __bf16* Oh = O + head_off;
+    const unsigned short* V = (const unsigned short*)Vv;
+    unsigned short* Oh = (unsigned short*)Ov + head_off;
     const __amdgpu_buffer_rsrc_t krs =
         make_rsrc((const unsigned char*)Kv + kv_off * EQ, (uint32_t)N * KROWB);
     const __amdgpu_buffer_rsrc_t vrs = make_rsrc(V + kv_off, (uint32_t)N * VROWB);
@@ -306,23 +331,20 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     __syncthreads();
 
     f32x16 S0[QB], S1[QB];
-    bf16x8 P0[QB][2], P1[QB][2];
+    i32x4 P0[QB][2], P1[QB][2];                    // P of a sub-step: two B operands per query block
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) { S0[qb][r] = 0.f; S1[qb][r] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { P0[qb][ks][e] = (__bf16)0.f; P1[qb][ks][e] = (__bf16)0.f; }
+        for (int ks = 0; ks < 2; ++ks) { P0[qb][ks] = i32x4{0, 0, 0, 0}; P1[qb][ks] = i32x4{0, 0, 0, 0}; }
     }
 
     auto mfma_qk = [&](qfrag_t a, qfrag_t b, f32x16 c) -> f32x16 {
         if constexpr (FP8)
             return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
         else
-            return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                           __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+            return mfma16<HALF>(a, b, c);
     };
 
     // S0 = scores of sub-step 0
@@ -345,7 +367,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     // in the odd slots that follow; two sets alternate between consecutive sub-steps.
     i32x4 kf[FP8 ? 1 : RING];
     i32x4 kf8[FP8 ? 2 : 1][FP8 ? KSTEPS : 1][2];
-    bf16x8 vf[RING];
+    i32x4 vf[RING];
     // Reads for slot u of an iteration whose tiles j-1, j, j+1 sit at bprv, bcur, bnxt:
     //   u in [0,SLOTS)        first half : K_j sub 1,     V_{j-1} sub 1
     //   u in [SLOTS,2SLOTS)   second half: K_{j+1} sub 0, V_j sub 0
@@ -361,7 +383,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         const SPH_LDS unsigned char* a = vp + vlane + (16 * ks) * VSTR + db * 64;
         const bf16x4 lo = lds_read_tr64(a);
         const bf16x4 hi = lds_read_tr64(a + 8 * VSTR);
-        vf[u % RING] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        vf[u % RING] = __builtin_bit_cast(i32x4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         if constexpr (FP8) {
             const int kk = i / (2 * QB), part = i % (2 * QB);
             if (kk < KSTEPS && part < 2) kf8[hh & 1][kk][part] = lds_read_b128(kp + klane + 64 * kk + 16 * part);
@@ -384,8 +406,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             const int hf = s / SLOTS, i = s % SLOTS;
             f32x16 (&Sn)[QB] = hf == 0 ? S1 : S0;
             f32x16 (&Sc)[QB] = hf == 0 ? S0 : S1;
-            bf16x8 (&Pc)[QB][2] = hf == 0 ? P0 : P1;
-            bf16x8 (&Pp)[QB][2] = hf == 0 ? P1 : P0;
+            i32x4 (&Pc)[QB][2] = hf == 0 ? P0 : P1;
+            i32x4 (&Pp)[QB][2] = hf == 0 ? P1 : P0;
             __builtin_amdgcn_sched_barrier(0);
             // The one barrier per tile.  Tile j+1, written to LDS during the previous
             // iteration, becomes visible before its first read (the prefetch below); and
@@ -444,7 +466,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                 const int ks = i / DB, db = i % DB;
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb)
-                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s % RING], Pp[qb][ks], oacc[db][qb], 0, 0, 0);
+                    oacc[db][qb] = mfma16<HALF>(vf[s % RING], Pp[qb][ks], oacc[db][qb]);
             }
             // B: a slice of the current sub-step's scores, 16*QB/SLOTS registers per slot
             constexpr int PER = 16 * QB / SLOTS;
@@ -472,9 +494,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                         zacc[qb][0] += a;
                         zacc[qb][1] += b;
                     }
-                    const bf16x2 c2 = cvt2(a, b);
-                    Pc[qb][r / 8][r % 8] = c2[0];
-                    Pc[qb][r / 8][r % 8 + 1] = c2[1];
+                    Pc[qb][r / 8][(r % 8) / 2] = pack2<HALF>(a, b);
                 }
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb)     // keep the running sums where they were computed
@@ -510,9 +530,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                     const float a = __builtin_amdgcn_exp2f(__builtin_fmaf(Sc[qb][r], scale_log2, zacc[qb][1]));
                     const float b = __builtin_amdgcn_exp2f(__builtin_fmaf(Sc[qb][r + 1], scale_log2, zacc[qb][1]));
                     zacc[qb][0] += a + b;
-                    const bf16x2 c2 = cvt2(a, b);
-                    Pc[qb][r / 8][r % 8] = c2[0];
-                    Pc[qb][r / 8][r % 8 + 1] = c2[1];
+                    Pc[qb][r / 8][(r % 8) / 2] = pack2<HALF>(a, b);
                 }
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb)
@@ -563,10 +581,10 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             const SPH_LDS unsigned char* a = vp + vlane + (16 * ks) * VSTR + db * 64;
             const bf16x4 lo = lds_read_tr64(a);
             const bf16x4 hi = lds_read_tr64(a + 8 * VSTR);
-            const bf16x8 vfr = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            const i32x4 vfr = __builtin_bit_cast(i32x4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
-                oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr, P1[qb][ks], oacc[db][qb], 0, 0, 0);
+                oacc[db][qb] = mfma16<HALF>(vfr, P1[qb][ks], oacc[db][qb]);
         }
     }
 
@@ -585,15 +603,15 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         }
         const int row = q0 + qb * 32 + l32;
         if (row < N) {
-            __bf16* dst = Oh + (size_t)row * D + 4 * h;
+            unsigned short* dst = Oh + (size_t)row * D + 4 * h;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const bf16x2 a = cvt2(oacc[db][qb][4 * g] * inv, oacc[db][qb][4 * g + 1] * inv);
-                    const bf16x2 b = cvt2(oacc[db][qb][4 * g + 2] * inv, oacc[db][qb][4 * g + 3] * inv);
-                    const bf16x4 o4 = {a[0], a[1], b[0], b[1]};
-                    *reinterpret_cast<bf16x4*>(dst + db * 32 + 8 * g) = o4;
+                    typedef __attribute__((ext_vector_type(2))) int i32x2;
+                    const i32x2 o4 = {pack2<HALF>(oacc[db][qb][4 * g] * inv, oacc[db][qb][4 * g + 1] * inv),
+                                      pack2<HALF>(oacc[db][qb][4 * g + 2] * inv, oacc[db][qb][4 * g + 3] * inv)};
+                    *reinterpret_cast<i32x2*>(dst + db * 32 + 8 * g) = o4;
                 }
         }
     }

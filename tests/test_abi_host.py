@@ -90,6 +90,7 @@ def test_normalized_entry_argument_errors(lib):
     assert call(normalizer=-1) == -8
     assert call(normalizer=2, dtype=2) == -4       # fp8 Q/K only with the L2 normalizer
     assert call(normalizer=3, dtype=0) == -4
+    assert call(normalizer=1, dtype=3) == -4       # fp16 storage only with the L2 normalizer
     assert call(d=100) == -3
 
 
@@ -103,6 +104,7 @@ def test_shape_limits_are_rejected_not_truncated(lib):
 def test_softmax_twin_is_bf16_only(lib):
     assert _call(lib, "sphattn_softmax_fwd", dtype=0) == -4
     assert _call(lib, "sphattn_softmax_fwd", dtype=2) == -4
+    assert _call(lib, "sphattn_softmax_fwd", dtype=3) == -4
 
 
 def test_bench_refuses_more_than_one_gpu():
