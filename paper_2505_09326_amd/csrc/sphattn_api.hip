@@ -97,8 +97,8 @@ int launch_pipelined(const Problem& p)
 template <int D, bool MULT>
 int launch_f32(const Problem& p)
 {
-    constexpr int BR = kWaves * 32;
-    constexpr int lds_bytes = 2 * 2 * 32 * (D + 4) * 4;
+    constexpr int BR = 32;                         // the four waves split the key axis
+    constexpr int lds_bytes = kWaves * 2 * 32 * (D + 4) * 4;
     auto kern = fwd_f32_kernel<D, MULT>;
     static std::atomic<uint64_t> done{0};
     if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;

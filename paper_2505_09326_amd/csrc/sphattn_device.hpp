@@ -25,15 +25,12 @@
 namespace sphattn {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
-typedef __attribute__((ext_vector_type(8))) int i32x8;
-typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 
@@ -79,17 +76,16 @@ __device__ __forceinline__ i32x4 lds_read_b128(const SPH_LDS unsigned char* p)
     return *reinterpret_cast<const SPH_LDS i32x4*>(p);
 }
 
-__device__ __forceinline__ bf16x4 lds_read_tr64(const SPH_LDS unsigned char* p)
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+
+// ds_read_b64_tr_b16: each lane supplies the address of 4 consecutive 16-bit elements; within
+// every block of 16 lanes the 16 x 4 elements are transposed, so lane i receives element (i & 3)
+// of the pieces supplied by lanes (i >> 2), 4 + (i >> 2), 8 + (i >> 2), 12 + (i >> 2).
+__device__ __forceinline__ i32x2 lds_read_tr64(const SPH_LDS unsigned char* p)
 {
     s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
         (SPH_LDS s16x4*)const_cast<SPH_LDS unsigned char*>(p));
-    return __builtin_bit_cast(bf16x4, v);
-}
-
-__device__ __forceinline__ bf16x2 cvt2(float a, float b)
-{
-    f32x2 v = {a, b};
-    return __builtin_convertvector(v, bf16x2);   // v_cvt_pk_bf16_f32, round to nearest even
+    return __builtin_bit_cast(i32x2, v);
 }
 
 // Two fp32 values rounded (to nearest even) and packed into one register of the 16-bit type.
@@ -381,9 +377,9 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         // matrix instruction (which needs K) covers all three reads
         const int ks = i / DB, db = i % DB;
         const SPH_LDS unsigned char* a = vp + vlane + (16 * ks) * VSTR + db * 64;
-        const bf16x4 lo = lds_read_tr64(a);
-        const bf16x4 hi = lds_read_tr64(a + 8 * VSTR);
-        vf[u % RING] = __builtin_bit_cast(i32x4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        const i32x2 lo = lds_read_tr64(a);
+        const i32x2 hi = lds_read_tr64(a + 8 * VSTR);
+        vf[u % RING] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
         if constexpr (FP8) {
             const int kk = i / (2 * QB), part = i % (2 * QB);
             if (kk < KSTEPS && part < 2) kf8[hh & 1][kk][part] = lds_read_b128(kp + klane + 64 * kk + 16 * part);
@@ -579,9 +575,9 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         for (int i = 0; i < SLOTS; ++i) {
             const int ks = i / DB, db = i % DB;
             const SPH_LDS unsigned char* a = vp + vlane + (16 * ks) * VSTR + db * 64;
-            const bf16x4 lo = lds_read_tr64(a);
-            const bf16x4 hi = lds_read_tr64(a + 8 * VSTR);
-            const i32x4 vfr = __builtin_bit_cast(i32x4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            const i32x2 lo = lds_read_tr64(a);
+            const i32x2 hi = lds_read_tr64(a + 8 * VSTR);
+            const i32x4 vfr = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
                 oacc[db][qb] = mfma16<HALF>(vfr, P1[qb][ks], oacc[db][qb]);
@@ -608,7 +604,6 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    typedef __attribute__((ext_vector_type(2))) int i32x2;
                     const i32x2 o4 = {pack2<HALF>(oacc[db][qb][4 * g] * inv, oacc[db][qb][4 * g + 1] * inv),
                                       pack2<HALF>(oacc[db][qb][4 * g + 2] * inv, oacc[db][qb][4 * g + 3] * inv)};
                     *reinterpret_cast<i32x2*>(dst + db * 32 + 8 * g) = o4;
@@ -622,9 +617,15 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
 // Same mapping as above with k = 2 per instruction: lane l holds row/column
 // (l & 31) and k index (l >> 5), so accumulator register 4g+t of S^T (key
 // 8g + 4h + t) is directly the B operand of the k-step that pairs it with the
-// V row of that key; V needs no transpose (one scalar per lane).  One wavefront
-// per 32 query rows, two LDS buffers, no further pipelining: this path serves
-// small fp32 problems where launch latency, not the matrix pipe, is the bound.
+// V row of that key; V needs no transpose (one scalar per lane).
+//
+// fp32 problems are small and latency-bound, so the work is cut for parallelism
+// rather than for reuse: a workgroup owns 32 query rows, and its four wavefronts
+// split the KEY axis (wave w takes key tiles w, w+4, ...), each carrying its own
+// partial (o, z).  Lemma 1's accumulator is a plain sum, so the four partials are
+// simply added (through LDS) before the tail o / sqrt(z) is applied once.  Each
+// wave stages its tiles in a private LDS region; there is no workgroup barrier in
+// the loop.
 // ---------------------------------------------------------------------------
 template <int D, bool MULT>
 __global__ __launch_bounds__(kThreads, 1)
@@ -633,12 +634,13 @@ void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                     const float* __restrict__ mult,
                     int N, int H, int kv_group, int n_qtiles, int n_wg)
 {
-    constexpr int BC = 32;
-    constexpr int BR = kWaves * 32;
+    constexpr int BC = 32;                         // keys per tile
     constexpr int ROWF = D + 4;                    // padded row, in floats: conflict-free columns
     constexpr int TILE_F = BC * ROWF;
+    constexpr int WAVE_F = 2 * TILE_F;             // K tile then V tile, private to a wave
     constexpr int DB = D / 32;
-    constexpr int LD = BC * D / 4 / kThreads;      // float4 loads per thread per tensor per tile
+    constexpr int LD = BC * D / 4 / 64;            // float4 loads per lane per tensor per tile
+    static_assert(kWaves * (DB * 16 + 1) * 64 <= kWaves * WAVE_F, "partials fit the staging space");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     SPH_LDS float* smem = (SPH_LDS float*)smem_raw;
@@ -656,7 +658,7 @@ void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
     const float* Vh = V + kv_off;
     float* Oh = O + head_off;
     const float* mrow = MULT ? mult + (size_t)bidx * N : nullptr;
-    const int q0 = qt * BR + wave * 32;
+    const int q0 = qt * 32;
 
     // Q as B operand of S^T = K Q^T: lane holds Q[q0 + l32][2kk + h]
     float qf[D / 2];
@@ -673,11 +675,13 @@ void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
     float z = 0.f;
 
+    SPH_LDS float* kb = smem + wave * WAVE_F;
+    SPH_LDS float* vb = kb + TILE_F;
     f32x4 kreg[LD], vreg[LD];
     auto load_tile = [&](int j0) {
 #pragma unroll
         for (int i = 0; i < LD; ++i) {
-            const int id = tid + i * kThreads;
+            const int id = lane + i * 64;
             const int r = id / (D / 4), c = id % (D / 4);
             if (j0 + r < N) {
                 kreg[i] = *reinterpret_cast<const f32x4*>(Kh + (size_t)(j0 + r) * D + 4 * c);
@@ -688,26 +692,23 @@ void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
             }
         }
     };
-    auto store_tile = [&](int buf) {
-        SPH_LDS float* kb = smem + buf * 2 * TILE_F;
+    auto store_tile = [&]() {
 #pragma unroll
         for (int i = 0; i < LD; ++i) {
-            const int id = tid + i * kThreads;
+            const int id = lane + i * 64;
             const int r = id / (D / 4), c = id % (D / 4);
             *reinterpret_cast<SPH_LDS f32x4*>(kb + r * ROWF + 4 * c) = kreg[i];
-            *reinterpret_cast<SPH_LDS f32x4*>(kb + TILE_F + r * ROWF + 4 * c) = vreg[i];
+            *reinterpret_cast<SPH_LDS f32x4*>(vb + r * ROWF + 4 * c) = vreg[i];
         }
     };
 
     const int n_tiles = (N + BC - 1) / BC;
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-    for (int jt = 0; jt < n_tiles; ++jt) {
-        const int buf = jt & 1;
-        if (jt + 1 < n_tiles) load_tile((jt + 1) * BC);
-        const SPH_LDS float* kb = smem + buf * 2 * TILE_F;
-        const SPH_LDS float* vb = kb + TILE_F;
+    if (wave < n_tiles) load_tile(wave * BC);
+    for (int jt = wave; jt < n_tiles; jt += kWaves) {
+        // LDS executes one wave's operations in order: the reads of the previous tile are done
+        // before these writes land, and the reads below see them
+        store_tile();
+        if (jt + kWaves < n_tiles) load_tile((jt + kWaves) * BC);
         // S^T (32 keys x 32 queries)
         f32x16 s;
 #pragma unroll
@@ -732,23 +733,41 @@ void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
             for (int db = 0; db < DB; ++db)
                 oacc[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(vb[key * ROWF + db * 32 + l32], s[r], oacc[db], 0, 0, 0);
         }
-        if (jt + 1 < n_tiles) store_tile(buf ^ 1);
-        __syncthreads();
     }
 
-    const float zt = sum_across_halves(z);
-    const float inv = zt > 0.f ? 1.0f / __builtin_sqrtf(zt) : 0.f;
-    const int row = q0 + l32;
-    if (row < N) {
-        float* dst = Oh + (size_t)row * D + 4 * h;
+    // ---- add the four waves' partial (o, z): register r of block db of wave w at
+    // part[w][db*16 + r][lane], z at part[w][DB*16][lane]
+    __syncthreads();                               // every wave is done with its staging space
+    constexpr int PART = (DB * 16 + 1) * 64;
+    SPH_LDS float* part = smem;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4 o4 = {oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv,
-                                  oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv};
-                *reinterpret_cast<f32x4*>(dst + db * 32 + 8 * g) = o4;
+        for (int r = 0; r < 16; ++r) part[wave * PART + (db * 16 + r) * 64 + lane] = oacc[db][r];
+    part[wave * PART + DB * 16 * 64 + lane] = z;
+    __syncthreads();
+
+    // wave w finishes output block db = w (32 columns of the head dimension)
+    if (wave < DB) {
+        float zt = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) zt += part[w * PART + DB * 16 * 64 + lane];
+        zt = sum_across_halves(zt);
+        const float inv = zt > 0.f ? 1.0f / __builtin_sqrtf(zt) : 0.f;
+        const int row = q0 + l32;
+        float* dst = Oh + (size_t)row * D + wave * 32 + 4 * h;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            f32x4 o4;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float acc = 0.f;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) acc += part[w * PART + (wave * 16 + 4 * g + t) * 64 + lane];
+                o4[t] = acc * inv;
             }
+            if (row < N) *reinterpret_cast<f32x4*>(dst + 8 * g) = o4;
+        }
     }
 }
 
