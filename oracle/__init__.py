@@ -61,6 +61,8 @@ def _load():
                                                   ctypes.POINTER(ctypes.c_int), ip]
         lib.oracle_spherical_streamed.restype = ip
         lib.oracle_spherical_streamed.argtypes = [dp, dp, dp, dp, ip, ip, ip, ip, ip]
+        lib.oracle_spherical_accumulate.restype = ip
+        lib.oracle_spherical_accumulate.argtypes = [vp, ip, vp, ip, vp, ip, dp, dp, dp, ip, ip, ip, ip, ip, ip]
         lib.oracle_widen.restype = None
         lib.oracle_widen.argtypes = [vp, ip, ctypes.c_size_t, ctypes.c_size_t, dp]
         lib.oracle_num_threads.restype = ip
@@ -251,4 +253,38 @@ def grn_attention_rows(Q, K, V, mult, bh: int, rows, kinds=None) -> np.ndarray:
         rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), int(rows.size))
     if rc != 0:
         raise RuntimeError(f"oracle_attention_rows_grn failed with {rc}")
+    return out
+
+
+def spherical_accumulate(Q, K, V, mult=None, kinds=None):
+    """The accumulator of Lemma 1 without its tail: (o_raw [B,H,N_q,d], z [B,H,N_q]) of the
+    query rows Q [B,H,N_q,d] over the keys/values K, V [B,H_kv,N_k,d] (mult [B,N_k] or None)."""
+    kq, kk, kv = kinds if kinds is not None else (None, None, None)
+    Q, kq = _prep(Q, kq)
+    K, kk = _prep(K, kk)
+    V, kv = _prep(V, kv)
+    B, H, Nq, d = Q.shape
+    if K.shape != V.shape or K.shape[0] != B or K.shape[3] != d:
+        raise ValueError("K, V must be [B,H_kv,N_k,d]")
+    H_kv, Nk = K.shape[1], K.shape[2]
+    m = _prep_mult(mult, B, Nk)
+    o_raw = np.empty((B, H, Nq, d), dtype=np.float64)
+    z = np.empty((B, H, Nq), dtype=np.float64)
+    rc = _load().oracle_spherical_accumulate(
+        Q.ctypes.data_as(ctypes.c_void_p), _KINDS[kq], K.ctypes.data_as(ctypes.c_void_p), _KINDS[kk],
+        V.ctypes.data_as(ctypes.c_void_p), _KINDS[kv], _dptr(m) if m is not None else None,
+        _dptr(o_raw), _dptr(z), B, H, H_kv, Nq, Nk, d)
+    if rc != 0:
+        raise RuntimeError(f"oracle_spherical_accumulate failed with {rc}")
+    return o_raw, z
+
+
+def spherical_tail(o_parts, z_parts) -> np.ndarray:
+    """Lemma 1's tail on a sum of accumulators: t(sum_p o_p, sum_p z_p) = o / sqrt(z), 0 where
+    z = 0.  o_parts [P,B,H,N,d], z_parts [P,B,H,N] (fp64)."""
+    o = np.asarray(o_parts, dtype=np.float64).sum(axis=0)
+    z = np.asarray(z_parts, dtype=np.float64).sum(axis=0)
+    out = np.zeros_like(o)
+    nz = z > 0.0
+    out[nz] = o[nz] / np.sqrt(z[nz])[:, None]
     return out

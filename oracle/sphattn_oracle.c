@@ -39,7 +39,9 @@
  * inputs, unit-norm weight rows, Cauchy-Schwarz bound, scale/sign invariance,
  * linearity in V, N = 1 and orthonormal-key closed forms, the Gram-matrix
  * closed form, and chunk-size / permutation / zero-padding invariance of the
- * streamed accumulator of Lemma 1.
+ * streamed accumulator of Lemma 1.  The bare accumulator (no tail) is pinned by
+ * exact rationals, by the one-key closed form on a rectangular shape, and by
+ * additivity over key partitions followed by the tail against the direct form.
  */
 #include <math.h>
 #include <stdint.h>
@@ -380,6 +382,66 @@ int oracle_spherical_streamed(const double *Q, const double *K, const double *V,
     }
     free(o);
     return 0;
+}
+
+/* The accumulator of Lemma 1 over one set of keys, without the tail: for the N_q query rows
+ * of every head against the N_k keys and values given,
+ *     o_raw[b,h,i,:] = sum_j a1(s_ij) V[b,g,j,:] = sum_j s_ij V[b,g,j,:]
+ *     z[b,h,i]       = sum_j a2(s_ij)            = sum_j s_ij^2
+ * with s_ij = sum_k Q[b,h,i,k] * (m[b,j] * K[b,g,j,k]), g = h / (H / H_kv), m = 1 if mult is
+ * NULL.  Q: [B,H,N_q,d]; K, V: [B,H_kv,N_k,d]; mult: [B,N_k]; O_raw: [B,H,N_q,d]; Z: [B,H,N_q].
+ * The accumulators of disjoint key sets add up to the accumulator of their union, and
+ * t(o, z) = o / sqrt(z) of the total is the attention output. */
+int oracle_spherical_accumulate(const void *Q, int q_kind, const void *K, int k_kind,
+                                const void *V, int v_kind, const double *mult,
+                                double *O_raw, double *Z,
+                                int B, int H, int H_kv, int N_q, int N_k, int d)
+{
+    if (!Q || !K || !V || !O_raw || !Z || B <= 0 || H <= 0 || H_kv <= 0 || H % H_kv ||
+        N_q <= 0 || N_k <= 0 || d <= 0)
+        return -1;
+    size_t kv_head = (size_t)N_k * d;
+    double *Kh = malloc(kv_head * sizeof *Kh);
+    double *Vh = malloc(kv_head * sizeof *Vh);
+    int status = (Kh && Vh) ? 0 : -1;
+    for (int bh = 0; bh < B * H && status == 0; ++bh) {
+        const int b = bh / H, h = bh % H;
+        const size_t kvh = (size_t)b * H_kv + h / (H / H_kv);
+        const double *m = mult ? mult + (size_t)b * N_k : NULL;
+        oracle_widen(K, k_kind, kvh * kv_head, kv_head, Kh);
+        oracle_widen(V, v_kind, kvh * kv_head, kv_head, Vh);
+#pragma omp parallel
+        {
+            double *q = malloc((size_t)d * sizeof *q);
+            if (!q) {
+#pragma omp atomic write
+                status = -1;
+            } else {
+#pragma omp for schedule(static)
+                for (int i = 0; i < N_q; ++i) {
+                    size_t row = (size_t)bh * N_q + i;
+                    double *o = O_raw + row * d;
+                    double z = 0.0;
+                    oracle_widen(Q, q_kind, row * d, (size_t)d, q);
+                    for (int k = 0; k < d; ++k)
+                        o[k] = 0.0;
+                    for (int j = 0; j < N_k; ++j) {
+                        double x = 0.0;
+                        for (int k = 0; k < d; ++k)
+                            x += q[k] * (m ? m[j] * Kh[(size_t)j * d + k] : Kh[(size_t)j * d + k]);
+                        z += x * x;
+                        for (int k = 0; k < d; ++k)
+                            o[k] += x * Vh[(size_t)j * d + k];
+                    }
+                    Z[row] = z;
+                }
+            }
+            free(q);
+        }
+    }
+    free(Kh);
+    free(Vh);
+    return status;
 }
 
 int oracle_num_threads(void)

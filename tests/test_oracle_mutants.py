@@ -32,6 +32,10 @@ MUTANTS = [
     ("streamed loop forgets to carry z", "                z += dz;", "                z = dz;"),
     ("bf16 widened from the low half", "uint32_t u = (uint32_t)bits << 16;", "uint32_t u = (uint32_t)bits;"),
     ("e4m3 bias off by one", "v = ldexp(1.0 + (double)m / 8.0, e - 7);", "v = ldexp(1.0 + (double)m / 8.0, e - 8);"),
+    ("accumulator sums x instead of x^2", "    z += x * x;\n                        for", "    z += x;\n                        for"),
+    ("accumulator forgets the multiplicity", "x += q[k] * (m ? m[j] * Kh[(size_t)j * d + k] : Kh[(size_t)j * d + k]);\n                        z +=",
+     "x += q[k] * Kh[(size_t)j * d + k];\n                        z +="),
+    ("accumulator indexes K/V rows with N_q", "const double *m = mult ? mult + (size_t)b * N_k : NULL;", "const double *m = mult ? mult + (size_t)b * N_q : NULL;"),
     ("softmax without max shift and with wrong scale", "double c = 1.0 / sqrt((double)d);", "double c = 1.0 / (double)d;"),
 ]
 
@@ -70,6 +74,9 @@ def _pin_calls(o):
     for hh in [(4, 2), (6, 1)]:
         yield lambda a=hh: pins.test_grn_variant_against_numpy_definition(o, *a)
     yield lambda: pins.test_grn_multiplicity_brute_force_rationals(o)
+    yield lambda: pins.test_accumulator_brute_force_rationals_rectangular(o)
+    yield lambda: pins.test_accumulator_single_key_closed_form(o)
+    yield lambda: pins.test_accumulators_add_over_key_partitions_and_tail_gives_attention(o, (0, 16, 32, 37))
 
 
 @pytest.mark.parametrize("idx", range(len(MUTANTS)))

@@ -377,3 +377,60 @@ def test_f16_widening_all_codes(oracle):
     np.testing.assert_array_equal(got[m], want[m])
     assert got[0x3C00] == 1.0 and got[0x7BFF] == 65504.0 and got[0x0001] == 2.0 ** -24
     assert got[0x7C00] == np.inf and got[0xFC00] == -np.inf
+
+
+# ---------------------------------------------------------------- the bare accumulator of Lemma 1
+def test_accumulator_brute_force_rationals_rectangular(oracle):
+    """(o_raw, z) without the tail, N_q != N_k, two query heads sharing one K/V head, with
+    multiplicities: exact rationals.  Catches a wrong N in an index, a missing multiplicity,
+    a tail applied by mistake, z from |x| or from the unscaled score."""
+    rng = np.random.default_rng(90)
+    Nq, Nk, d = 3, 5, 2
+    Qi = rng.integers(-5, 6, size=(2, Nq, d))
+    Ki, Vi = rng.integers(-5, 6, size=(Nk, d)), rng.integers(-5, 6, size=(Nk, d))
+    m = [1, 3, 0, 2, 1]
+    o_raw, z = oracle.spherical_accumulate((Qi / 2.0).reshape(1, 2, Nq, d), Ki.astype(np.float64).reshape(1, 1, Nk, d),
+                                           (Vi / 4.0).reshape(1, 1, Nk, d), np.array([m], dtype=np.float64))
+    Kf = [[Fraction(int(x)) * m[j] for x in r] for j, r in enumerate(Ki)]
+    Vf = [[Fraction(int(x), 4) for x in r] for r in Vi]
+    for h in range(2):
+        Qf = [[Fraction(int(x), 2) for x in r] for r in Qi[h]]
+        want_o, want_z = _brute_force_exact(Qf, Kf, Vf)
+        for i in range(Nq):
+            assert z[0, h, i] == float(want_z[i])
+            for c in range(d):
+                assert o_raw[0, h, i, c] == float(want_o[i][c])
+
+
+def test_accumulator_single_key_closed_form(oracle):
+    """One key: o = (m q.k) v and z = (m q.k)^2, for any number of query rows."""
+    Q = _rand((2, 3, 7, 4), 91)
+    K, V = _rand((2, 3, 1, 4), 92), _rand((2, 3, 1, 4), 93)
+    m = np.array([[2.5], [0.5]])
+    o_raw, z = oracle.spherical_accumulate(Q, K, V, m)
+    s = np.einsum("bhik,bhk->bhi", Q, K[:, :, 0]) * m[:, None, :]
+    np.testing.assert_allclose(z, s * s, rtol=1e-14)
+    np.testing.assert_allclose(o_raw, s[..., None] * V[:, :, 0][:, :, None, :], rtol=1e-14)
+
+
+@pytest.mark.parametrize("cuts", [(0, 37), (0, 1, 37), (0, 16, 32, 37), (0, 5, 6, 30, 37)])
+def test_accumulators_add_over_key_partitions_and_tail_gives_attention(oracle, cuts):
+    """Lemma 1: the accumulators of the slices of any partition of the key axis add up, and the
+    tail of the sum is the attention output (pinned above by other means)."""
+    Q, K, V = _rand((2, 4, 37, 8), 94), _rand((2, 2, 37, 8), 95), _rand((2, 2, 37, 8), 96)
+    m = np.random.default_rng(97).uniform(0.5, 4.0, size=(2, 37))
+    parts = [oracle.spherical_accumulate(Q, K[:, :, a:b], V[:, :, a:b], m[:, a:b])
+             for a, b in zip(cuts[:-1], cuts[1:])]
+    O = oracle.spherical_tail(np.stack([p[0] for p in parts]), np.stack([p[1] for p in parts]))
+    np.testing.assert_allclose(O, _grn_numpy(Q, K, V, m, 2), rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(O, oracle.grn_attention(Q, K, V, m), rtol=1e-11, atol=1e-13)
+
+
+def test_tail_of_zero_accumulator_is_zero(oracle):
+    o = np.zeros((2, 1, 1, 3, 4))
+    z = np.zeros((2, 1, 1, 3))
+    o[0, 0, 0, 1], z[0, 0, 0, 1] = [3.0, 0.0, -4.0, 1.0], 4.0
+    out = oracle.spherical_tail(o, z)
+    np.testing.assert_array_equal(out[0, 0, 0], 0.0)
+    np.testing.assert_array_equal(out[0, 0, 2], 0.0)
+    np.testing.assert_array_equal(out[0, 0, 1], [1.5, 0.0, -2.0, 0.5])
