@@ -15,13 +15,16 @@
  * pair (o, z) per query row (Lemma 1), never materialising the N x N scores.
  *
  * All pointers are DEVICE pointers owned by the caller.  The library allocates
- * nothing, keeps no state between calls (beyond a once-per-device kernel attribute) and is
+ * nothing (the one entry point that needs scratch memory, sphattn_splitkv_fwd, takes it from
+ * the caller), keeps no state between calls (beyond a once-per-device kernel attribute) and is
  * re-entrant.  Work is enqueued on `stream`
  * (a hipStream_t passed as void*; NULL is the default stream) and the call
  * returns without synchronising.
  */
 #ifndef SPHATTN_H
 #define SPHATTN_H
+
+#include <stddef.h>
 
 #ifdef __cplusplus
 extern "C" {
@@ -45,7 +48,8 @@ enum {
     SPHATTN_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned */
     SPHATTN_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch */
     SPHATTN_ERR_ALIAS = -7,       /* O overlaps Q, K or V (or mult) */
-    SPHATTN_ERR_NORMALIZER = -8   /* normalizer is not a sphattn_normalizer value */
+    SPHATTN_ERR_NORMALIZER = -8,  /* normalizer is not a sphattn_normalizer value */
+    SPHATTN_ERR_WORKSPACE = -9    /* workspace NULL, not 16-byte aligned, or too small */
 };
 
 /* Normalizers N(x)_i = a1(x_i) / b(sum_j a2(x_j)) (paper, Appendix A.1, Definition 2). */
@@ -72,6 +76,17 @@ typedef enum {
  */
 int sphattn_fwd(const void* Q, const void* K, const void* V, void* O,
                 int B, int H, int N, int d, int dtype, void* stream);
+
+/*
+ * sphattn_fwd that also hands out the row aggregates of Definition 2:
+ *   Z : [B,H,N] fp32 device pointer (4-byte aligned), Z[b,h,i] = z_i = sum_j s_ij^2 as the
+ *       kernel accumulated it (fp32, from the fp32 scores); NULL: not written.  Must not overlap
+ *       any other argument.  O_i * sqrt(z_i) recovers the unnormalised row, which is what a
+ *       caller needs to merge results over key sets (Lemma 1) or to differentiate the tail.
+ * Everything else as sphattn_fwd.
+ */
+int sphattn_fwd_z(const void* Q, const void* K, const void* V, void* O, float* Z,
+                  int B, int H, int N, int d, int dtype, void* stream);
 
 /*
  * Gene-regulatory-network variant (paper, Section 3.1 and Appendix A.2).  Tokens are genes;
@@ -111,6 +126,71 @@ int sphattn_normalized_fwd(const void* Q, const void* K, const void* V, void* O,
  */
 int sphattn_softmax_fwd(const void* Q, const void* K, const void* V, void* O,
                         int B, int H, int N, int d, int dtype, void* stream);
+
+/*
+ * The accumulator of Lemma 1 (Appendix A.1) over one set of keys, WITHOUT the tail: for query
+ * rows Q[b,h,0..N_q) against the N_k keys/values given,
+ *
+ *     o_part[b,h,i,:] = sum_j s_ij * V[b,g,j,:]        z_part[b,h,i] = sum_j s_ij^2
+ *
+ * with s_ij as in sphattn_grn_fwd (mult NULL: all ones; H_kv == H: no sharing).  Because the
+ * accumulator of a concatenation of key sets is the sum of their accumulators, the caller may
+ * cut the key axis any way it likes (over calls, streams or GPUs), add the pairs, and apply
+ * the tail once with sphattn_combine.
+ *
+ *   Q              : [B,H,N_q,d];   K, V : [B,H_kv,N_k,d] in the format `dtype` names.
+ *   mult           : [B,N_k] fp32 or NULL.
+ *   o_part, z_part : [B,H,N_q,d] and [B,H,N_q] fp32 (16- and 4-byte aligned), written in full;
+ *                    must not overlap each other or the inputs.
+ * Errors as sphattn_fwd (SPHATTN_ERR_SHAPE also for N_q or N_k <= 0).
+ */
+int sphattn_partial_fwd(const void* Q, const void* K, const void* V, const float* mult,
+                        float* o_part, float* z_part,
+                        int B, int H, int H_kv, int N_q, int N_k, int d, int dtype, void* stream);
+
+/*
+ * Sum of n_parts accumulator pairs followed by the tail of Lemma 1:
+ *
+ *     z_i = sum_p z_parts[p][b,h,i]      O[b,h,i,:] = (sum_p o_parts[p][b,h,i,:]) / sqrt(z_i)
+ *
+ * (0 if z_i == 0).  The parts are added in ascending p, in fp32.
+ *   o_parts : [n_parts][B,H,N,d] fp32, contiguous;   z_parts : [n_parts][B,H,N] fp32.
+ *   O       : [B,H,N,d] in the OUTPUT type of `dtype` (fp32 for SPHATTN_F32, IEEE half for
+ *             SPHATTN_F16, bfloat16 otherwise);   Z : [B,H,N] fp32 or NULL, receives z_i.
+ *   n_parts : 1 .. 65536.
+ * Outputs must not overlap the parts.  Errors as sphattn_fwd.
+ */
+int sphattn_combine(const float* o_parts, const float* z_parts, int n_parts, void* O, float* Z,
+                    int B, int H, int N, int d, int dtype, void* stream);
+
+/*
+ * sphattn_grn_fwd with the key axis cut into n_splits slices that run as separate workgroups
+ * (sphattn_partial_fwd per slice, then sphattn_combine, in two launches).  It pays when
+ * B * H * N / 256 is below the number of compute units, i.e. few heads of moderate length.
+ *
+ *   n_splits       : slices asked for; 0 lets sphattn_splitkv_heuristic choose.  Slices are
+ *                    whole 64-key tiles of equal size, so fewer than asked may be used.
+ *   workspace      : device scratch, 16-byte aligned, at least
+ *                    sphattn_splitkv_workspace_bytes(B,H,N,d,n_splits) bytes (n_splits as passed
+ *                    here, or the heuristic's value when 0); contents undefined afterwards.
+ *                    Must not overlap any other argument; calls that overlap in time need
+ *                    workspaces of their own.
+ *   Z              : [B,H,N] fp32 or NULL, as in sphattn_fwd_z.
+ * Other arguments and errors as sphattn_grn_fwd; a bad workspace returns SPHATTN_ERR_WORKSPACE,
+ * n_splits < 0 returns SPHATTN_ERR_SHAPE.
+ */
+int sphattn_splitkv_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O, float* Z,
+                        int B, int H, int H_kv, int N, int d, int dtype, int n_splits,
+                        void* workspace, size_t workspace_size, void* stream);
+
+/* Bytes of workspace sphattn_splitkv_fwd needs for n_splits >= 1 slices: n_splits * B*H*N * (d+1)
+ * fp32 values, rounded up to 256.  Returns 0 for arguments sphattn_splitkv_fwd would reject. */
+size_t sphattn_splitkv_workspace_bytes(int B, int H, int N, int d, int n_splits);
+
+/* Number of slices sphattn_splitkv_fwd uses when asked for 0: 1 when whole-key-axis workgroups
+ * already cover the compute units, otherwise enough to cover them with slices of at least
+ * 8 tiles.  Host-only arithmetic. */
+int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype);
 
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* sphattn_strerror(int code);

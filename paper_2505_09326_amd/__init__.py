@@ -20,7 +20,9 @@ SPHATTN_F16 = 3
 _DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN_FP8QK_BF16V,
                 "f16": SPHATTN_F16}
 
-EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_grn_fwd", "sphattn_normalized_fwd", "sphattn_softmax_fwd",
+EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_fwd_z", "sphattn_grn_fwd", "sphattn_normalized_fwd",
+                    "sphattn_softmax_fwd", "sphattn_partial_fwd", "sphattn_combine", "sphattn_splitkv_fwd",
+                    "sphattn_splitkv_workspace_bytes", "sphattn_splitkv_heuristic",
                     "sphattn_strerror", "sphattn_version")
 
 NORMALIZERS = {"l2": 0, "softmax": 1, "l1": 2, "sqrelu": 3}
@@ -52,6 +54,19 @@ def load_library() -> ctypes.CDLL:
         lib.sphattn_grn_fwd.argtypes = [vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, vp]
         lib.sphattn_normalized_fwd.restype = ip
         lib.sphattn_normalized_fwd.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_fwd_z.restype = ip
+        lib.sphattn_fwd_z.argtypes = [vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_partial_fwd.restype = ip
+        lib.sphattn_partial_fwd.argtypes = [vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_combine.restype = ip
+        lib.sphattn_combine.argtypes = [vp, vp, ip, vp, vp, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_splitkv_fwd.restype = ip
+        lib.sphattn_splitkv_fwd.argtypes = [vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, ip,
+                                            vp, ctypes.c_size_t, vp]
+        lib.sphattn_splitkv_workspace_bytes.restype = ctypes.c_size_t
+        lib.sphattn_splitkv_workspace_bytes.argtypes = [ip, ip, ip, ip, ip]
+        lib.sphattn_splitkv_heuristic.restype = ip
+        lib.sphattn_splitkv_heuristic.argtypes = [ip, ip, ip, ip, ip]
         lib.sphattn_strerror.restype = ctypes.c_char_p
         lib.sphattn_strerror.argtypes = [ip]
         lib.sphattn_version.restype = ip
@@ -154,3 +169,96 @@ def sphattn_softmax_fwd(Q, K, V, O=None, dtype="bf16", stream=None):
     if O is None:
         O = _alloc_out(Q, V, dtype)
     return _call("sphattn_softmax_fwd", Q, K, V, O, dtype, stream)
+
+
+def _check_device(names, *tensors):
+    for t in tensors:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError(f"{names} must be contiguous device tensors")
+
+
+def _stream_of(t, stream):
+    import torch
+    return torch.cuda.current_stream(t.device).cuda_stream if stream is None else stream
+
+
+def _ptr(t):
+    return t.data_ptr() if t is not None else None
+
+
+def sphattn_fwd_z(Q, K, V, O=None, Z=None, dtype="bf16", stream=None):
+    """sphattn_fwd that also returns the row aggregates z_i = sum_j s_ij^2: (O, Z [B,H,N] fp32)."""
+    import torch
+    lib = load_library()
+    if O is None:
+        O = _alloc_out(Q, V, dtype)
+    if Z is None:
+        Z = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    _check_device("Q, K, V, O, Z", Q, K, V, O, Z)
+    B, H, N, d = Q.shape
+    rc = lib.sphattn_fwd_z(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), Z.data_ptr(),
+                           B, H, N, d, _dtype_code(dtype), ctypes.c_void_p(_stream_of(Q, stream)))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return O, Z
+
+
+def sphattn_partial_fwd(Q, K, V, mult=None, o_part=None, z_part=None, dtype="bf16", stream=None):
+    """Unnormalised accumulator pair of Q [B,H,N_q,d] over the keys K, V [B,H_kv,N_k,d]:
+    (o_part [B,H,N_q,d] fp32, z_part [B,H,N_q] fp32)."""
+    import torch
+    lib = load_library()
+    if o_part is None:
+        o_part = torch.empty(Q.shape, dtype=torch.float32, device=Q.device)
+    if z_part is None:
+        z_part = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    _check_device("Q, K, V, mult, o_part, z_part", Q, K, V, mult, o_part, z_part)
+    B, H, Nq, d = Q.shape
+    rc = lib.sphattn_partial_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(mult),
+                                 o_part.data_ptr(), z_part.data_ptr(), B, H, K.shape[1], Nq, K.shape[2], d,
+                                 _dtype_code(dtype), ctypes.c_void_p(_stream_of(Q, stream)))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return o_part, z_part
+
+
+def sphattn_combine(o_parts, z_parts, O=None, Z=None, dtype="bf16", stream=None):
+    """Tail of the summed accumulators: o_parts [P,B,H,N,d], z_parts [P,B,H,N] (fp32) -> O."""
+    import torch
+    lib = load_library()
+    P, B, H, N, d = o_parts.shape
+    if O is None:
+        code = _dtype_code(dtype)
+        dt = {SPHATTN_F32: torch.float32, SPHATTN_F16: torch.float16}.get(code, torch.bfloat16)
+        O = torch.empty((B, H, N, d), dtype=dt, device=o_parts.device)
+    _check_device("o_parts, z_parts, O, Z", o_parts, z_parts, O, Z)
+    rc = lib.sphattn_combine(o_parts.data_ptr(), z_parts.data_ptr(), P, O.data_ptr(), _ptr(Z),
+                             B, H, N, d, _dtype_code(dtype), ctypes.c_void_p(_stream_of(o_parts, stream)))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return O
+
+
+def sphattn_splitkv_workspace_bytes(B, H, N, d, n_splits) -> int:
+    return int(load_library().sphattn_splitkv_workspace_bytes(B, H, N, d, n_splits))
+
+
+def sphattn_splitkv_heuristic(B, H, N, d, dtype="bf16") -> int:
+    return int(load_library().sphattn_splitkv_heuristic(B, H, N, d, _dtype_code(dtype)))
+
+
+def sphattn_splitkv_fwd(Q, K, V, workspace, mult=None, O=None, Z=None, n_splits=0, dtype="bf16", stream=None):
+    """sphattn_grn_fwd with the key axis cut into n_splits slices (0: the library's choice);
+    `workspace` is a device byte tensor of at least sphattn_splitkv_workspace_bytes(...)."""
+    lib = load_library()
+    if O is None:
+        O = _alloc_out(Q, V, dtype)
+    _check_device("Q, K, V, mult, O, Z, workspace", Q, K, V, mult, O, Z, workspace)
+    B, H, N, d = Q.shape
+    rc = lib.sphattn_splitkv_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(mult), O.data_ptr(), _ptr(Z),
+                                 B, H, K.shape[1], N, d, _dtype_code(dtype), int(n_splits),
+                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                 ctypes.c_void_p(_stream_of(Q, stream)))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return O

@@ -13,7 +13,7 @@ namespace {
 
 using namespace sphattn;
 
-constexpr int kVersion = 200;   // 0.2.0
+constexpr int kVersion = 300;   // 0.3.0
 
 bool overlaps(const void* a, size_t an, const void* b, size_t bn)
 {
@@ -21,32 +21,49 @@ bool overlaps(const void* a, size_t an, const void* b, size_t bn)
     return a0 < b0 + bn && b0 < a0 + an;
 }
 
-int check_args(const void* Q, const void* K, const void* V, void* O, const float* mult,
-               int B, int H, int H_kv, int N, int d, int dtype)
+int check_shape(int B, int H, int H_kv, int Nq, int Nk, int d, int dtype)
 {
-    if (!Q || !K || !V || !O) return SPHATTN_ERR_NULL;
-    if (B <= 0 || H <= 0 || N <= 0 || H_kv <= 0 || H % H_kv != 0) return SPHATTN_ERR_SHAPE;
+    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || H_kv <= 0 || H % H_kv != 0) return SPHATTN_ERR_SHAPE;
     if (d != 64 && d != 128) return SPHATTN_ERR_HEAD_DIM;
     if (dtype != SPHATTN_F32 && dtype != SPHATTN_BF16 && dtype != SPHATTN_FP8QK_BF16V &&
         dtype != SPHATTN_F16)
         return SPHATTN_ERR_DTYPE;
+    const unsigned __int128 nmax = Nq > Nk ? Nq : Nk;
     // B*H*N*d elements must be addressable with 64-bit offsets and B*H*tiles with int
-    unsigned __int128 elems = (unsigned __int128)B * H * (unsigned __int128)N * d;
-    if (elems > ((unsigned __int128)1 << 40)) return SPHATTN_ERR_SHAPE;
-    if ((unsigned __int128)B * H * (((unsigned __int128)N + 127) / 128) > 0x7fffffff)
-        return SPHATTN_ERR_SHAPE;
+    if ((unsigned __int128)B * H * nmax * d > ((unsigned __int128)1 << 40)) return SPHATTN_ERR_SHAPE;
+    if ((unsigned __int128)B * H * ((nmax + 31) / 32) > 0x7fffffff) return SPHATTN_ERR_SHAPE;
     // one head of one tensor is addressed through a 32-bit buffer range
-    if ((unsigned __int128)N * d * 4 > 0x7fffffff) return SPHATTN_ERR_SHAPE;
-    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return SPHATTN_ERR_ALIGN;
-    if ((uintptr_t)mult & 3) return SPHATTN_ERR_ALIGN;
-    const size_t n = (size_t)elems, nkv = n / H * H_kv;
+    if (nmax * d * 4 > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    return SPHATTN_OK;
+}
+
+// `out` is what the call writes (out_bytes of it); it must not overlap anything the call reads.
+int check_args(const void* Q, const void* K, const void* V, const void* out, size_t out_bytes,
+               const float* mult, const float* Z,
+               int B, int H, int H_kv, int Nq, int Nk, int d, int dtype)
+{
+    if (!Q || !K || !V || !out) return SPHATTN_ERR_NULL;
+    const int rc = check_shape(B, H, H_kv, Nq, Nk, d, dtype);
+    if (rc != SPHATTN_OK) return rc;
+    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)out) & 15) return SPHATTN_ERR_ALIGN;
+    if (((uintptr_t)mult | (uintptr_t)Z) & 3) return SPHATTN_ERR_ALIGN;
+    const size_t nq = (size_t)B * H * Nq * d, nkv = (size_t)B * H_kv * Nk * d;
     const size_t qk = dtype == SPHATTN_F32 ? 4 : dtype == SPHATTN_FP8QK_BF16V ? 1 : 2;
     const size_t vo = dtype == SPHATTN_F32 ? 4 : 2;
-    if (overlaps(O, n * vo, Q, n * qk) || overlaps(O, n * vo, K, nkv * qk) ||
-        overlaps(O, n * vo, V, nkv * vo) ||
-        (mult && overlaps(O, n * vo, mult, (size_t)B * N * 4)))
+    const size_t zb = (size_t)B * H * Nq * 4;
+    if (overlaps(out, out_bytes, Q, nq * qk) || overlaps(out, out_bytes, K, nkv * qk) ||
+        overlaps(out, out_bytes, V, nkv * vo) ||
+        (mult && overlaps(out, out_bytes, mult, (size_t)B * Nk * 4)))
+        return SPHATTN_ERR_ALIAS;
+    if (Z && (overlaps(Z, zb, Q, nq * qk) || overlaps(Z, zb, K, nkv * qk) || overlaps(Z, zb, V, nkv * vo) ||
+              overlaps(Z, zb, out, out_bytes) || (mult && overlaps(Z, zb, mult, (size_t)B * Nk * 4))))
         return SPHATTN_ERR_ALIAS;
     return SPHATTN_OK;
+}
+
+size_t out_bytes_of(int B, int H, int N, int d, int dtype)
+{
+    return (size_t)B * H * N * d * (dtype == SPHATTN_F32 ? 4 : 2);
 }
 
 // Kernels that use more than 64 KB of LDS need their limit raised once per device; `done` is
@@ -70,43 +87,62 @@ bool raise_lds_limit(Kern kern, int lds_bytes, std::atomic<uint64_t>& done)
     return true;
 }
 
+// A launch.  Whole problem: O is the output tensor, Z the optional row aggregates, n_splits 1.
+// Partial accumulators: O is the fp32 slice-major o buffer, Z the z buffer, and the key axis
+// is cut into n_splits slices of keys_per_split rows.
 struct Problem {
-    const void* Q; const void* K; const void* V; void* O; const float* mult;
-    int B, H, H_kv, N;
+    const void* Q; const void* K; const void* V; void* O; const float* mult; float* Z;
+    int B, H, H_kv, Nq, Nk;
     hipStream_t stream;
+    int n_splits = 1, keys_per_split = 0;
 };
 
-template <int D, int QB, QKType QKT, Norm NORM, bool MULT>
+// Key slices are whole 64-key tiles.  Asking for more slices than there are tiles, or for a
+// count that does not divide them evenly, yields fewer, equally sized slices (the last may be
+// shorter).
+struct SplitPlan { int n_splits, keys_per_split; };
+SplitPlan plan_splits(int Nk, int requested)
+{
+    const int tiles = (Nk + kBC - 1) / kBC;
+    const int per = (tiles + requested - 1) / requested;
+    return SplitPlan{(tiles + per - 1) / per, per * kBC};
+}
+
+template <int D, int QB, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
 int launch_pipelined(const Problem& p)
 {
     constexpr int BR = kWaves * 32 * QB;
     constexpr int EQ = QKT == QKType::Fp8 ? 1 : 2;
     constexpr int lds_bytes = kNBuf * kBC * (D * EQ + kKPad + D * 2 + kVPad);
-    auto kern = fwd_pipelined_kernel<D, QB, QKT, NORM, MULT>;
+    auto kern = fwd_pipelined_kernel<D, QB, QKT, NORM, MULT, PARTIAL>;
     static std::atomic<uint64_t> done{0};
     if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;
-    const int n_qtiles = (p.N + BR - 1) / BR;
-    const int n_wg = p.B * p.H * n_qtiles;
+    const int n_qtiles = (p.Nq + BR - 1) / BR;
+    const long long n_wg = (long long)p.B * p.H * n_qtiles * p.n_splits;
+    if (n_wg > 0x7fffffff) return SPHATTN_ERR_SHAPE;
     const float scale_log2 = 1.4426950408889634f / __builtin_sqrtf((float)D);
-    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, p.stream,
-                       p.Q, p.K, p.V, p.O, p.mult,
-                       p.N, p.H, p.H / p.H_kv, n_qtiles, n_wg, scale_log2);
+    hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, p.stream,
+                       p.Q, p.K, p.V, p.O, p.mult, p.Z,
+                       p.Nq, p.Nk, p.H, p.H / p.H_kv, n_qtiles, (int)n_wg,
+                       p.n_splits, p.keys_per_split, scale_log2);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
-template <int D, bool MULT>
+template <int D, bool MULT, bool PARTIAL = false>
 int launch_f32(const Problem& p)
 {
     constexpr int BR = 32;                         // the four waves split the key axis
     constexpr int lds_bytes = kWaves * 2 * 32 * (D + 4) * 4;
-    auto kern = fwd_f32_kernel<D, MULT>;
+    auto kern = fwd_f32_kernel<D, MULT, PARTIAL>;
     static std::atomic<uint64_t> done{0};
     if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;
-    const int n_qtiles = (p.N + BR - 1) / BR;
-    const int n_wg = p.B * p.H * n_qtiles;
-    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), lds_bytes, p.stream,
-                       (const float*)p.Q, (const float*)p.K, (const float*)p.V, (float*)p.O, p.mult,
-                       p.N, p.H, p.H / p.H_kv, n_qtiles, n_wg);
+    const int n_qtiles = (p.Nq + BR - 1) / BR;
+    const long long n_wg = (long long)p.B * p.H * n_qtiles * p.n_splits;
+    if (n_wg > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, p.stream,
+                       (const float*)p.Q, (const float*)p.K, (const float*)p.V, (float*)p.O, p.mult, p.Z,
+                       p.Nq, p.Nk, p.H, p.H / p.H_kv, n_qtiles, (int)n_wg,
+                       p.n_splits, p.keys_per_split);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
@@ -122,7 +158,7 @@ bool narrow_tiles_pay(const Problem& p)
         if (e[0] == '2' && e[1] == '5' && e[2] == '6' && !e[3]) return false;
     }
     constexpr long long kCus = 256;
-    return (long long)p.B * p.H * ((p.N + 255) / 256) < kCus;
+    return (long long)p.B * p.H * ((p.Nq + 255) / 256) < kCus;
 }
 
 template <Norm NORM, bool MULT>
@@ -155,6 +191,52 @@ int dispatch(const Problem& p, int d, int dtype)
     return SPHATTN_ERR_DTYPE;
 }
 
+// Partial accumulators over key slices: always the 256-row workgroup (the slices, not narrower
+// tiles, are what fills the CUs).
+template <bool MULT>
+int dispatch_partial(const Problem& p, int d, int dtype)
+{
+    constexpr Norm S = Norm::Spherical;
+    switch (dtype) {
+    case SPHATTN_BF16:
+        return d == 128 ? launch_pipelined<128, 2, QKType::Bf16, S, MULT, true>(p)
+                        : launch_pipelined<64, 2, QKType::Bf16, S, MULT, true>(p);
+    case SPHATTN_F16:
+        return d == 128 ? launch_pipelined<128, 2, QKType::F16, S, MULT, true>(p)
+                        : launch_pipelined<64, 2, QKType::F16, S, MULT, true>(p);
+    case SPHATTN_FP8QK_BF16V:
+        return d == 128 ? launch_pipelined<128, 2, QKType::Fp8, S, MULT, true>(p)
+                        : launch_pipelined<64, 2, QKType::Fp8, S, MULT, true>(p);
+    case SPHATTN_F32:
+        return d == 128 ? launch_f32<128, MULT, true>(p) : launch_f32<64, MULT, true>(p);
+    default:
+        return SPHATTN_ERR_DTYPE;
+    }
+}
+
+template <int D>
+int launch_combine(const float* o_parts, const float* z_parts, int n_parts, void* O, float* Z,
+                   size_t rows, int dtype, hipStream_t stream)
+{
+    const size_t threads = rows * (D / 4);
+    const size_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks), block(256);
+    if (dtype == SPHATTN_F32)
+        hipLaunchKernelGGL((combine_kernel<D, 0>), grid, block, 0, stream, o_parts, z_parts, n_parts, O, Z, rows);
+    else if (dtype == SPHATTN_F16)
+        hipLaunchKernelGGL((combine_kernel<D, 2>), grid, block, 0, stream, o_parts, z_parts, n_parts, O, Z, rows);
+    else
+        hipLaunchKernelGGL((combine_kernel<D, 1>), grid, block, 0, stream, o_parts, z_parts, n_parts, O, Z, rows);
+    return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
+}
+
+size_t workspace_bytes(int B, int H, int N, int d, int n_splits)
+{
+    const size_t rows = (size_t)B * H * N;
+    return ((size_t)n_splits * rows * (d + 1) * 4 + 255) & ~(size_t)255;
+}
+
 }  // namespace
 
 extern "C" {
@@ -162,18 +244,24 @@ extern "C" {
 int sphattn_fwd(const void* Q, const void* K, const void* V, void* O,
                 int B, int H, int N, int d, int dtype, void* stream)
 {
-    const int rc = check_args(Q, K, V, O, nullptr, B, H, H, N, d, dtype);
+    return sphattn_fwd_z(Q, K, V, O, nullptr, B, H, N, d, dtype, stream);
+}
+
+int sphattn_fwd_z(const void* Q, const void* K, const void* V, void* O, float* Z,
+                  int B, int H, int N, int d, int dtype, void* stream)
+{
+    const int rc = check_args(Q, K, V, O, out_bytes_of(B, H, N, d, dtype), nullptr, Z, B, H, H, N, N, d, dtype);
     if (rc != SPHATTN_OK) return rc;
-    const Problem p{Q, K, V, O, nullptr, B, H, H, N, (hipStream_t)stream};
+    const Problem p{Q, K, V, O, nullptr, Z, B, H, H, N, N, (hipStream_t)stream};
     return dispatch<Norm::Spherical, false>(p, d, dtype);
 }
 
 int sphattn_grn_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O,
                     int B, int H, int H_kv, int N, int d, int dtype, void* stream)
 {
-    const int rc = check_args(Q, K, V, O, mult, B, H, H_kv, N, d, dtype);
+    const int rc = check_args(Q, K, V, O, out_bytes_of(B, H, N, d, dtype), mult, nullptr, B, H, H_kv, N, N, d, dtype);
     if (rc != SPHATTN_OK) return rc;
-    const Problem p{Q, K, V, O, mult, B, H, H_kv, N, (hipStream_t)stream};
+    const Problem p{Q, K, V, O, mult, nullptr, B, H, H_kv, N, N, (hipStream_t)stream};
     return mult ? dispatch<Norm::Spherical, true>(p, d, dtype)
                 : dispatch<Norm::Spherical, false>(p, d, dtype);
 }
@@ -181,11 +269,11 @@ int sphattn_grn_fwd(const void* Q, const void* K, const void* V, const float* mu
 int sphattn_normalized_fwd(const void* Q, const void* K, const void* V, void* O,
                            int B, int H, int N, int d, int dtype, int normalizer, void* stream)
 {
-    const int rc = check_args(Q, K, V, O, nullptr, B, H, H, N, d, dtype);
+    const int rc = check_args(Q, K, V, O, out_bytes_of(B, H, N, d, dtype), nullptr, nullptr, B, H, H, N, N, d, dtype);
     if (rc != SPHATTN_OK) return rc;
     if (normalizer < SPHATTN_NORM_L2 || normalizer > SPHATTN_NORM_SQRELU) return SPHATTN_ERR_NORMALIZER;
     if (normalizer != SPHATTN_NORM_L2 && dtype != SPHATTN_BF16) return SPHATTN_ERR_DTYPE;
-    const Problem p{Q, K, V, O, nullptr, B, H, H, N, (hipStream_t)stream};
+    const Problem p{Q, K, V, O, nullptr, nullptr, B, H, H, N, N, (hipStream_t)stream};
     switch (normalizer) {
     case SPHATTN_NORM_L2: return dispatch<Norm::Spherical, false>(p, d, dtype);
     case SPHATTN_NORM_SOFTMAX: return dispatch<Norm::Softmax, false>(p, d, dtype);
@@ -197,11 +285,97 @@ int sphattn_normalized_fwd(const void* Q, const void* K, const void* V, void* O,
 int sphattn_softmax_fwd(const void* Q, const void* K, const void* V, void* O,
                         int B, int H, int N, int d, int dtype, void* stream)
 {
-    const int rc = check_args(Q, K, V, O, nullptr, B, H, H, N, d, dtype);
+    const int rc = check_args(Q, K, V, O, out_bytes_of(B, H, N, d, dtype), nullptr, nullptr, B, H, H, N, N, d, dtype);
     if (rc != SPHATTN_OK) return rc;
     if (dtype != SPHATTN_BF16) return SPHATTN_ERR_DTYPE;
-    const Problem p{Q, K, V, O, nullptr, B, H, H, N, (hipStream_t)stream};
+    const Problem p{Q, K, V, O, nullptr, nullptr, B, H, H, N, N, (hipStream_t)stream};
     return dispatch<Norm::Softmax, false>(p, d, dtype);
+}
+
+int sphattn_partial_fwd(const void* Q, const void* K, const void* V, const float* mult,
+                        float* o_part, float* z_part,
+                        int B, int H, int H_kv, int N_q, int N_k, int d, int dtype, void* stream)
+{
+    if (!z_part) return SPHATTN_ERR_NULL;
+    const int rc = check_args(Q, K, V, o_part, (size_t)B * H * N_q * d * 4, mult, z_part,
+                              B, H, H_kv, N_q, N_k, d, dtype);
+    if (rc != SPHATTN_OK) return rc;
+    Problem p{Q, K, V, o_part, mult, z_part, B, H, H_kv, N_q, N_k, (hipStream_t)stream};
+    p.n_splits = 1;
+    p.keys_per_split = plan_splits(N_k, 1).keys_per_split;
+    return mult ? dispatch_partial<true>(p, d, dtype) : dispatch_partial<false>(p, d, dtype);
+}
+
+int sphattn_combine(const float* o_parts, const float* z_parts, int n_parts, void* O, float* Z,
+                    int B, int H, int N, int d, int dtype, void* stream)
+{
+    if (!o_parts || !z_parts || !O) return SPHATTN_ERR_NULL;
+    const int rc = check_shape(B, H, H, N, N, d, dtype);
+    if (rc != SPHATTN_OK) return rc;
+    if (n_parts <= 0 || n_parts > 65536) return SPHATTN_ERR_SHAPE;
+    if (((uintptr_t)o_parts | (uintptr_t)O) & 15) return SPHATTN_ERR_ALIGN;
+    if (((uintptr_t)z_parts | (uintptr_t)Z) & 3) return SPHATTN_ERR_ALIGN;
+    const size_t rows = (size_t)B * H * N, ob = out_bytes_of(B, H, N, d, dtype);
+    const size_t pob = (size_t)n_parts * rows * d * 4, pzb = (size_t)n_parts * rows * 4;
+    if (overlaps(O, ob, o_parts, pob) || overlaps(O, ob, z_parts, pzb) ||
+        (Z && (overlaps(Z, rows * 4, o_parts, pob) || overlaps(Z, rows * 4, z_parts, pzb) ||
+               overlaps(Z, rows * 4, O, ob))))
+        return SPHATTN_ERR_ALIAS;
+    return d == 128 ? launch_combine<128>(o_parts, z_parts, n_parts, O, Z, rows, dtype, (hipStream_t)stream)
+                    : launch_combine<64>(o_parts, z_parts, n_parts, O, Z, rows, dtype, (hipStream_t)stream);
+}
+
+size_t sphattn_splitkv_workspace_bytes(int B, int H, int N, int d, int n_splits)
+{
+    if (B <= 0 || H <= 0 || N <= 0 || (d != 64 && d != 128) || n_splits <= 0) return 0;
+    if ((unsigned __int128)B * H * (unsigned __int128)N * (d + 1) * 4 * n_splits > ((unsigned __int128)1 << 46)) return 0;
+    return workspace_bytes(B, H, N, d, n_splits);
+}
+
+int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype)
+{
+    if (B <= 0 || H <= 0 || N <= 0 || (d != 64 && d != 128)) return 1;
+    constexpr long long kCus = 256;
+    const int rows_per_wg = dtype == SPHATTN_F32 ? 32 : 256;
+    const long long wg = (long long)B * H * ((N + rows_per_wg - 1) / rows_per_wg);
+    if (wg >= kCus) return 1;
+    // enough slices to give every CU a workgroup, but no slice shorter than 8 tiles
+    const long long want = (kCus + wg - 1) / wg;
+    const long long most = ((N + kBC - 1) / kBC + 7) / 8;
+    const long long s = want < most ? want : most;
+    return plan_splits(N, (int)(s < 1 ? 1 : s)).n_splits;
+}
+
+int sphattn_splitkv_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O, float* Z,
+                        int B, int H, int H_kv, int N, int d, int dtype, int n_splits,
+                        void* workspace, size_t workspace_size, void* stream)
+{
+    const int rc = check_args(Q, K, V, O, out_bytes_of(B, H, N, d, dtype), mult, Z, B, H, H_kv, N, N, d, dtype);
+    if (rc != SPHATTN_OK) return rc;
+    if (n_splits < 0) return SPHATTN_ERR_SHAPE;
+    if (n_splits == 0) n_splits = sphattn_splitkv_heuristic(B, H, N, d, dtype);
+    const SplitPlan plan = plan_splits(N, n_splits);
+    const size_t need = sphattn_splitkv_workspace_bytes(B, H, N, d, plan.n_splits);
+    if (!workspace || need == 0 || workspace_size < need || ((uintptr_t)workspace & 15)) return SPHATTN_ERR_WORKSPACE;
+    const size_t ob = out_bytes_of(B, H, N, d, dtype);
+    const size_t nq = (size_t)B * H * N * d, nkv = (size_t)B * H_kv * N * d;
+    const size_t qk = dtype == SPHATTN_F32 ? 4 : dtype == SPHATTN_FP8QK_BF16V ? 1 : 2;
+    const size_t vo = dtype == SPHATTN_F32 ? 4 : 2;
+    if (overlaps(workspace, need, Q, nq * qk) || overlaps(workspace, need, K, nkv * qk) ||
+        overlaps(workspace, need, V, nkv * vo) || overlaps(workspace, need, O, ob) ||
+        (mult && overlaps(workspace, need, mult, (size_t)B * N * 4)) ||
+        (Z && overlaps(workspace, need, Z, (size_t)B * H * N * 4)))
+        return SPHATTN_ERR_ALIAS;
+    const size_t rows = (size_t)B * H * N;
+    float* o_parts = (float*)workspace;
+    float* z_parts = o_parts + (size_t)plan.n_splits * rows * d;
+    Problem p{Q, K, V, o_parts, mult, z_parts, B, H, H_kv, N, N, (hipStream_t)stream};
+    p.n_splits = plan.n_splits;
+    p.keys_per_split = plan.keys_per_split;
+    const int r1 = mult ? dispatch_partial<true>(p, d, dtype) : dispatch_partial<false>(p, d, dtype);
+    if (r1 != SPHATTN_OK) return r1;
+    return d == 128 ? launch_combine<128>(o_parts, z_parts, plan.n_splits, O, Z, rows, dtype, (hipStream_t)stream)
+                    : launch_combine<64>(o_parts, z_parts, plan.n_splits, O, Z, rows, dtype, (hipStream_t)stream);
 }
 
 const char* sphattn_strerror(int code)
@@ -216,6 +390,7 @@ const char* sphattn_strerror(int code)
     case SPHATTN_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
     case SPHATTN_ERR_ALIAS: return "O must not overlap Q, K or V";
     case SPHATTN_ERR_NORMALIZER: return "normalizer is not a sphattn_normalizer value";
+    case SPHATTN_ERR_WORKSPACE: return "workspace is NULL, misaligned or smaller than sphattn_splitkv_workspace_bytes";
     default: return "unknown sphattn error code";
     }
 }

@@ -160,12 +160,20 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 // Gene-regulatory-network options (paper, Section 3.1; Appendix A.2): MULT multiplies the
 // score of key j by that gene's multiplicity mult[b, j] (the key row scaled by a scalar, applied
 // to the fp32 score before it is squared and rounded); kv_group query heads share one K/V head.
-template <int D, int QB, QKType QKT, Norm NORM, bool MULT>
+//
+// Shapes: Q and O have Nq rows per head, K and V have Nk.  Zv, when not null, receives z_i.
+// PARTIAL (Lemma 1 without the tail): the key axis is cut into n_splits slices of
+// keys_per_split rows (a multiple of the tile) and a workgroup accumulates one slice only; it
+// writes the unnormalised fp32 pair, o to Ov[split][b,h,i,:] and z to Zv[split][b,h,i].
+// Because the accumulator is a plain sum, the slices are added afterwards (combine_kernel)
+// and the tail is applied once.
+template <int D, int QB, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
 __global__ __launch_bounds__(kThreads, 1)
 void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv,
                           const void* __restrict__ Vv, void* __restrict__ Ov,
-                          const float* __restrict__ mult,
-                          int N, int H, int kv_group, int n_qtiles, int n_wg, float scale_log2)
+                          const float* __restrict__ mult, float* __restrict__ Zv,
+                          int Nq, int Nk, int H, int kv_group, int n_qtiles, int n_wg,
+                          int n_splits, int keys_per_split, float scale_log2)
 {
     constexpr bool FP8 = QKT == QKType::Fp8;
     constexpr bool HALF = QKT == QKType::F16;      // 16-bit type of V, O and P
@@ -193,6 +201,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     static_assert((2 * SLOTS) % RING == 0 && PD < RING && PD <= SLOTS, "ring indices must repeat");
     static_assert(QKT == QKType::Bf16 || NORM == Norm::Spherical, "fp8 and fp16 storage: spherical only");
     static_assert(!MULT || NORM == Norm::Spherical, "multiplicities belong to the spherical variant");
+    static_assert(!PARTIAL || NORM == Norm::Spherical, "partial accumulators: spherical only");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
@@ -203,19 +212,23 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     const int i16 = lane & 15, blk = (lane >> 4) & 1;
 
     const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
-    const int bh = lid / n_qtiles, qt = lid % n_qtiles;
-    const size_t head_off = (size_t)bh * N * D;    // in elements
+    // consecutive ids: the query tiles of one (head, key slice), which stream the same K/V
+    const int qt = lid % n_qtiles;
+    const int split = PARTIAL ? (lid / n_qtiles) % n_splits : 0;
+    const int bh = PARTIAL ? lid / (n_qtiles * n_splits) : lid / n_qtiles;
+    const size_t head_off = (size_t)bh * Nq * D;   // in elements
     const int bidx = bh / H;
-    const size_t kv_off = (size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * N * D;
+    const int k0 = PARTIAL ? split * keys_per_split : 0;                     // this workgroup's keys:
+    const int N = PARTIAL ? min(Nk - k0, keys_per_split) : Nk;               // k0 .. k0 + N - 1
+    const size_t kv_off = ((size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * Nk + k0) * D;
     const unsigned char* Qh = (const unsigned char*)Qv + head_off * EQ;
     const unsigned short* V = (const unsigned short*)Vv;
-    unsigned short* Oh = (unsigned short*)Ov + head_off;
     const __amdgpu_buffer_rsrc_t krs =
         make_rsrc((const unsigned char*)Kv + kv_off * EQ, (uint32_t)N * KROWB);
     const __amdgpu_buffer_rsrc_t vrs = make_rsrc(V + kv_off, (uint32_t)N * VROWB);
-    // multiplicities of this cell; reads past key N return 0 (those keys are zero anyway)
+    // multiplicities of this cell; reads past the last key return 0 (those keys are zero anyway)
     const __amdgpu_buffer_rsrc_t mrs =
-        make_rsrc(MULT ? mult + (size_t)bidx * N : nullptr, MULT ? (uint32_t)N * 4 : 0);
+        make_rsrc(MULT ? mult + (size_t)bidx * Nk + k0 : nullptr, MULT ? (uint32_t)N * 4 : 0);
     const int q0 = qt * BR + wave * 32 * QB;
 
     // ---- per-lane LDS byte offsets inside a tile; everything else is an immediate
@@ -241,7 +254,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         int row = q0 + qb * 32 + l32;
-        row = row < N ? row : N - 1;               // rows past the end are computed and dropped
+        row = row < Nq ? row : Nq - 1;             // rows past the end are computed and dropped
         const unsigned char* src = Qh + (size_t)row * KROWB + (FP8 ? 32 : 16) * h;
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
@@ -584,21 +597,49 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         }
     }
 
+    // ---- partial result: the pair (o, z) as it stands, in fp32
+    if constexpr (PARTIAL) {
+        const size_t rows0 = ((size_t)split * (n_wg / (n_qtiles * n_splits)) + bh) * Nq;
+        float* Op = (float*)Ov + rows0 * D;
+        float* Zp = Zv + rows0;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float z = sum_across_halves(zacc[qb][0] + zacc[qb][1]);
+            const int row = q0 + qb * 32 + l32;
+            if (row < Nq) {
+                if (h == 0) Zp[row] = z;
+                float* dst = Op + (size_t)row * D + 4 * h;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const f32x4 o4 = {oacc[db][qb][4 * g], oacc[db][qb][4 * g + 1],
+                                          oacc[db][qb][4 * g + 2], oacc[db][qb][4 * g + 3]};
+                        *reinterpret_cast<f32x4*>(dst + db * 32 + 8 * g) = o4;
+                    }
+            }
+        }
+        return;
+    }
+
     // ---- tail t(o, z) = o / b(z): spherical b = sqrt, the others b = id
+    unsigned short* Oh = (unsigned short*)Ov + head_off;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        float inv;
+        float inv, z;
         if constexpr (NORM == Norm::Spherical) {
-            const float z = sum_across_halves(zacc[qb][0] + zacc[qb][1]);
+            z = sum_across_halves(zacc[qb][0] + zacc[qb][1]);
             inv = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
         } else if constexpr (NORM == Norm::Softmax) {
-            inv = 1.0f / sum_across_halves(zacc[qb][0]);
+            z = sum_across_halves(zacc[qb][0]);
+            inv = 1.0f / z;
         } else {
-            const float z = sum_across_halves(zacc[qb][0] + zacc[qb][1]);
+            z = sum_across_halves(zacc[qb][0] + zacc[qb][1]);
             inv = z > 0.f ? 1.0f / z : 0.f;
         }
         const int row = q0 + qb * 32 + l32;
-        if (row < N) {
+        if (row < Nq) {
+            if (Zv != nullptr && h == 0) Zv[(size_t)bh * Nq + row] = z;
             unsigned short* dst = Oh + (size_t)row * D + 4 * h;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -627,12 +668,14 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
 // wave stages its tiles in a private LDS region; there is no workgroup barrier in
 // the loop.
 // ---------------------------------------------------------------------------
-template <int D, bool MULT>
+// Nq, Nk, Zv, PARTIAL, n_splits and keys_per_split as in fwd_pipelined_kernel.
+template <int D, bool MULT, bool PARTIAL = false>
 __global__ __launch_bounds__(kThreads, 1)
 void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                     const float* __restrict__ V, float* __restrict__ O,
-                    const float* __restrict__ mult,
-                    int N, int H, int kv_group, int n_qtiles, int n_wg)
+                    const float* __restrict__ mult, float* __restrict__ Zv,
+                    int Nq, int Nk, int H, int kv_group, int n_qtiles, int n_wg,
+                    int n_splits, int keys_per_split)
 {
     constexpr int BC = 32;                         // keys per tile
     constexpr int ROWF = D + 4;                    // padded row, in floats: conflict-free columns
@@ -649,22 +692,25 @@ void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
-    const int bh = lid / n_qtiles, qt = lid % n_qtiles;
-    const size_t head_off = (size_t)bh * N * D;
+    const int qt = lid % n_qtiles;
+    const int split = PARTIAL ? (lid / n_qtiles) % n_splits : 0;
+    const int bh = PARTIAL ? lid / (n_qtiles * n_splits) : lid / n_qtiles;
+    const size_t head_off = (size_t)bh * Nq * D;
     const int bidx = bh / H;
-    const size_t kv_off = (size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * N * D;
+    const int k0 = PARTIAL ? split * keys_per_split : 0;
+    const int N = PARTIAL ? min(Nk - k0, keys_per_split) : Nk;      // keys k0 .. k0 + N - 1
+    const size_t kv_off = ((size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * Nk + k0) * D;
     const float* Qh = Q + head_off;
     const float* Kh = K + kv_off;
     const float* Vh = V + kv_off;
-    float* Oh = O + head_off;
-    const float* mrow = MULT ? mult + (size_t)bidx * N : nullptr;
+    const float* mrow = MULT ? mult + (size_t)bidx * Nk + k0 : nullptr;
     const int q0 = qt * 32;
 
     // Q as B operand of S^T = K Q^T: lane holds Q[q0 + l32][2kk + h]
     float qf[D / 2];
     {
         int row = q0 + l32;
-        row = row < N ? row : N - 1;
+        row = row < Nq ? row : Nq - 1;
 #pragma unroll
         for (int kk = 0; kk < D / 2; ++kk) qf[kk] = Qh[(size_t)row * D + 2 * kk + h];
     }
@@ -753,9 +799,13 @@ void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) zt += part[w * PART + DB * 16 * 64 + lane];
         zt = sum_across_halves(zt);
-        const float inv = zt > 0.f ? 1.0f / __builtin_sqrtf(zt) : 0.f;
+        const float inv = PARTIAL ? 1.f : zt > 0.f ? 1.0f / __builtin_sqrtf(zt) : 0.f;
         const int row = q0 + l32;
-        float* dst = Oh + (size_t)row * D + wave * 32 + 4 * h;
+        // partial: the fp32 pair (o, z) of this key slice, slice-major
+        const size_t rows0 = PARTIAL ? ((size_t)split * (n_wg / (n_qtiles * n_splits)) + bh) * Nq
+                                     : (size_t)bh * Nq;
+        if (wave == 0 && h == 0 && row < Nq && (PARTIAL || Zv != nullptr)) Zv[rows0 + row] = zt;
+        float* dst = O + (rows0 + row) * D + wave * 32 + 4 * h;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             f32x4 o4;
@@ -766,8 +816,42 @@ void fwd_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                 for (int w = 0; w < kWaves; ++w) acc += part[w * PART + (wave * 16 + 4 * g + t) * 64 + lane];
                 o4[t] = acc * inv;
             }
-            if (row < N) *reinterpret_cast<f32x4*>(dst + 8 * g) = o4;
+            if (row < Nq) *reinterpret_cast<f32x4*>(dst + 8 * g) = o4;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Adds the partial pairs (o, z) of n_parts key slices and applies the tail once
+// (Lemma 1: the accumulator of a concatenation is the sum of the accumulators):
+//     O[r,:] = (sum_p o_p[r,:]) / sqrt(sum_p z_p[r])        (0 if the sum of z is 0)
+// rows = B*H*N query rows; part p starts rows*D floats (o) / rows floats (z) after part
+// p-1.  One thread per 4 output columns; the parts are added in ascending order, so the
+// result does not depend on the launch.  OUT: 0 fp32, 1 bfloat16, 2 IEEE half.
+// ---------------------------------------------------------------------------
+template <int D, int OUT>
+__global__ __launch_bounds__(256)
+void combine_kernel(const float* __restrict__ o_parts, const float* __restrict__ z_parts,
+                    int n_parts, void* __restrict__ Ov, float* __restrict__ Zv, size_t rows)
+{
+    constexpr int C4 = D / 4;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t row = idx / C4;
+    const int c4 = (int)(idx % C4);
+    if (row >= rows) return;
+    float z = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < n_parts; ++p) {
+        z += z_parts[(size_t)p * rows + row];
+        acc += *reinterpret_cast<const f32x4*>(o_parts + ((size_t)p * rows + row) * D + 4 * c4);
+    }
+    const float inv = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
+    if (Zv != nullptr && c4 == 0) Zv[row] = z;
+    if constexpr (OUT == 0) {
+        *reinterpret_cast<f32x4*>((float*)Ov + row * D + 4 * c4) = acc * inv;
+    } else {
+        const i32x2 o4 = {pack2<OUT == 2>(acc[0] * inv, acc[1] * inv), pack2<OUT == 2>(acc[2] * inv, acc[3] * inv)};
+        *reinterpret_cast<i32x2*>((unsigned short*)Ov + row * D + 4 * c4) = o4;
     }
 }
 

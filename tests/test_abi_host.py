@@ -41,7 +41,7 @@ def test_header_symbols_are_exported(lib):
 def test_version_and_strerror(lib):
     assert lib.sphattn_version() >= 100
     assert lib.sphattn_strerror(0) == b"success"
-    for code in range(-8, 0):
+    for code in range(-9, 0):
         assert b"unknown" not in lib.sphattn_strerror(code)
     assert b"unknown" in lib.sphattn_strerror(-99)
 
@@ -105,6 +105,70 @@ def test_softmax_twin_is_bf16_only(lib):
     assert _call(lib, "sphattn_softmax_fwd", dtype=0) == -4
     assert _call(lib, "sphattn_softmax_fwd", dtype=2) == -4
     assert _call(lib, "sphattn_softmax_fwd", dtype=3) == -4
+
+
+def test_partial_and_combine_argument_errors(lib):
+    P = ctypes.c_void_p
+
+    def partial(Q=0x1000, K=0x2000000, V=0x4000000, mult=0, o=0x10000000, z=0x20000000,
+                B=1, H=2, H_kv=1, Nq=100, Nk=300, d=64, dtype=1):
+        return lib.sphattn_partial_fwd(P(Q), P(K), P(V), P(mult), P(o), P(z), B, H, H_kv, Nq, Nk, d, dtype, None)
+    assert partial(z=0) == -1
+    assert partial(o=0) == -1
+    assert partial(Nq=0) == -2
+    assert partial(Nk=-1) == -2
+    assert partial(H_kv=3) == -2
+    assert partial(d=80) == -3
+    assert partial(dtype=5) == -4
+    assert partial(o=0x10000004) == -5
+    assert partial(z=0x20000002) == -5
+    assert partial(o=0x1000) == -7                           # o_part is Q
+    assert partial(z=0x10000000 + 16) == -7                  # z_part inside o_part
+
+    def combine(o=0x10000000, z=0x20000000, n=3, O=0x30000000, Z=0, B=1, H=2, N=100, d=64, dtype=1):
+        return lib.sphattn_combine(P(o), P(z), n, P(O), P(Z), B, H, N, d, dtype, None)
+    assert combine(o=0) == -1
+    assert combine(O=0) == -1
+    assert combine(n=0) == -2
+    assert combine(n=10 ** 6) == -2
+    assert combine(N=0) == -2
+    assert combine(d=32) == -3
+    assert combine(dtype=-1) == -4
+    assert combine(O=0x30000008) == -5
+    assert combine(O=0x10000000 + 3 * 200 * 64 * 4 - 16) == -7     # O overlaps the last part
+    assert combine(Z=0x20000000) == -7                             # Z is z_parts
+
+
+def test_splitkv_argument_errors_and_workspace_size(lib):
+    P = ctypes.c_void_p
+    need = lib.sphattn_splitkv_workspace_bytes(1, 2, 1000, 128, 4)
+    assert need >= 4 * 2 * 1000 * 129 * 4 and need % 256 == 0 and need < 4 * 2 * 1000 * 129 * 4 + 256
+    assert lib.sphattn_splitkv_workspace_bytes(1, 2, 1000, 100, 4) == 0
+    assert lib.sphattn_splitkv_workspace_bytes(0, 2, 1000, 128, 4) == 0
+    assert lib.sphattn_splitkv_workspace_bytes(1, 2, 1000, 128, 0) == 0
+
+    def call(ws=0x40000000, size=need, n_splits=4, O=0x6000000, Z=0, N=1000, dtype=1):
+        return lib.sphattn_splitkv_fwd(P(0x1000), P(0x2000000), P(0x4000000), P(0), P(O), P(Z),
+                                       1, 2, 2, N, 128, dtype, n_splits, P(ws), size, None)
+    assert call(ws=0) == -9
+    assert call(size=need - 256) == -9
+    assert call(ws=0x40000004) == -9
+    assert call(n_splits=-1) == -2
+    assert call(N=0) == -2
+    assert call(dtype=8) == -4
+    assert call(ws=0x6000000) == -7                          # workspace is O
+    assert call(Z=0x40000000 + 64) == -7                     # Z inside the workspace
+
+
+def test_splitkv_heuristic_splits_only_underfilled_launches(lib):
+    h = lib.sphattn_splitkv_heuristic
+    assert h(2, 16, 8192, 128, 1) == 1                # 1024 workgroups already
+    assert h(1, 1, 65536, 128, 1) == 1                # 256 workgroups
+    assert h(1, 1, 8192, 128, 1) == 8                 # 32 workgroups -> 8 slices of 16 tiles
+    assert h(1, 2, 4096, 64, 1) == 8                  # 32 workgroups; 64 tiles / 8 per slice
+    assert h(1, 1, 300, 128, 1) == 1                  # 5 tiles: too short to cut
+    assert h(1, 1, 2048, 64, 0) == 4                  # fp32: 32-row workgroups, 64 of them
+    assert h(0, 1, 8192, 128, 1) == 1                 # nonsense in, 1 out
 
 
 def test_bench_refuses_more_than_one_gpu():
