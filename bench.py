@@ -83,6 +83,9 @@ def main() -> int:
     ap.add_argument("--grn", type=int, default=0, metavar="H_KV",
                     help="also time the gene-regulatory-network entry point on the same shape with "
                          "H_KV shared K/V heads and Poisson(1.5) multiplicities")
+    ap.add_argument("--splitkv", type=int, default=0, metavar="HEADS",
+                    help="also time the split-key forward against the unsplit call on the first HEADS "
+                         "heads of batch 0 of the workload (few heads leave CUs idle; the split fills them)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run a plain 256 MiB device copy (untimed), as the known-size "
                          "reference that HBM byte counters are scaled by when profiling")
@@ -162,6 +165,25 @@ def main() -> int:
         ms_g = sum(per_g) / len(per_g)
         result["grn_variant"] = {"H_kv": args.grn, "multiplicities": "Poisson(1.5)", "kernel_ms_avg": ms_g,
                                  "tflops": w.flops / (ms_g * 1e-3) / 1e12}
+
+    if args.splitkv:
+        hs = min(args.splitkv, w.H)
+        qs, ks, vs = (t[:1, :hs].contiguous() for t in (qd, kd, vd))
+        outs = torch.empty_like(vs)
+        n_splits = pkg.sphattn_splitkv_heuristic(1, hs, w.N, w.d, w.dtype)
+        ws = torch.empty(pkg.sphattn_splitkv_workspace_bytes(1, hs, w.N, w.d, n_splits), dtype=torch.uint8, device=dev)
+        _, per_u = time_launches(lambda: pkg.sphattn_fwd(qs, ks, vs, outs, dtype=w.dtype),
+                                 max(10, args.steps // 4), max(5, args.warmup // 4))
+        _, per_s = time_launches(lambda: pkg.sphattn_splitkv_fwd(qs, ks, vs, ws, O=outs, n_splits=n_splits, dtype=w.dtype),
+                                 max(10, args.steps // 4), max(5, args.warmup // 4))
+        ms_u, ms_s = sum(per_u) / len(per_u), sum(per_s) / len(per_s)
+        fl = 4.0 * hs * w.N * w.N * w.d
+        result["splitkv_variant"] = {
+            "shape": f"B=1 H={hs} N={w.N} d={w.d} {w.dtype}", "n_splits": n_splits,
+            "workspace_bytes": ws.numel(), "unsplit_ms_avg": ms_u, "split_ms_avg": ms_s,
+            "unsplit_tflops": fl / (ms_u * 1e-3) / 1e12, "split_tflops": fl / (ms_s * 1e-3) / 1e12,
+            "split_speedup": ms_u / ms_s,
+        }
 
     if args.copy_reference:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
