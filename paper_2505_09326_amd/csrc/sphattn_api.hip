@@ -2,6 +2,7 @@
 // selection by (dtype, d), launch on the caller's stream.  Allocates nothing and
 // never synchronises.
 #include "sphattn_device.hpp"
+#include "sphattn_pipelined.hpp"
 #include "../../include/sphattn.h"
 
 #include <stdint.h>
@@ -108,13 +109,13 @@ SplitPlan plan_splits(int Nk, int requested)
     return SplitPlan{(tiles + per - 1) / per, per * kBC};
 }
 
-template <int D, int QB, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
+template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
 int launch_pipelined(const Problem& p)
 {
-    constexpr int BR = kWaves * 32 * QB;
+    constexpr int BR = kWaves * 16 * NQ;
     constexpr int EQ = QKT == QKType::Fp8 ? 1 : 2;
     constexpr int lds_bytes = kNBuf * kBC * (D * EQ + kKPad + D * 2 + kVPad);
-    auto kern = fwd_pipelined_kernel<D, QB, QKT, NORM, MULT, PARTIAL>;
+    auto kern = fwd_pipelined_kernel<D, NQ, QKT, NORM, MULT, PARTIAL>;
     static std::atomic<uint64_t> done{0};
     if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;
     const int n_qtiles = (p.Nq + BR - 1) / BR;
@@ -167,21 +168,21 @@ int dispatch(const Problem& p, int d, int dtype)
     if (dtype == SPHATTN_BF16) {
         if constexpr (NORM == Norm::Spherical && !MULT) {
             if (narrow_tiles_pay(p)) {
-                if (d == 128) return launch_pipelined<128, 1, QKType::Bf16, NORM, MULT>(p);
-                return launch_pipelined<64, 1, QKType::Bf16, NORM, MULT>(p);
+                if (d == 128) return launch_pipelined<128, 2, QKType::Bf16, NORM, MULT>(p);
+                return launch_pipelined<64, 2, QKType::Bf16, NORM, MULT>(p);
             }
         }
-        if (d == 128) return launch_pipelined<128, 2, QKType::Bf16, NORM, MULT>(p);
-        return launch_pipelined<64, 2, QKType::Bf16, NORM, MULT>(p);
+        if (d == 128) return launch_pipelined<128, 4, QKType::Bf16, NORM, MULT>(p);
+        return launch_pipelined<64, 4, QKType::Bf16, NORM, MULT>(p);
     }
     if constexpr (NORM == Norm::Spherical) {
         if (dtype == SPHATTN_F16) {
-            if (d == 128) return launch_pipelined<128, 2, QKType::F16, NORM, MULT>(p);
-            return launch_pipelined<64, 2, QKType::F16, NORM, MULT>(p);
+            if (d == 128) return launch_pipelined<128, 4, QKType::F16, NORM, MULT>(p);
+            return launch_pipelined<64, 4, QKType::F16, NORM, MULT>(p);
         }
         if (dtype == SPHATTN_FP8QK_BF16V) {
-            if (d == 128) return launch_pipelined<128, 2, QKType::Fp8, NORM, MULT>(p);
-            return launch_pipelined<64, 2, QKType::Fp8, NORM, MULT>(p);
+            if (d == 128) return launch_pipelined<128, 4, QKType::Fp8, NORM, MULT>(p);
+            return launch_pipelined<64, 4, QKType::Fp8, NORM, MULT>(p);
         }
         if (dtype == SPHATTN_F32) {
             if (d == 128) return launch_f32<128, MULT>(p);
@@ -199,14 +200,14 @@ int dispatch_partial(const Problem& p, int d, int dtype)
     constexpr Norm S = Norm::Spherical;
     switch (dtype) {
     case SPHATTN_BF16:
-        return d == 128 ? launch_pipelined<128, 2, QKType::Bf16, S, MULT, true>(p)
-                        : launch_pipelined<64, 2, QKType::Bf16, S, MULT, true>(p);
+        return d == 128 ? launch_pipelined<128, 4, QKType::Bf16, S, MULT, true>(p)
+                        : launch_pipelined<64, 4, QKType::Bf16, S, MULT, true>(p);
     case SPHATTN_F16:
-        return d == 128 ? launch_pipelined<128, 2, QKType::F16, S, MULT, true>(p)
-                        : launch_pipelined<64, 2, QKType::F16, S, MULT, true>(p);
+        return d == 128 ? launch_pipelined<128, 4, QKType::F16, S, MULT, true>(p)
+                        : launch_pipelined<64, 4, QKType::F16, S, MULT, true>(p);
     case SPHATTN_FP8QK_BF16V:
-        return d == 128 ? launch_pipelined<128, 2, QKType::Fp8, S, MULT, true>(p)
-                        : launch_pipelined<64, 2, QKType::Fp8, S, MULT, true>(p);
+        return d == 128 ? launch_pipelined<128, 4, QKType::Fp8, S, MULT, true>(p)
+                        : launch_pipelined<64, 4, QKType::Fp8, S, MULT, true>(p);
     case SPHATTN_F32:
         return d == 128 ? launch_f32<128, MULT, true>(p) : launch_f32<64, MULT, true>(p);
     default:

@@ -1,0 +1,578 @@
+// Software-pipelined forward kernel on the 16x16 matrix instructions of gfx950:
+// 16-bit V/O (bf16 or fp16); Q/K in the same type or OCP E4M3.
+//
+// One workgroup = 4 wavefronts (one per SIMD) = one tile of BR = 4*16*NQ query rows of one
+// (b,h); a wavefront owns NQ blocks of 16 query rows.  The key axis is streamed in tiles of 64
+// rows (Theorem 1: the query axis is partitioned, the key axis is streamed); the only state
+// carried between key tiles is the pair (o, z) of Lemma 1, held in fp32 registers:
+//
+//     o_i += sum_j s_ij * v_j        z_i += sum_j s_ij^2        tail: O_i = o_i / sqrt(z_i)
+//
+// Matrix-core mapping.  Scores are produced TRANSPOSED,
+//     S^T[kb][qb] (16 keys x 16 queries) += K frag (A: 16 keys x k) * Q frag (B: k x 16 queries)
+// with v_mfma_f32_16x16x32_{bf16,f16} (k = 32) or v_mfma_f32_16x16x128_f8f6f4 (k = 128, E4M3).
+// In the accumulator layout of the 16x16 instructions lane l owns query column (l & 15) and, in
+// register t, key row 4(l>>4) + t.  The two key blocks kb = 0, 1 of a 32-key sub-step therefore
+// put 8 scores of one query into every lane, and 8 values of one column are exactly one B
+// operand of the second contraction
+//     O^T[db][qb] (16 columns of d x 16 queries) += V^T frag (A: 16 x 32 keys) * P^T (B: 32 keys x 16)
+// where k-slot e of lane group g = l>>4 stands for key 4g + e (e < 4) or 16 + 4g + (e - 4):
+// any assignment of keys to k-slots is valid as long as A and B use the same one.  So the
+// scores never leave their registers: they are squared and summed into z in place (plain fp32
+// FMAs), rounded to the 16-bit type in place, and fed straight back to the matrix cores.  The
+// A operand V^T comes from the row-major V tile in LDS through two transposing reads
+// (ds_read_b64_tr_b16: keys 4g..4g+3 and 16+4g..16+4g+3).  z is a per-lane partial sum; the
+// four lanes that share a query (l, l^16, l^32, l^48) are combined once, in the tail.
+//
+// Why 16x16 and not 32x32 instructions: on Gaussian operands the part is power-bound, and the
+// 16x16x32 form sustains about 10 % more flop/s at the power limit than 32x32x16 (measured with
+// loops of nothing but matrix instructions: 1930 against 1755 TFLOP/s), which outweighs its
+// lower issue efficiency with one wave per SIMD.
+//
+// Pipeline.  The key axis advances in sub-steps of 32 keys.  Three stages of three consecutive
+// sub-steps are in flight at once in every wavefront, so that the matrix pipe, the vector ALU
+// and the LDS all stay busy with one wave per SIMD:
+//     A(t+1)  S^T = K Q^T            matrix cores -> score registers (next)
+//     B(t)    normaliser on scores   plain VALU on score registers (current)
+//                spherical: z += s^2, P = bf16(s)   (no exp, no max, no rescale)
+//                SoftMax twin: running max, exp2, running sum, rescale factor
+//     C(t-1)  O^T += V^T P^T         matrix cores <- P registers (previous)
+// A sub-step is cut into SLOTS slots (one V^T fragment each); LDS fragment reads run PD slots
+// ahead of their use, across sub-step and tile boundaries.  K/V tiles of 64 keys rotate through
+// four LDS buffers: in iteration j tiles j and j+1 feed stage A, tiles j-1 and j feed stage C,
+// tile j+2 is written and tile j+3 is on its way from HBM/L2 into registers, with one workgroup
+// barrier per tile.  Global loads go through buffer descriptors whose range check returns
+// zeros past the end of the head: a zero key contributes nothing to o or z, so ragged N needs
+// no masking in the spherical case.
+//
+// Gene-regulatory-network options (paper, Section 3.1; Appendix A.2): MULT multiplies the
+// score of key j by that gene's multiplicity mult[b, j] (the key row scaled by a scalar, applied
+// to the fp32 score before it is squared and rounded); kv_group query heads share one K/V head.
+//
+// Shapes: Q and O have Nq rows per head, K and V have Nk.  Zv, when not null, receives z_i.
+// PARTIAL (Lemma 1 without the tail): the key axis is cut into n_splits slices of
+// keys_per_split rows (a multiple of the tile) and a workgroup accumulates one slice only; it
+// writes the unnormalised fp32 pair, o to Ov[split][b,h,i,:] and z to Zv[split][b,h,i].
+// Because the accumulator is a plain sum, the slices are added afterwards (combine_kernel)
+// and the tail is applied once.
+#pragma once
+#include "sphattn_device.hpp"
+
+namespace sphattn {
+
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+template <bool HALF>
+__device__ __forceinline__ f32x4 mfma16x16(i32x4 a, i32x4 b, f32x4 c)
+{
+    if constexpr (HALF)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// v_permlane16_swap exchanges the odd rows (of 16 lanes) of its first operand with the even rows
+// of its second.  Fed two copies of x, every lane ends up with x of the even and of the odd row
+// of its pair of rows; with both_halves() on top, a value is combined over the four lanes
+// l, l^16, l^32, l^48 without LDS traffic.
+__device__ __forceinline__ HalfPair both_rows(float x)
+{
+    float a = x, b = x;
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+    return HalfPair{a, b};
+}
+
+__device__ __forceinline__ float max_across_groups(float x)
+{
+    const HalfPair r = both_rows(x);
+    return max_across_halves(fmaxf(r.lo, r.hi));
+}
+
+__device__ __forceinline__ float sum_across_groups(float x)
+{
+    const HalfPair r = both_rows(x);
+    return sum_across_halves(r.lo + r.hi);
+}
+
+template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
+__global__ __launch_bounds__(kThreads, 1)
+void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv,
+                          const void* __restrict__ Vv, void* __restrict__ Ov,
+                          const float* __restrict__ mult, float* __restrict__ Zv,
+                          int Nq, int Nk, int H, int kv_group, int n_qtiles, int n_wg,
+                          int n_splits, int keys_per_split, float scale_log2)
+{
+    constexpr bool FP8 = QKT == QKType::Fp8;
+    constexpr bool HALF = QKT == QKType::F16;      // 16-bit type of V, O and P
+    constexpr int BC = kBC;
+    constexpr int BR = kWaves * 16 * NQ;
+    constexpr int EQ = FP8 ? 1 : 2;                // bytes per Q/K element
+    constexpr int KROWB = D * EQ, KCH = KROWB / 16, KTILE = BC * KROWB;   // as stored in HBM
+    constexpr int VROWB = D * 2, VCH = VROWB / 16, VTILE = BC * VROWB;
+    constexpr int KSTR = KROWB + kKPad, VSTR = VROWB + kVPad;             // LDS row strides
+    constexpr int KLDS = BC * KSTR;                                        // K tile in LDS
+    constexpr int BUF_BYTES = KLDS + BC * VSTR;    // K tile then V tile
+    constexpr int LDK = BC * KCH / kThreads;       // 16-byte chunks per thread per K tile
+    constexpr int LDV = BC * VCH / kThreads;
+    constexpr int NST = LDK + LDV;                 // staged chunks per thread per tile
+    constexpr int DB = D / 16;                     // 16-column blocks of the head dimension
+    constexpr int SLOTS = DB;                      // slots per sub-step: one V^T fragment each
+    constexpr int KK = D / 32;                     // 16-bit: k-steps of K Q^T
+    constexpr int QKM = FP8 ? 2 * NQ / SLOTS : NQ; // score matrix instructions per slot
+    constexpr int PAIRS = 4 * NQ / SLOTS;          // score register pairs of stage B per slot
+    constexpr int PD = 3;                          // LDS prefetch distance in slots
+    constexpr int RING = 4;                        // fragment registers in rotation
+    constexpr int VALU_PER_MFMA = 1;               // VALU instructions issued behind each MFMA (measured best of 1..4)
+    static_assert(D == 64 || D == 128, "head dimension 128 or 64");
+    static_assert(NQ == 4 || NQ == 2, "64 or 32 query rows per wave");
+    static_assert(FP8 || 2 * KK == SLOTS, "16-bit: one K fragment (key block, k-step) per slot");
+    static_assert(!FP8 || (2 * NQ) % SLOTS == 0, "fp8: whole score instructions per slot");
+    static_assert(PAIRS >= 1 && NST <= SLOTS, "slot plan");
+    static_assert((2 * SLOTS) % RING == 0 && PD < RING && PD <= SLOTS, "ring indices must repeat");
+    static_assert(QKT == QKType::Bf16 || NORM == Norm::Spherical, "fp8 and fp16 storage: spherical only");
+    static_assert(!MULT || NORM == Norm::Spherical, "multiplicities belong to the spherical variant");
+    static_assert(!PARTIAL || NORM == Norm::Spherical, "partial accumulators: spherical only");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int n16 = lane & 15, g = lane >> 4;
+
+    const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
+    // consecutive ids: the query tiles of one (head, key slice), which stream the same K/V
+    const int qt = lid % n_qtiles;
+    const int split = PARTIAL ? (lid / n_qtiles) % n_splits : 0;
+    const int bh = PARTIAL ? lid / (n_qtiles * n_splits) : lid / n_qtiles;
+    const size_t head_off = (size_t)bh * Nq * D;   // in elements
+    const int bidx = bh / H;
+    const int k0 = PARTIAL ? split * keys_per_split : 0;                     // this workgroup's keys:
+    const int N = PARTIAL ? min(Nk - k0, keys_per_split) : Nk;               // k0 .. k0 + N - 1
+    const size_t kv_off = ((size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * Nk + k0) * D;
+    const unsigned char* Qh = (const unsigned char*)Qv + head_off * EQ;
+    const unsigned short* V = (const unsigned short*)Vv;
+    const __amdgpu_buffer_rsrc_t krs =
+        make_rsrc((const unsigned char*)Kv + kv_off * EQ, (uint32_t)N * KROWB);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(V + kv_off, (uint32_t)N * VROWB);
+    // multiplicities of this cell; reads past the last key return 0 (those keys are zero anyway)
+    const __amdgpu_buffer_rsrc_t mrs =
+        make_rsrc(MULT ? mult + (size_t)bidx * Nk + k0 : nullptr, MULT ? (uint32_t)N * 4 : 0);
+    const int q0 = qt * BR + wave * 16 * NQ;
+
+    // ---- per-lane LDS byte offsets inside a tile; everything else is an immediate
+    // K fragment, 16-bit (kb, kk): row 16kb + n16, bytes 64kk + 16g .. +15
+    // K fragment, fp8    (kb)    : row 16kb + n16, bytes 32g .. 32g+31 (two 16-byte reads)
+    const int klane = n16 * KSTR + (FP8 ? 32 : 16) * g;
+    // V^T fragment db: rows 4g + (n16>>2) [+16], 8 bytes at column 16db + 4(n16&3).  Within a
+    // 16-lane block, lane i supplies the 8-byte piece row (i>>2), columns 4(i&3)..+3 and
+    // receives column i of all 4 rows.
+    const int vlane = KLDS + (4 * g + (n16 >> 2)) * VSTR + (4 * (n16 & 3)) * 2;
+    // staging: chunks 0..LDK-1 are K, LDK..NST-1 are V; chunk id = tid + i*256 of its tile,
+    // i.e. row tid/CH + i*(256/CH), 16-byte column tid%CH
+    const int kst_lane = (tid / KCH) * KSTR + (tid % KCH) * 16;
+    const int vst_lane = KLDS + (tid / VCH) * VSTR + (tid % VCH) * 16;
+    const int kld_lane = tid * 16, vld_lane = tid * 16;      // tiles are contiguous in HBM
+
+    // ---- Q fragments (B operands of S^T = K Q^T), held for the whole kernel: lane holds
+    // Q[q0 + 16qb + n16][k-slots of group g].  fp8 with d = 64 fills half of the k = 128 of
+    // the instruction: groups 2 and 3 hold zeros on both sides.
+    constexpr int QREGS = FP8 ? 8 : 4;
+    constexpr int QSTEPS = FP8 ? 1 : KK;
+    typedef __attribute__((ext_vector_type(QREGS))) int qfrag_t;
+    const bool k_live = !FP8 || D == 128 || g < 2;
+    qfrag_t qf[NQ][QSTEPS];
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+        int row = q0 + qb * 16 + n16;
+        row = row < Nq ? row : Nq - 1;             // rows past the end are computed and dropped
+        const unsigned char* src = Qh + (size_t)row * KROWB + (FP8 ? 32 : 16) * g;
+#pragma unroll
+        for (int kk = 0; kk < QSTEPS; ++kk) {
+            if constexpr (FP8) {
+                i32x4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
+                if (k_live) {
+                    lo = *reinterpret_cast<const i32x4*>(src);
+                    hi = *reinterpret_cast<const i32x4*>(src + 16);
+                }
+                qf[qb][kk] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            } else {
+                qf[qb][kk] = *reinterpret_cast<const i32x4*>(src + kk * 64);
+            }
+        }
+    }
+
+    f32x4 oacc[DB][NQ];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) oacc[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // spherical: zacc = per-lane partial sums of s^2 (two chains per query block)
+    // SoftMax:   zacc[qb][0] = per-lane partial denominator, zacc[qb][1] = exponent offset of
+    //            the current sub-step, mrun = running max of raw scores, apend = factor that
+    //            o still has to be multiplied with before the next stage C
+    float zacc[NQ][2], mrun[NQ], apend[NQ], anext[NQ];
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+        zacc[qb][0] = zacc[qb][1] = 0.f;
+        mrun[qb] = -INFINITY;
+        apend[qb] = anext[qb] = 1.f;
+    }
+
+    // multipliers of the lane's 8 keys (16kb + 4g + t) of a sub-step, double-buffered by parity
+    f32x4 mreg[MULT ? 2 : 1][2];
+    auto mload = [&](int par, int kb, int substep) {
+        if constexpr (MULT)
+            mreg[par][kb] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                mrs, (16 * kb + 4 * g) * 4, substep * 128, 0));
+    };
+
+    i32x4 stage[NST];
+    auto gload_chunk = [&](int c, int tile) {
+        if (c < LDK)
+            stage[c] = __builtin_amdgcn_raw_buffer_load_b128(krs, kld_lane, tile * KTILE + c * kThreads * 16, 0);
+        else
+            stage[c] = __builtin_amdgcn_raw_buffer_load_b128(vrs, vld_lane, tile * VTILE + (c - LDK) * kThreads * 16, 0);
+    };
+    auto lstore_chunk = [&](int c, SPH_LDS unsigned char* buf) {
+        const int off = c < LDK ? kst_lane + c * (kThreads / KCH) * KSTR
+                                : vst_lane + (c - LDK) * (kThreads / VCH) * VSTR;
+        *reinterpret_cast<SPH_LDS i32x4*>(buf + off) = stage[c];
+    };
+
+    const int n_tiles = (N + BC - 1) / BC;
+
+    // ---- prologue: buffer 3 plays "tile -1" (zeros) for the first stage C; tiles 0 and 1 go
+    // to buffers 0 and 1; tile 2 waits in registers
+    {
+        const i32x4 zero4 = {0, 0, 0, 0};
+        for (int i = tid; i < BUF_BYTES / 16; i += kThreads)
+            *reinterpret_cast<SPH_LDS i32x4*>(smem + 3 * BUF_BYTES + i * 16) = zero4;
+    }
+    {   // all three tiles are requested before the first is waited for: one memory latency
+        i32x4 first[2][NST];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int c = 0; c < NST; ++c) { gload_chunk(c, t); first[t][c] = stage[c]; }
+#pragma unroll
+        for (int c = 0; c < NST; ++c) gload_chunk(c, 2);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int c = 0; c < NST; ++c) {
+                const i32x4 keep = stage[c];
+                stage[c] = first[t][c];
+                lstore_chunk(c, smem + t * BUF_BYTES);
+                stage[c] = keep;
+            }
+    }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) mload(0, kb, 0);
+    __syncthreads();
+
+    // scores of a sub-step: [key block][query block]; P of a sub-step: one B operand per query block
+    f32x4 S0[2][NQ], S1[2][NQ];
+    i32x4 P0[NQ], P1[NQ];
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) { S0[kb][qb] = f32x4{0, 0, 0, 0}; S1[kb][qb] = f32x4{0, 0, 0, 0}; }
+        P0[qb] = i32x4{0, 0, 0, 0};
+        P1[qb] = i32x4{0, 0, 0, 0};
+    }
+
+    auto mfma_qk = [&](qfrag_t a, qfrag_t b, f32x4 c) -> f32x4 {
+        if constexpr (FP8)
+            return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+        else
+            return mfma16x16<HALF>(a, b, c);
+    };
+    // the two 16-byte halves of an fp8 K fragment; groups without data (d = 64) supply zeros
+    auto k8frag = [&](i32x4 lo, i32x4 hi) -> i32x8 {
+        const i32x4 zero4 = {0, 0, 0, 0};
+        if (!k_live) { lo = zero4; hi = zero4; }
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    // S0 = scores of sub-step 0
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        if constexpr (FP8) {
+            const SPH_LDS unsigned char* a = smem + klane + 16 * kb * KSTR;
+            const qfrag_t kfr = k8frag(lds_read_b128(a), lds_read_b128(a + 16));
+#pragma unroll
+            for (int qb = 0; qb < NQ; ++qb) S0[kb][qb] = mfma_qk(kfr, qf[qb][0], S0[kb][qb]);
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const qfrag_t kfr = lds_read_b128(smem + klane + 16 * kb * KSTR + 64 * kk);
+#pragma unroll
+                for (int qb = 0; qb < NQ; ++qb) S0[kb][qb] = mfma_qk(kfr, qf[qb][kk], S0[kb][qb]);
+            }
+        }
+    }
+
+    // Fragment registers.  16-bit: one K fragment per slot, in a ring.  fp8: the K fragment of
+    // key block kb arrives as two 16-byte halves with the V^T fragment of the first slot that
+    // uses it; two sets alternate between consecutive sub-steps.
+    i32x4 kf[FP8 ? 1 : RING];
+    i32x4 kf8[FP8 ? 2 : 1][2][2];
+    i32x4 vf[RING];
+    // Reads for slot u of an iteration whose tiles j-1, j, j+1 sit at bprv, bcur, bnxt:
+    //   u in [0,SLOTS)        first half : K_j sub 1,     V_{j-1} sub 1
+    //   u in [SLOTS,2SLOTS)   second half: K_{j+1} sub 0, V_j sub 0
+    //   u >= 2SLOTS           next iteration's first half: K_{j+1} sub 1, V_j sub 1
+    auto issue_reads = [&](int u, const SPH_LDS unsigned char* bprv, const SPH_LDS unsigned char* bcur,
+                           const SPH_LDS unsigned char* bnxt) {
+        const int hh = u / SLOTS, i = u % SLOTS;
+        const SPH_LDS unsigned char* kp = hh == 0 ? bcur + 32 * KSTR : hh == 1 ? bnxt : bnxt + 32 * KSTR;
+        const SPH_LDS unsigned char* vp = hh == 0 ? bprv + 32 * VSTR : hh == 1 ? bcur : bcur + 32 * VSTR;
+        // V first, K last: LDS returns in order, so the one wait in front of the slot's first
+        // matrix instruction (which needs K) covers all reads of the slot
+        const SPH_LDS unsigned char* a = vp + vlane + i * 32;
+        const i32x2 lo = lds_read_tr64(a);
+        const i32x2 hi = lds_read_tr64(a + 16 * VSTR);
+        vf[u % RING] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+        if constexpr (FP8) {
+            if (i % (SLOTS / 2) == 0) {
+                const int kb = i / (SLOTS / 2);
+                kf8[hh & 1][kb][0] = lds_read_b128(kp + klane + 16 * kb * KSTR);
+                kf8[hh & 1][kb][1] = lds_read_b128(kp + klane + 16 * kb * KSTR + 16);
+            }
+        } else {
+            const int kb = i / KK, kk = i % KK;
+            kf[u % RING] = lds_read_b128(kp + klane + 16 * kb * KSTR + 64 * kk);
+        }
+    };
+
+    // buffers of tiles j-1, j, j+1, j+2
+    SPH_LDS unsigned char* bprv = smem + 3 * BUF_BYTES;
+    SPH_LDS unsigned char* bcur = smem;
+    SPH_LDS unsigned char* bnxt = smem + BUF_BYTES;
+    SPH_LDS unsigned char* bnn = smem + 2 * BUF_BYTES;
+#pragma unroll
+    for (int u = 0; u < PD; ++u) issue_reads(u, bprv, bcur, bnxt);
+
+    for (int j = 0; j < n_tiles; ++j) {
+#pragma unroll
+        for (int s = 0; s < 2 * SLOTS; ++s) {
+            const int hf = s / SLOTS, i = s % SLOTS;
+            f32x4 (&Sn)[2][NQ] = hf == 0 ? S1 : S0;
+            f32x4 (&Sc)[2][NQ] = hf == 0 ? S0 : S1;
+            i32x4 (&Pc)[NQ] = hf == 0 ? P0 : P1;
+            i32x4 (&Pp)[NQ] = hf == 0 ? P1 : P0;
+            __builtin_amdgcn_sched_barrier(0);
+            // The one barrier per tile.  Tile j+1, written to LDS during the previous
+            // iteration, becomes visible before its first read (the prefetch below); and
+            // every wave has finished the previous iteration, whose first half was the last
+            // reader of the buffer that this iteration's second half overwrites.
+            if (s == SLOTS - PD) {
+                // LDS operations complete in issue order.  At least OUT of them have been
+                // issued since this wave's last staging write of the previous iteration, so
+                // once no more than OUT are outstanding that write has landed.  No full
+                // drain: the fragment reads already in flight keep flying across the barrier.
+                constexpr int NRD = FP8 ? 2 : 3;   // LDS reads per slot, at least
+                constexpr int OUT = NRD * (SLOTS - PD) < 15 ? NRD * (SLOTS - PD) : 15;
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0xC07F | (OUT << 8));
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
+            issue_reads(s + PD, bprv, bcur, bnxt);
+
+            // SoftMax twin: o must carry the factor from the previous sub-step's new maximum
+            // before stage C adds to it; skipped when no lane's maximum moved.  Slot i owns
+            // the accumulators of column block i, which stage C of this slot is about to use.
+            if constexpr (NORM == Norm::Softmax) {
+                bool moved = false;
+#pragma unroll
+                for (int qb = 0; qb < NQ; ++qb) moved |= apend[qb] != 1.f;
+                if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+#pragma unroll
+                    for (int qb = 0; qb < NQ; ++qb) oacc[i][qb] *= apend[qb];
+                }
+            }
+
+            // A: next sub-step's scores
+            if constexpr (FP8) {
+#pragma unroll
+                for (int u = 0; u < QKM; ++u) {
+                    const int idx = i * QKM + u, kb = idx / NQ, qb = idx % NQ;
+                    const qfrag_t kfr = k8frag(kf8[hf][kb][0], kf8[hf][kb][1]);
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    Sn[kb][qb] = mfma_qk(kfr, qf[qb][0], zero);
+                }
+            } else {
+                const int kb = i / KK, kk = i % KK;
+#pragma unroll
+                for (int qb = 0; qb < NQ; ++qb) {
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    Sn[kb][qb] = mfma_qk(kf[s % RING], qf[qb][kk], kk == 0 ? zero : Sn[kb][qb]);
+                }
+            }
+            // C: V^T fragment i (columns 16i .. 16i+15 of d) against the previous sub-step's P
+#pragma unroll
+            for (int qb = 0; qb < NQ; ++qb)
+                oacc[i][qb] = mfma16x16<HALF>(vf[s % RING], Pp[qb], oacc[i][qb]);
+
+            // B: PAIRS register pairs of the current sub-step's scores.  Pair p = (block p/2,
+            // registers 2(p%2), 2(p%2)+1); block = (kb, qb); the pair becomes register
+            // 2kb + p%2 of the B operand P[qb].
+            if constexpr (NORM == Norm::Softmax) {
+                if (i == 0) {
+                    // keys past N (ragged last tile only) must not take part in the SoftMax
+                    const int key0 = (2 * j + hf) * 32;      // first key of the current sub-step
+                    if (key0 + 32 > N) {
+#pragma unroll
+                        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                            for (int qb = 0; qb < NQ; ++qb)
+#pragma unroll
+                                for (int t = 0; t < 4; ++t)
+                                    if (key0 + 16 * kb + 4 * g + t >= N) Sc[kb][qb][t] = -INFINITY;
+                    }
+#pragma unroll
+                    for (int qb = 0; qb < NQ; ++qb) {
+                        float mx = fmaxf(Sc[0][qb][0], Sc[1][qb][0]);
+#pragma unroll
+                        for (int t = 1; t < 4; ++t) mx = fmaxf(mx, fmaxf(Sc[0][qb][t], Sc[1][qb][t]));
+                        mx = max_across_groups(mx);
+                        const float mnew = fmaxf(mrun[qb], mx);
+                        anext[qb] = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * scale_log2);
+                        mrun[qb] = mnew;
+                        zacc[qb][0] *= anext[qb];
+                        zacc[qb][1] = -mnew * scale_log2;    // offset of this sub-step's exponents
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < PAIRS; ++u) {
+                const int p = i * PAIRS + u;
+                const int blkid = p / 2, c = p % 2, kb = blkid / NQ, qb = blkid % NQ;
+                float a = Sc[kb][qb][2 * c], b = Sc[kb][qb][2 * c + 1];
+                if constexpr (MULT) {
+                    a *= mreg[hf][kb][2 * c];
+                    b *= mreg[hf][kb][2 * c + 1];
+                }
+                if constexpr (NORM == Norm::Spherical) {           // a2 = x^2, a1 = x
+                    zacc[qb][0] = __builtin_fmaf(a, a, zacc[qb][0]);
+                    zacc[qb][1] = __builtin_fmaf(b, b, zacc[qb][1]);
+                } else if constexpr (NORM == Norm::L1) {           // a2 = |x|, a1 = x
+                    zacc[qb][0] += __builtin_fabsf(a);
+                    zacc[qb][1] += __builtin_fabsf(b);
+                } else if constexpr (NORM == Norm::SqRelu) {       // a1 = a2 = relu(x)^2
+                    a = fmaxf(a, 0.f);
+                    b = fmaxf(b, 0.f);
+                    a *= a;
+                    b *= b;
+                    zacc[qb][0] += a;
+                    zacc[qb][1] += b;
+                } else {                                            // a1 = a2 = exp(x/sqrt(d) - max)
+                    a = __builtin_amdgcn_exp2f(__builtin_fmaf(a, scale_log2, zacc[qb][1]));
+                    b = __builtin_amdgcn_exp2f(__builtin_fmaf(b, scale_log2, zacc[qb][1]));
+                    zacc[qb][0] += a + b;
+                }
+                Pc[qb][2 * kb + c] = pack2<HALF>(a, b);
+            }
+#pragma unroll
+            for (int qb = 0; qb < NQ; ++qb) {      // keep the running sums where they were computed
+                if constexpr (NORM == Norm::Softmax) asm volatile("" : "+v"(zacc[qb][0]));
+                else asm volatile("" : "+v"(zacc[qb][0]), "+v"(zacc[qb][1]));
+            }
+            if constexpr (NORM == Norm::Softmax) {
+                if (i == SLOTS - 1) {
+#pragma unroll
+                    for (int qb = 0; qb < NQ; ++qb) apend[qb] = anext[qb];
+                }
+            }
+            if (MULT && i < 2) mload(hf ^ 1, i, 2 * j + hf + 1);
+            // staging, second half only: tile j+2 into LDS, tile j+3 out of HBM/L2
+            if (hf == 1 && i < NST) {
+                lstore_chunk(i, bnn);
+                gload_chunk(i, j + 3);
+            }
+            // issue order inside the slot: after each matrix instruction, at most one LDS read
+            // and one VALU instruction, so that the matrix pipe never waits on the issue port
+            if constexpr (NORM != Norm::Softmax) {
+                constexpr int NM = QKM + NQ;
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                    if (m < 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+                    __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);   // VALU
+                    if (hf == 1 && m == NM - 2) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
+                    if (hf == 1 && m == NM - 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
+                }
+            }
+        }
+        SPH_LDS unsigned char* t = bprv; bprv = bcur; bcur = bnxt; bnxt = bnn; bnn = t;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- drain: stage C of the last sub-step (V of the last tile, sub 1, now at bprv)
+    {
+        const SPH_LDS unsigned char* vp = bprv + 32 * VSTR;
+#pragma unroll
+        for (int i = 0; i < SLOTS; ++i) {
+            const SPH_LDS unsigned char* a = vp + vlane + i * 32;
+            const i32x2 lo = lds_read_tr64(a);
+            const i32x2 hi = lds_read_tr64(a + 16 * VSTR);
+            const i32x4 vfr = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+#pragma unroll
+            for (int qb = 0; qb < NQ; ++qb) {
+                if constexpr (NORM == Norm::Softmax) oacc[i][qb] *= apend[qb];
+                oacc[i][qb] = mfma16x16<HALF>(vfr, P1[qb], oacc[i][qb]);
+            }
+        }
+    }
+
+    // ---- partial result: the pair (o, z) as it stands, in fp32
+    if constexpr (PARTIAL) {
+        const size_t rows0 = ((size_t)split * (n_wg / (n_qtiles * n_splits)) + bh) * Nq;
+        float* Op = (float*)Ov + rows0 * D;
+        float* Zp = Zv + rows0;
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) {
+            const float z = sum_across_groups(zacc[qb][0] + zacc[qb][1]);
+            const int row = q0 + qb * 16 + n16;
+            if (row < Nq) {
+                if (g == 0) Zp[row] = z;
+                float* dst = Op + (size_t)row * D + 4 * g;
+#pragma unroll
+                for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(dst + db * 16) = oacc[db][qb];
+            }
+        }
+        return;
+    }
+
+    // ---- tail t(o, z) = o / b(z): spherical b = sqrt, the others b = id
+    unsigned short* Oh = (unsigned short*)Ov + head_off;
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+        float inv, z;
+        if constexpr (NORM == Norm::Spherical) {
+            z = sum_across_groups(zacc[qb][0] + zacc[qb][1]);
+            inv = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
+        } else if constexpr (NORM == Norm::Softmax) {
+            z = sum_across_groups(zacc[qb][0]);
+            inv = 1.0f / z;
+        } else {
+            z = sum_across_groups(zacc[qb][0] + zacc[qb][1]);
+            inv = z > 0.f ? 1.0f / z : 0.f;
+        }
+        const int row = q0 + qb * 16 + n16;
+        if (row < Nq) {
+            if (Zv != nullptr && g == 0) Zv[(size_t)bh * Nq + row] = z;
+            unsigned short* dst = Oh + (size_t)row * D + 4 * g;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const i32x2 o4 = {pack2<HALF>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
+                                  pack2<HALF>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
+                *reinterpret_cast<i32x2*>(dst + db * 16) = o4;
+            }
+        }
+    }
+}
+
+}  // namespace sphattn
