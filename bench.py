@@ -152,7 +152,16 @@ def main() -> int:
         _, per_t = time_launches(twin, max(10, args.steps // 4), max(5, args.warmup // 4))
         ms_t = sum(per_t) / len(per_t)
         result["softmax_twin"] = {"kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12,
-                                  "spherical_speedup": ms_t / ms_kernel}
+                                  "spherical_speedup": ms_t / ms_kernel,
+                                  "form": "32x32x16 MFMA, the fastest SoftMax form here"}
+
+        def twin16():
+            pkg.sphattn_normalized_fwd(qd, kd, vd, out, dtype=w.dtype, normalizer="softmax")
+        _, per_t = time_launches(twin16, max(10, args.steps // 4), max(5, args.warmup // 4))
+        ms_t = sum(per_t) / len(per_t)
+        result["softmax_twin_same_instructions"] = {
+            "kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12, "spherical_speedup": ms_t / ms_kernel,
+            "form": "16x16x32 MFMA, the spherical kernel with exp/max/rescale in stage B"}
 
     if args.grn:
         g = torch.Generator(device="cpu").manual_seed(w.seed + 1000)

@@ -108,7 +108,9 @@ int sphattn_grn_fwd(const void* Q, const void* K, const void* V, const float* mu
 /*
  * Attention with any of the normalizers above in place of the SoftMax (paper, Theorem 1: every
  * normalized contraction streams the same way; only the per-score functions and the tail
- * change).  SPHATTN_NORM_L2 is sphattn_fwd, SPHATTN_NORM_SOFTMAX is sphattn_softmax_fwd.
+ * change).  SPHATTN_NORM_L2 is sphattn_fwd; SPHATTN_NORM_SOFTMAX computes what
+ * sphattn_softmax_fwd computes, on the family's kernel (the same matrix instructions as the
+ * spherical case) instead of the SoftMax-specific one.
  * A row whose aggregate sum_j a2(s_ij) is 0 gives 0.  dtype must be SPHATTN_BF16 unless the
  * normalizer is SPHATTN_NORM_L2.  Other arguments, layout, ownership and errors as sphattn_fwd;
  * an unknown normalizer returns SPHATTN_ERR_NORMALIZER.
@@ -120,7 +122,9 @@ int sphattn_normalized_fwd(const void* Q, const void* K, const void* V, void* O,
  * Comparison twin on the same tiling skeleton: standard SoftMax attention,
  * O = softmax(Q K^T / sqrt(d)) V, i.e. the same normalized contraction with
  * a1 = a2 = exp, b = id, computed with the usual running-maximum rescaling.
- * It exists to measure what the exponential costs (paper, Section 1).
+ * It exists to measure what the exponential costs (paper, Section 1), so it runs in the
+ * form that is fastest for SoftMax (32x32x16 matrix instructions, which hide the
+ * quarter-rate exponential better than the 16x16x32 ones of the spherical kernel).
  * Same arguments, layout, ownership and error behaviour as sphattn_fwd;
  * dtype must be SPHATTN_BF16.
  */

@@ -3,6 +3,7 @@
 // never synchronises.
 #include "sphattn_device.hpp"
 #include "sphattn_pipelined.hpp"
+#include "sphattn_softmax32.hpp"
 #include "../../include/sphattn.h"
 
 #include <stdint.h>
@@ -144,6 +145,23 @@ int launch_f32(const Problem& p)
                        (const float*)p.Q, (const float*)p.K, (const float*)p.V, (float*)p.O, p.mult, p.Z,
                        p.Nq, p.Nk, p.H, p.H / p.H_kv, n_qtiles, (int)n_wg,
                        p.n_splits, p.keys_per_split);
+    return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
+}
+
+template <int D>
+int launch_softmax32(const Problem& p)
+{
+    constexpr int BR = 256;
+    constexpr int lds_bytes = kNBuf * kBC * (D * 2 + kKPad + D * 2 + kVPad);
+    auto kern = softmax32_kernel<D>;
+    static std::atomic<uint64_t> done{0};
+    if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;
+    const int n_qtiles = (p.Nq + BR - 1) / BR;
+    const long long n_wg = (long long)p.B * p.H * n_qtiles;
+    if (n_wg > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    const float scale_log2 = 1.4426950408889634f / __builtin_sqrtf((float)D);
+    hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, p.stream,
+                       p.Q, p.K, p.V, p.O, p.Nq, n_qtiles, (int)n_wg, scale_log2);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
@@ -290,7 +308,7 @@ int sphattn_softmax_fwd(const void* Q, const void* K, const void* V, void* O,
     if (rc != SPHATTN_OK) return rc;
     if (dtype != SPHATTN_BF16) return SPHATTN_ERR_DTYPE;
     const Problem p{Q, K, V, O, nullptr, nullptr, B, H, H, N, N, (hipStream_t)stream};
-    return dispatch<Norm::Softmax, false>(p, d, dtype);
+    return d == 128 ? launch_softmax32<128>(p) : launch_softmax32<64>(p);
 }
 
 int sphattn_partial_fwd(const void* Q, const void* K, const void* V, const float* mult,

@@ -122,7 +122,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     constexpr int PAIRS = 4 * NQ / SLOTS;          // score register pairs of stage B per slot
     constexpr int PD = 3;                          // LDS prefetch distance in slots
     constexpr int RING = 4;                        // fragment registers in rotation
-    constexpr int VALU_PER_MFMA = 1;               // VALU instructions issued behind each MFMA (measured best of 1..4)
+    // VALU instructions issued behind each MFMA (measured best of 1..4; SoftMax: of 0..6)
+    constexpr int VALU_PER_MFMA = NORM == Norm::Softmax ? 3 : 1;
     static_assert(D == 64 || D == 128, "head dimension 128 or 64");
     static_assert(NQ == 4 || NQ == 2, "64 or 32 query rows per wave");
     static_assert(FP8 || 2 * KK == SLOTS, "16-bit: one K fragment (key block, k-step) per slot");
@@ -382,15 +383,19 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             issue_reads(s + PD, bprv, bcur, bnxt);
 
             // SoftMax twin: o must carry the factor from the previous sub-step's new maximum
-            // before stage C adds to it; skipped when no lane's maximum moved.  Slot i owns
-            // the accumulators of column block i, which stage C of this slot is about to use.
+            // before stage C adds to it.  One test per sub-step; the whole accumulator is
+            // rescaled in the (rare, once the maxima have settled) case that a maximum moved.
             if constexpr (NORM == Norm::Softmax) {
-                bool moved = false;
+                if (i == 0) {
+                    bool moved = false;
 #pragma unroll
-                for (int qb = 0; qb < NQ; ++qb) moved |= apend[qb] != 1.f;
-                if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+                    for (int qb = 0; qb < NQ; ++qb) moved |= apend[qb] != 1.f;
+                    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
 #pragma unroll
-                    for (int qb = 0; qb < NQ; ++qb) oacc[i][qb] *= apend[qb];
+                        for (int db = 0; db < DB; ++db)
+#pragma unroll
+                            for (int qb = 0; qb < NQ; ++qb) oacc[db][qb] *= apend[qb];
+                    }
                 }
             }
 
@@ -494,7 +499,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             }
             // issue order inside the slot: after each matrix instruction, at most one LDS read
             // and one VALU instruction, so that the matrix pipe never waits on the issue port
-            if constexpr (NORM != Norm::Softmax) {
+            {
                 constexpr int NM = QKM + NQ;
 #pragma unroll
                 for (int m = 0; m < NM; ++m) {
