@@ -39,9 +39,10 @@
 //     C(t-1)  O^T += V^T P^T         matrix cores <- P registers (previous)
 // A sub-step is cut into SLOTS slots (one V^T fragment each); LDS fragment reads run PD slots
 // ahead of their use, across sub-step and tile boundaries.  K/V tiles of 64 keys rotate through
-// four LDS buffers: in iteration j tiles j and j+1 feed stage A, tiles j-1 and j feed stage C,
-// tile j+2 is written and tile j+3 is on its way from HBM/L2 into registers, with one workgroup
-// barrier per tile.  Global loads go through buffer descriptors whose range check returns
+// four LDS buffers: in iteration j tiles j and j+1 feed stage A, tiles j-1 and j feed stage C
+// and tile j+2 is on its way from HBM/L2 straight into LDS (buffer_load ... lds, no registers
+// and no LDS store instructions in between), with one workgroup barrier per tile.  Global
+// loads go through buffer descriptors whose range check returns
 // zeros past the end of the head: a zero key contributes nothing to o or z, so ragged N needs
 // no masking in the spherical case.
 //
@@ -94,6 +95,25 @@ __device__ __forceinline__ float sum_across_groups(float x)
     return sum_across_halves(r.lo + r.hi);
 }
 
+// The four words of a raw buffer descriptor (base, no stride, size in bytes, 32-bit raw format)
+// for use as an inline-assembly operand.
+__device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes)
+{
+    const uint64_t a = (uint64_t)base;
+    return i32x4{(int)(uint32_t)a, (int)(uint32_t)(a >> 32) & 0xffff, (int)bytes, 0x00020000};
+}
+
+// One 1 KB global -> LDS copy: lane l fetches 16 bytes at rsrc[voff + soff] and they land at LDS
+// byte lds + 16 l (buffer_load_dwordx4 ... lds takes its LDS base from M0).  Written as inline
+// assembly so that the compiler does not make every later LDS read wait for the copy: the
+// kernel orders copies and reads itself, with one vmcnt wait and a barrier per tile.  Bytes
+// outside the descriptor's range arrive as zeros.
+__device__ __forceinline__ void copy_to_lds(i32x4 rsrc, uint32_t lds, int voff, int soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+
 template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
 __global__ __launch_bounds__(kThreads, 1)
 void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv,
@@ -109,13 +129,18 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     constexpr int EQ = FP8 ? 1 : 2;                // bytes per Q/K element
     constexpr int KROWB = D * EQ, KCH = KROWB / 16, KTILE = BC * KROWB;   // as stored in HBM
     constexpr int VROWB = D * 2, VCH = VROWB / 16, VTILE = BC * VROWB;
-    constexpr int KSTR = KROWB + kKPad, VSTR = VROWB + kVPad;             // LDS row strides
-    constexpr int KLDS = BC * KSTR;                                        // K tile in LDS
-    constexpr int BUF_BYTES = KLDS + BC * VSTR;    // K tile then V tile
-    constexpr int LDK = BC * KCH / kThreads;       // 16-byte chunks per thread per K tile
-    constexpr int LDV = BC * VCH / kThreads;
-    constexpr int NST = LDK + LDV;                 // staged chunks per thread per tile
     constexpr int DB = D / 16;                     // 16-column blocks of the head dimension
+    // LDS image of a tile: fragment-sized blocks, each contiguous, so that a wave's 1 KB
+    // global->LDS copy fills whole blocks and every fragment read is linear in the lane id
+    // (no padding, no swizzle, no bank conflicts):
+    //   K block (rb, c): key rows 16rb..16rb+15 x bytes 64c..64c+63, row-major, 1 KB
+    //   V block (rb, db): key rows 16rb..16rb+15 x bytes 32db..32db+31, row-major, 512 B
+    constexpr int KBLK = KROWB / 64;               // K blocks per 16 rows
+    constexpr int KLDS = KTILE;                    // K tile in LDS
+    constexpr int BUF_BYTES = KTILE + VTILE;       // K tile then V tile
+    constexpr int LDK = KBLK;                      // 1 KB copies per wave per K tile (wave w: rows 16w..16w+15)
+    constexpr int LDV = DB / 2;                    // ... per V tile (two V blocks each)
+    constexpr int NST = LDK + LDV;
     constexpr int SLOTS = DB;                      // slots per sub-step: one V^T fragment each
     constexpr int KK = D / 32;                     // 16-bit: k-steps of K Q^T
     constexpr int QKM = FP8 ? 2 * NQ / SLOTS : NQ; // score matrix instructions per slot
@@ -128,7 +153,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     static_assert(NQ == 4 || NQ == 2, "64 or 32 query rows per wave");
     static_assert(FP8 || 2 * KK == SLOTS, "16-bit: one K fragment (key block, k-step) per slot");
     static_assert(!FP8 || (2 * NQ) % SLOTS == 0, "fp8: whole score instructions per slot");
-    static_assert(PAIRS >= 1 && NST <= SLOTS, "slot plan");
+    static_assert(PAIRS >= 1 && NST <= SLOTS + PD - 1, "slot plan");
+    static_assert(KCH >= 1 && VCH >= 1, "rows are whole 16-byte chunks");
     static_assert((2 * SLOTS) % RING == 0 && PD < RING && PD <= SLOTS, "ring indices must repeat");
     static_assert(QKT == QKType::Bf16 || NORM == Norm::Spherical, "fp8 and fp16 storage: spherical only");
     static_assert(!MULT || NORM == Norm::Spherical, "multiplicities belong to the spherical variant");
@@ -153,27 +179,27 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     const size_t kv_off = ((size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * Nk + k0) * D;
     const unsigned char* Qh = (const unsigned char*)Qv + head_off * EQ;
     const unsigned short* V = (const unsigned short*)Vv;
-    const __amdgpu_buffer_rsrc_t krs =
-        make_rsrc((const unsigned char*)Kv + kv_off * EQ, (uint32_t)N * KROWB);
-    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(V + kv_off, (uint32_t)N * VROWB);
     // multiplicities of this cell; reads past the last key return 0 (those keys are zero anyway)
     const __amdgpu_buffer_rsrc_t mrs =
         make_rsrc(MULT ? mult + (size_t)bidx * Nk + k0 : nullptr, MULT ? (uint32_t)N * 4 : 0);
     const int q0 = qt * BR + wave * 16 * NQ;
 
     // ---- per-lane LDS byte offsets inside a tile; everything else is an immediate
-    // K fragment, 16-bit (kb, kk): row 16kb + n16, bytes 64kk + 16g .. +15
-    // K fragment, fp8    (kb)    : row 16kb + n16, bytes 32g .. 32g+31 (two 16-byte reads)
-    const int klane = n16 * KSTR + (FP8 ? 32 : 16) * g;
-    // V^T fragment db: rows 4g + (n16>>2) [+16], 8 bytes at column 16db + 4(n16&3).  Within a
-    // 16-lane block, lane i supplies the 8-byte piece row (i>>2), columns 4(i&3)..+3 and
-    // receives column i of all 4 rows.
-    const int vlane = KLDS + (4 * g + (n16 >> 2)) * VSTR + (4 * (n16 & 3)) * 2;
-    // staging: chunks 0..LDK-1 are K, LDK..NST-1 are V; chunk id = tid + i*256 of its tile,
-    // i.e. row tid/CH + i*(256/CH), 16-byte column tid%CH
-    const int kst_lane = (tid / KCH) * KSTR + (tid % KCH) * 16;
-    const int vst_lane = KLDS + (tid / VCH) * VSTR + (tid % VCH) * 16;
-    const int kld_lane = tid * 16, vld_lane = tid * 16;      // tiles are contiguous in HBM
+    // K fragment, 16-bit (kb, kk): row 16kb + n16, bytes 64kk + 16g .. +15: block (kb, kk), offset
+    //                              64 n16 + 16 g
+    // K fragment, fp8    (kb)    : row 16kb + n16, bytes 32g .. 32g+31 (two 16-byte reads): block
+    //                              (kb, g/2), offset 64 n16 + 32 (g%2); groups without data (d = 64)
+    //                              read the only block and are zeroed afterwards
+    const int klane = FP8 ? ((g >> 1) % KBLK) * 1024 + n16 * 64 + (g & 1) * 32 : n16 * 64 + g * 16;
+    // V^T fragment db: rows 4g + (n16>>2) [+16], 8 bytes at column 16db + 4(n16&3): block
+    // (0 [1], db), offset 32 (4g + (n16>>2)) + 8 (n16&3) = 8 lane.  Within a 16-lane block, lane i
+    // supplies the 8-byte piece row (i>>2), columns 4(i&3)..+3 and receives column i of all 4 rows.
+    const int vlane = KLDS + lane * 8;
+    // global -> LDS copies: lane l of a copy lands at LDS byte 16 l of the copy's 1 KB
+    //   K copy c of wave w: block (w, c): row 16w + l/4, bytes 64c + 16 (l%4)
+    //   V copy c of wave w: blocks (w, 2c), (w, 2c+1): row 16w + (l%32)/2, bytes 64c + 32 (l/32) + 16 (l%2)
+    const int kld_lane = (16 * wave + (lane >> 2)) * KROWB + (lane & 3) * 16;
+    const int vld_lane = (16 * wave + ((lane & 31) >> 1)) * VROWB + (lane >> 5) * 32 + (lane & 1) * 16;
 
     // ---- Q fragments (B operands of S^T = K Q^T), held for the whole kernel: lane holds
     // Q[q0 + 16qb + n16][k-slots of group g].  fp8 with d = 64 fills half of the k = 128 of
@@ -228,48 +254,35 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                 mrs, (16 * kb + 4 * g) * 4, substep * 128, 0));
     };
 
-    i32x4 stage[NST];
-    auto gload_chunk = [&](int c, int tile) {
+    // copy c (K: c < LDK, V: the rest) of this wave's share of tile `tile` into buffer `buf`.
+    // Rows past the end of the head are out of the descriptor's range and arrive as zeros.
+    const i32x4 krw = rsrc_words((const unsigned char*)Kv + kv_off * EQ, (uint32_t)N * KROWB);
+    const i32x4 vrw = rsrc_words(V + kv_off, (uint32_t)N * VROWB);
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto copy_chunk = [&](int c, int tile, SPH_LDS unsigned char* buf) {
+        const uint32_t base = (uint32_t)(uintptr_t)buf;
         if (c < LDK)
-            stage[c] = __builtin_amdgcn_raw_buffer_load_b128(krs, kld_lane, tile * KTILE + c * kThreads * 16, 0);
+            copy_to_lds(krw, base + (wave_u * KBLK + c) * 1024, kld_lane, tile * KTILE + c * 64);
         else
-            stage[c] = __builtin_amdgcn_raw_buffer_load_b128(vrs, vld_lane, tile * VTILE + (c - LDK) * kThreads * 16, 0);
-    };
-    auto lstore_chunk = [&](int c, SPH_LDS unsigned char* buf) {
-        const int off = c < LDK ? kst_lane + c * (kThreads / KCH) * KSTR
-                                : vst_lane + (c - LDK) * (kThreads / VCH) * VSTR;
-        *reinterpret_cast<SPH_LDS i32x4*>(buf + off) = stage[c];
+            copy_to_lds(vrw, base + KLDS + (wave_u * DB + 2 * (c - LDK)) * 512, vld_lane, tile * VTILE + (c - LDK) * 64);
     };
 
     const int n_tiles = (N + BC - 1) / BC;
 
     // ---- prologue: buffer 3 plays "tile -1" (zeros) for the first stage C; tiles 0 and 1 go
-    // to buffers 0 and 1; tile 2 waits in registers
+    // to buffers 0 and 1
     {
         const i32x4 zero4 = {0, 0, 0, 0};
         for (int i = tid; i < BUF_BYTES / 16; i += kThreads)
             *reinterpret_cast<SPH_LDS i32x4*>(smem + 3 * BUF_BYTES + i * 16) = zero4;
     }
-    {   // all three tiles are requested before the first is waited for: one memory latency
-        i32x4 first[2][NST];
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int c = 0; c < NST; ++c) { gload_chunk(c, t); first[t][c] = stage[c]; }
-#pragma unroll
-        for (int c = 0; c < NST; ++c) gload_chunk(c, 2);
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int c = 0; c < NST; ++c) {
-                const i32x4 keep = stage[c];
-                stage[c] = first[t][c];
-                lstore_chunk(c, smem + t * BUF_BYTES);
-                stage[c] = keep;
-            }
-    }
+        for (int c = 0; c < NST; ++c) copy_chunk(c, t, smem + t * BUF_BYTES);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) mload(0, kb, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's copies have landed
     __syncthreads();
 
     // scores of a sub-step: [key block][query block]; P of a sub-step: one B operand per query block
@@ -300,14 +313,14 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
         if constexpr (FP8) {
-            const SPH_LDS unsigned char* a = smem + klane + 16 * kb * KSTR;
+            const SPH_LDS unsigned char* a = smem + klane + kb * KBLK * 1024;
             const qfrag_t kfr = k8frag(lds_read_b128(a), lds_read_b128(a + 16));
 #pragma unroll
             for (int qb = 0; qb < NQ; ++qb) S0[kb][qb] = mfma_qk(kfr, qf[qb][0], S0[kb][qb]);
         } else {
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                const qfrag_t kfr = lds_read_b128(smem + klane + 16 * kb * KSTR + 64 * kk);
+                const qfrag_t kfr = lds_read_b128(smem + klane + (kb * KBLK + kk) * 1024);
 #pragma unroll
                 for (int qb = 0; qb < NQ; ++qb) S0[kb][qb] = mfma_qk(kfr, qf[qb][kk], S0[kb][qb]);
             }
@@ -327,23 +340,24 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     auto issue_reads = [&](int u, const SPH_LDS unsigned char* bprv, const SPH_LDS unsigned char* bcur,
                            const SPH_LDS unsigned char* bnxt) {
         const int hh = u / SLOTS, i = u % SLOTS;
-        const SPH_LDS unsigned char* kp = hh == 0 ? bcur + 32 * KSTR : hh == 1 ? bnxt : bnxt + 32 * KSTR;
-        const SPH_LDS unsigned char* vp = hh == 0 ? bprv + 32 * VSTR : hh == 1 ? bcur : bcur + 32 * VSTR;
+        // second sub-step of a tile: key rows 32..63 = row blocks 2 and 3
+        const SPH_LDS unsigned char* kp = hh == 0 ? bcur + 2 * KBLK * 1024 : hh == 1 ? bnxt : bnxt + 2 * KBLK * 1024;
+        const SPH_LDS unsigned char* vp = hh == 0 ? bprv + 2 * DB * 512 : hh == 1 ? bcur : bcur + 2 * DB * 512;
         // V first, K last: LDS returns in order, so the one wait in front of the slot's first
         // matrix instruction (which needs K) covers all reads of the slot
-        const SPH_LDS unsigned char* a = vp + vlane + i * 32;
+        const SPH_LDS unsigned char* a = vp + vlane + i * 512;
         const i32x2 lo = lds_read_tr64(a);
-        const i32x2 hi = lds_read_tr64(a + 16 * VSTR);
+        const i32x2 hi = lds_read_tr64(a + DB * 512);
         vf[u % RING] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
         if constexpr (FP8) {
             if (i % (SLOTS / 2) == 0) {
                 const int kb = i / (SLOTS / 2);
-                kf8[hh & 1][kb][0] = lds_read_b128(kp + klane + 16 * kb * KSTR);
-                kf8[hh & 1][kb][1] = lds_read_b128(kp + klane + 16 * kb * KSTR + 16);
+                kf8[hh & 1][kb][0] = lds_read_b128(kp + klane + kb * KBLK * 1024);
+                kf8[hh & 1][kb][1] = lds_read_b128(kp + klane + kb * KBLK * 1024 + 16);
             }
         } else {
             const int kb = i / KK, kk = i % KK;
-            kf[u % RING] = lds_read_b128(kp + klane + 16 * kb * KSTR + 64 * kk);
+            kf[u % RING] = lds_read_b128(kp + klane + (kb * KBLK + kk) * 1024);
         }
     };
 
@@ -364,19 +378,16 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             i32x4 (&Pc)[NQ] = hf == 0 ? P0 : P1;
             i32x4 (&Pp)[NQ] = hf == 0 ? P1 : P0;
             __builtin_amdgcn_sched_barrier(0);
-            // The one barrier per tile.  Tile j+1, written to LDS during the previous
-            // iteration, becomes visible before its first read (the prefetch below); and
-            // every wave has finished the previous iteration, whose first half was the last
-            // reader of the buffer that this iteration's second half overwrites.
+            // The one barrier per tile.  Tile j+1, copied into LDS during the previous
+            // iteration, becomes visible before its first read (the prefetch below): every wave
+            // waits for its own copies (all but the youngest vector-memory operations, which are
+            // this sub-step's multiplicity loads) and then for the others.  Past the barrier
+            // every wave has also finished the previous iteration, whose first half was the
+            // last reader of the buffer that this iteration's copies overwrite.
             if (s == SLOTS - PD) {
-                // LDS operations complete in issue order.  At least OUT of them have been
-                // issued since this wave's last staging write of the previous iteration, so
-                // once no more than OUT are outstanding that write has landed.  No full
-                // drain: the fragment reads already in flight keep flying across the barrier.
-                constexpr int NRD = FP8 ? 2 : 3;   // LDS reads per slot, at least
-                constexpr int OUT = NRD * (SLOTS - PD) < 15 ? NRD * (SLOTS - PD) : 15;
                 asm volatile("" ::: "memory");
-                __builtin_amdgcn_s_waitcnt(0xC07F | (OUT << 8));
+                constexpr int YOUNGER = MULT ? (SLOTS - PD < 2 ? SLOTS - PD : 2) : 0;
+                __builtin_amdgcn_s_waitcnt(0x0F70 | YOUNGER);         // vmcnt(YOUNGER)
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
             }
@@ -492,11 +503,10 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                 }
             }
             if (MULT && i < 2) mload(hf ^ 1, i, 2 * j + hf + 1);
-            // staging, second half only: tile j+2 into LDS, tile j+3 out of HBM/L2
-            if (hf == 1 && i < NST) {
-                lstore_chunk(i, bnn);
-                gload_chunk(i, j + 3);
-            }
+            // copies of tile j+2 out of HBM/L2 into the free buffer, one per slot, right after
+            // the barrier: they have a whole tile's time to land
+            constexpr int FIRST_COPY = SLOTS - PD + 1;
+            if (s >= FIRST_COPY && s < FIRST_COPY + NST) copy_chunk(s - FIRST_COPY, j + 2, bnn);
             // issue order inside the slot: after each matrix instruction, at most one LDS read
             // and one VALU instruction, so that the matrix pipe never waits on the issue port
             {
@@ -506,8 +516,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
                     if (m < 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
                     __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);   // VALU
-                    if (hf == 1 && m == NM - 2) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
-                    if (hf == 1 && m == NM - 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
+                    if (s >= FIRST_COPY && s < FIRST_COPY + NST && m == NM - 1)
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (the copy)
                 }
             }
         }
@@ -517,12 +527,12 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
 
     // ---- drain: stage C of the last sub-step (V of the last tile, sub 1, now at bprv)
     {
-        const SPH_LDS unsigned char* vp = bprv + 32 * VSTR;
+        const SPH_LDS unsigned char* vp = bprv + 2 * DB * 512;
 #pragma unroll
         for (int i = 0; i < SLOTS; ++i) {
-            const SPH_LDS unsigned char* a = vp + vlane + i * 32;
+            const SPH_LDS unsigned char* a = vp + vlane + i * 512;
             const i32x2 lo = lds_read_tr64(a);
-            const i32x2 hi = lds_read_tr64(a + 16 * VSTR);
+            const i32x2 hi = lds_read_tr64(a + DB * 512);
             const i32x4 vfr = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
 #pragma unroll
             for (int qb = 0; qb < NQ; ++qb) {
