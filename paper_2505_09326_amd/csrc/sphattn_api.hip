@@ -115,7 +115,7 @@ int launch_pipelined(const Problem& p)
 {
     constexpr int BR = kWaves * 16 * NQ;
     constexpr int EQ = QKT == QKType::Fp8 ? 1 : 2;
-    constexpr int lds_bytes = kNBuf * kBC * (D * EQ + D * 2);
+    constexpr int lds_bytes = kNBuf * kBC * (D * EQ + D * 2 + (MULT ? 4 : 0));
     auto kern = fwd_pipelined_kernel<D, NQ, QKT, NORM, MULT, PARTIAL>;
     static std::atomic<uint64_t> done{0};
     if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;

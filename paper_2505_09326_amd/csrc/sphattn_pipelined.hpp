@@ -137,18 +137,22 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     //   V block (rb, db): key rows 16rb..16rb+15 x bytes 32db..32db+31, row-major, 512 B
     constexpr int KBLK = KROWB / 64;               // K blocks per 16 rows
     constexpr int KLDS = KTILE;                    // K tile in LDS
-    constexpr int BUF_BYTES = KTILE + VTILE;       // K tile then V tile
+    constexpr int MLDS = KTILE + VTILE;            // the tile's 64 multiplicities (MULT only)
+    constexpr int BUF_BYTES = KTILE + VTILE + (MULT ? BC * 4 : 0);   // K tile, V tile, multiplicities
     constexpr int LDK = KBLK;                      // 1 KB copies per wave per K tile (wave w: rows 16w..16w+15)
     constexpr int LDV = DB / 2;                    // ... per V tile (two V blocks each)
-    constexpr int NST = LDK + LDV;
+    constexpr int NST = LDK + LDV + (MULT ? 1 : 0);   // and one 256-byte copy (wave 0) of multiplicities
     constexpr int SLOTS = DB;                      // slots per sub-step: one V^T fragment each
     constexpr int KK = D / 32;                     // 16-bit: k-steps of K Q^T
     constexpr int QKM = FP8 ? 2 * NQ / SLOTS : NQ; // score matrix instructions per slot
     constexpr int PAIRS = 4 * NQ / SLOTS;          // score register pairs of stage B per slot
-    constexpr int PD = 3;                          // LDS prefetch distance in slots
+    constexpr int NBUF = kNBuf;                    // LDS tile buffers in rotation (a fifth, with copies
+                                                   // issued a tile earlier, measured no faster)
+    constexpr int PD = 3;                          // LDS prefetch distance in slots (2: no faster)
     constexpr int RING = 4;                        // fragment registers in rotation
     // VALU instructions issued behind each MFMA (measured best of 1..4; SoftMax: of 0..6)
-    constexpr int VALU_PER_MFMA = NORM == Norm::Softmax ? 3 : 1;
+    constexpr int VALU_PER_MFMA = NORM == Norm::Softmax ? 3 : MULT ? 2 : 1;
+    static_assert(NBUF == 4, "tiles j-1 .. j+2 are resident");
     static_assert(D == 64 || D == 128, "head dimension 128 or 64");
     static_assert(NQ == 4 || NQ == 2, "64 or 32 query rows per wave");
     static_assert(FP8 || 2 * KK == SLOTS, "16-bit: one K fragment (key block, k-step) per slot");
@@ -179,9 +183,6 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     const size_t kv_off = ((size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * Nk + k0) * D;
     const unsigned char* Qh = (const unsigned char*)Qv + head_off * EQ;
     const unsigned short* V = (const unsigned short*)Vv;
-    // multiplicities of this cell; reads past the last key return 0 (those keys are zero anyway)
-    const __amdgpu_buffer_rsrc_t mrs =
-        make_rsrc(MULT ? mult + (size_t)bidx * Nk + k0 : nullptr, MULT ? (uint32_t)N * 4 : 0);
     const int q0 = qt * BR + wave * 16 * NQ;
 
     // ---- per-lane LDS byte offsets inside a tile; everything else is an immediate
@@ -246,25 +247,30 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         apend[qb] = anext[qb] = 1.f;
     }
 
-    // multipliers of the lane's 8 keys (16kb + 4g + t) of a sub-step, double-buffered by parity
+    // multipliers of the lane's 8 keys (16kb + 4g + t) of a sub-step, double-buffered by parity.
+    // They travel with their tile: copied into LDS behind K and V, read from there one sub-step
+    // ahead of their use.
     f32x4 mreg[MULT ? 2 : 1][2];
-    auto mload = [&](int par, int kb, int substep) {
+    auto mload = [&](int par, int kb, const SPH_LDS unsigned char* buf, int sub) {
         if constexpr (MULT)
-            mreg[par][kb] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
-                mrs, (16 * kb + 4 * g) * 4, substep * 128, 0));
+            mreg[par][kb] = __builtin_bit_cast(f32x4, lds_read_b128(buf + MLDS + (32 * sub + 16 * kb + 4 * g) * 4));
     };
 
     // copy c (K: c < LDK, V: the rest) of this wave's share of tile `tile` into buffer `buf`.
     // Rows past the end of the head are out of the descriptor's range and arrive as zeros.
     const i32x4 krw = rsrc_words((const unsigned char*)Kv + kv_off * EQ, (uint32_t)N * KROWB);
     const i32x4 vrw = rsrc_words(V + kv_off, (uint32_t)N * VROWB);
+    // multiplicities of this cell's keys; those past the last key arrive as 0 (their keys are zero anyway)
+    const i32x4 mrw = rsrc_words(MULT ? mult + (size_t)bidx * Nk + k0 : nullptr, MULT ? (uint32_t)N * 4 : 0);
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     auto copy_chunk = [&](int c, int tile, SPH_LDS unsigned char* buf) {
         const uint32_t base = (uint32_t)(uintptr_t)buf;
         if (c < LDK)
             copy_to_lds(krw, base + (wave_u * KBLK + c) * 1024, kld_lane, tile * KTILE + c * 64);
-        else
+        else if (c < LDK + LDV)
             copy_to_lds(vrw, base + KLDS + (wave_u * DB + 2 * (c - LDK)) * 512, vld_lane, tile * VTILE + (c - LDK) * 64);
+        else if (wave == 0 && lane < BC / 4)       // 16 lanes x 4 multiplicities
+            copy_to_lds(mrw, base + MLDS, lane * 16, tile * BC * 4);
     };
 
     const int n_tiles = (N + BC - 1) / BC;
@@ -274,16 +280,16 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     {
         const i32x4 zero4 = {0, 0, 0, 0};
         for (int i = tid; i < BUF_BYTES / 16; i += kThreads)
-            *reinterpret_cast<SPH_LDS i32x4*>(smem + 3 * BUF_BYTES + i * 16) = zero4;
+            *reinterpret_cast<SPH_LDS i32x4*>(smem + (NBUF - 1) * BUF_BYTES + i * 16) = zero4;
     }
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < NBUF - 2; ++t)
 #pragma unroll
         for (int c = 0; c < NST; ++c) copy_chunk(c, t, smem + t * BUF_BYTES);
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) mload(0, kb, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's copies have landed
     __syncthreads();
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) mload(0, kb, smem, 0);
 
     // scores of a sub-step: [key block][query block]; P of a sub-step: one B operand per query block
     f32x4 S0[2][NQ], S1[2][NQ];
@@ -362,7 +368,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     };
 
     // buffers of tiles j-1, j, j+1, j+2
-    SPH_LDS unsigned char* bprv = smem + 3 * BUF_BYTES;
+    SPH_LDS unsigned char* bprv = smem + (NBUF - 1) * BUF_BYTES;
     SPH_LDS unsigned char* bcur = smem;
     SPH_LDS unsigned char* bnxt = smem + BUF_BYTES;
     SPH_LDS unsigned char* bnn = smem + 2 * BUF_BYTES;
@@ -380,14 +386,13 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             __builtin_amdgcn_sched_barrier(0);
             // The one barrier per tile.  Tile j+1, copied into LDS during the previous
             // iteration, becomes visible before its first read (the prefetch below): every wave
-            // waits for its own copies (all but the youngest vector-memory operations, which are
-            // this sub-step's multiplicity loads) and then for the others.  Past the barrier
+            // waits for its own copies (they are its only vector-memory operations in flight) and
+            // then for the others.  Past the barrier
             // every wave has also finished the previous iteration, whose first half was the
             // last reader of the buffer that this iteration's copies overwrite.
             if (s == SLOTS - PD) {
                 asm volatile("" ::: "memory");
-                constexpr int YOUNGER = MULT ? (SLOTS - PD < 2 ? SLOTS - PD : 2) : 0;
-                __builtin_amdgcn_s_waitcnt(0x0F70 | YOUNGER);         // vmcnt(YOUNGER)
+                __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
             }
@@ -502,7 +507,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                     for (int qb = 0; qb < NQ; ++qb) apend[qb] = anext[qb];
                 }
             }
-            if (MULT && i < 2) mload(hf ^ 1, i, 2 * j + hf + 1);
+            // multipliers of the next sub-step: second half of tile j, or first half of tile j+1
+            if (MULT && i < 2) mload(hf ^ 1, i, hf == 0 ? bcur : bnxt, hf ^ 1);
             // copies of tile j+2 out of HBM/L2 into the free buffer, one per slot, right after
             // the barrier: they have a whole tile's time to land
             constexpr int FIRST_COPY = SLOTS - PD + 1;
