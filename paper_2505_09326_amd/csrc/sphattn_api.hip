@@ -358,6 +358,10 @@ int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype)
     const int rows_per_wg = dtype == SPHATTN_F32 ? 32 : 256;
     const long long wg = (long long)B * H * ((N + rows_per_wg - 1) / rows_per_wg);
     if (wg >= kCus) return 1;
+    // Half-filled launches run on 128-row workgroups instead (twice as many, 15-25 % slower per
+    // row); two slices of 256-row workgroups beat that only when the combine step is small
+    // against a slice (measured: N = 32768 yes, N = 4096 and 8192 no).
+    if (dtype != SPHATTN_F32 && 2 * wg >= kCus && N < 16384) return 1;
     // enough slices to give every CU a workgroup, but no slice shorter than 8 tiles
     const long long want = (kCus + wg - 1) / wg;
     const long long most = ((N + kBC - 1) / kBC + 7) / 8;

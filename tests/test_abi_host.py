@@ -166,6 +166,8 @@ def test_splitkv_heuristic_splits_only_underfilled_launches(lib):
     assert h(1, 1, 65536, 128, 1) == 1                # 256 workgroups
     assert h(1, 1, 8192, 128, 1) == 8                 # 32 workgroups -> 8 slices of 16 tiles
     assert h(1, 2, 4096, 64, 1) == 8                  # 32 workgroups; 64 tiles / 8 per slice
+    assert h(1, 8, 4096, 128, 1) == 1                 # 128 workgroups: 128-row tiles fill the CUs instead
+    assert h(1, 1, 32768, 128, 1) == 2                # 128 workgroups, long: two slices of 256-row tiles
     assert h(1, 1, 300, 128, 1) == 1                  # 5 tiles: too short to cut
     assert h(1, 1, 2048, 64, 0) == 4                  # fp32: 32-row workgroups, 64 of them
     assert h(0, 1, 8192, 128, 1) == 1                 # nonsense in, 1 out
