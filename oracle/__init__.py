@@ -63,6 +63,8 @@ def _load():
         lib.oracle_spherical_streamed.argtypes = [dp, dp, dp, dp, ip, ip, ip, ip, ip]
         lib.oracle_spherical_accumulate.restype = ip
         lib.oracle_spherical_accumulate.argtypes = [vp, ip, vp, ip, vp, ip, dp, dp, dp, ip, ip, ip, ip, ip, ip]
+        lib.oracle_spherical_bwd.restype = ip
+        lib.oracle_spherical_bwd.argtypes = [vp, ip, vp, ip, vp, ip, vp, ip, dp, dp, dp, ip, ip, ip, ip]
         lib.oracle_widen.restype = None
         lib.oracle_widen.argtypes = [vp, ip, ctypes.c_size_t, ctypes.c_size_t, dp]
         lib.oracle_num_threads.restype = ip
@@ -288,3 +290,24 @@ def spherical_tail(o_parts, z_parts) -> np.ndarray:
     nz = z > 0.0
     out[nz] = o[nz] / np.sqrt(z[nz])[:, None]
     return out
+
+
+def spherical_attention_bwd(Q, K, V, dO, kinds=None):
+    """Gradients (dQ, dK, dV), fp64 [B,H,N,d], of sum(O * dO) for spherical attention O(Q, K, V);
+    kinds = (q, k, v, dO) stored formats."""
+    kq, kk, kv, kg = kinds if kinds is not None else (None, None, None, None)
+    Q, kq = _prep(Q, kq)
+    K, kk = _prep(K, kk)
+    V, kv = _prep(V, kv)
+    dO, kg = _prep(dO, kg)
+    if not (Q.shape == K.shape == V.shape == dO.shape):
+        raise ValueError("Q, K, V, dO must share the shape [B,H,N,d]")
+    B, H, N, d = Q.shape
+    dQ, dK, dV = (np.empty((B, H, N, d), dtype=np.float64) for _ in range(3))
+    rc = _load().oracle_spherical_bwd(
+        Q.ctypes.data_as(ctypes.c_void_p), _KINDS[kq], K.ctypes.data_as(ctypes.c_void_p), _KINDS[kk],
+        V.ctypes.data_as(ctypes.c_void_p), _KINDS[kv], dO.ctypes.data_as(ctypes.c_void_p), _KINDS[kg],
+        _dptr(dQ), _dptr(dK), _dptr(dV), B, H, N, d)
+    if rc != 0:
+        raise RuntimeError(f"oracle_spherical_bwd failed with {rc}")
+    return dQ, dK, dV

@@ -41,7 +41,11 @@
  * closed form, and chunk-size / permutation / zero-padding invariance of the
  * streamed accumulator of Lemma 1.  The bare accumulator (no tail) is pinned by
  * exact rationals, by the one-key closed form on a rectangular shape, and by
- * additivity over key partitions followed by the tail against the direct form.
+ * additivity over key partitions followed by the tail against the direct form.  The
+ * backward (derived here, not in the paper) is pinned by central finite differences of
+ * the forward oracle, by automatic differentiation of a library statement of the
+ * definition, by dV = W^T dO with W from the forward oracle, and by Euler's identity for
+ * the scale invariances (q_i . dQ_i = 0 for every row, sum_j k_j . dK_j = 0 per head).
  */
 #include <math.h>
 #include <stdint.h>
@@ -441,6 +445,89 @@ int oracle_spherical_accumulate(const void *Q, int q_kind, const void *K, int k_
     }
     free(Kh);
     free(Vh);
+    return status;
+}
+
+/* Backward of spherical attention.  The paper states no backward pass; this is the chain
+ * rule applied to the definition above.  With r_i = z_i^(-1/2), O_i = r_i sum_j s_ij v_j and a
+ * given upstream gradient dO:
+ *     dV_j  = sum_i r_i s_ij dO_i
+ *     ds_ij = r_i (dO_i . v_j) - (dO_i . O_i) r_i^2 s_ij     (through o, and through r via z)
+ *     dQ_i  = sum_j ds_ij k_j          dK_j = sum_i ds_ij q_i
+ * A row with z_i = 0 has O_i = 0 by definition and contributes no gradient.
+ * Q, K, V, dO: [B,H,N,d] in their stored formats; dQ, dK, dV: [B,H,N,d] fp64.
+ * Two passes per head, as the formulas read: rows i in parallel for dQ (and the row
+ * quantities), then keys j in parallel for dK and dV. */
+int oracle_spherical_bwd(const void *Q, int q_kind, const void *K, int k_kind,
+                         const void *V, int v_kind, const void *dO, int g_kind,
+                         double *dQ, double *dK, double *dV, int B, int H, int N, int d)
+{
+    if (!Q || !K || !V || !dO || !dQ || !dK || !dV || B <= 0 || H <= 0 || N <= 0 || d <= 0)
+        return -1;
+    size_t head = (size_t)N * d;
+    double *Qh = malloc(head * sizeof *Qh), *Kh = malloc(head * sizeof *Kh);
+    double *Vh = malloc(head * sizeof *Vh), *Gh = malloc(head * sizeof *Gh);
+    double *r = malloc((size_t)N * sizeof *r), *delta = malloc((size_t)N * sizeof *delta);
+    int status = (Qh && Kh && Vh && Gh && r && delta) ? 0 : -1;
+    for (int bh = 0; bh < B * H && status == 0; ++bh) {
+        oracle_widen(Q, q_kind, bh * head, head, Qh);
+        oracle_widen(K, k_kind, bh * head, head, Kh);
+        oracle_widen(V, v_kind, bh * head, head, Vh);
+        oracle_widen(dO, g_kind, bh * head, head, Gh);
+        /* rows: r_i, delta_i = dO_i . O_i, dQ_i */
+#pragma omp parallel for schedule(static)
+        for (int i = 0; i < N; ++i) {
+            const double *q = Qh + (size_t)i * d, *g = Gh + (size_t)i * d;
+            double *dq = dQ + bh * head + (size_t)i * d;
+            double z = 0.0, go = 0.0;                /* go = dO_i . o_raw_i */
+            for (int j = 0; j < N; ++j) {
+                double s = 0.0, gv = 0.0;
+                for (int k = 0; k < d; ++k) {
+                    s += q[k] * Kh[(size_t)j * d + k];
+                    gv += g[k] * Vh[(size_t)j * d + k];
+                }
+                z += s * s;
+                go += s * gv;
+            }
+            r[i] = z > 0.0 ? 1.0 / sqrt(z) : 0.0;
+            delta[i] = r[i] * go;                    /* dO_i . O_i */
+            for (int k = 0; k < d; ++k)
+                dq[k] = 0.0;
+            for (int j = 0; j < N; ++j) {
+                double s = 0.0, gv = 0.0;
+                for (int k = 0; k < d; ++k) {
+                    s += q[k] * Kh[(size_t)j * d + k];
+                    gv += g[k] * Vh[(size_t)j * d + k];
+                }
+                double ds = r[i] * gv - delta[i] * r[i] * r[i] * s;
+                for (int k = 0; k < d; ++k)
+                    dq[k] += ds * Kh[(size_t)j * d + k];
+            }
+        }
+        /* keys: dK_j, dV_j */
+#pragma omp parallel for schedule(static)
+        for (int j = 0; j < N; ++j) {
+            const double *kj = Kh + (size_t)j * d, *vj = Vh + (size_t)j * d;
+            double *dk = dK + bh * head + (size_t)j * d, *dv = dV + bh * head + (size_t)j * d;
+            for (int k = 0; k < d; ++k)
+                dk[k] = dv[k] = 0.0;
+            for (int i = 0; i < N; ++i) {
+                const double *q = Qh + (size_t)i * d, *g = Gh + (size_t)i * d;
+                double s = 0.0, gv = 0.0;
+                for (int k = 0; k < d; ++k) {
+                    s += q[k] * kj[k];
+                    gv += g[k] * vj[k];
+                }
+                double w = r[i] * s;
+                double ds = r[i] * gv - delta[i] * r[i] * r[i] * s;
+                for (int k = 0; k < d; ++k) {
+                    dv[k] += w * g[k];
+                    dk[k] += ds * q[k];
+                }
+            }
+        }
+    }
+    free(Qh); free(Kh); free(Vh); free(Gh); free(r); free(delta);
     return status;
 }
 

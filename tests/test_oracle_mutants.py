@@ -36,6 +36,10 @@ MUTANTS = [
     ("accumulator forgets the multiplicity", "x += q[k] * (m ? m[j] * Kh[(size_t)j * d + k] : Kh[(size_t)j * d + k]);\n                        z +=",
      "x += q[k] * Kh[(size_t)j * d + k];\n                        z +="),
     ("accumulator indexes K/V rows with N_q", "const double *m = mult ? mult + (size_t)b * N_k : NULL;", "const double *m = mult ? mult + (size_t)b * N_q : NULL;"),
+    ("backward: the term through z has the wrong power of r", "double ds = r[i] * gv - delta[i] * r[i] * r[i] * s;\n                for (int k = 0; k < d; ++k)\n                    dq[k]",
+     "double ds = r[i] * gv - delta[i] * r[i] * s;\n                for (int k = 0; k < d; ++k)\n                    dq[k]"),
+    ("backward: dK built from k instead of q", "dk[k] += ds * q[k];", "dk[k] += ds * kj[k];"),
+    ("backward: dV forgets the normalisation", "double w = r[i] * s;", "double w = s;"),
     ("softmax without max shift and with wrong scale", "double c = 1.0 / sqrt((double)d);", "double c = 1.0 / (double)d;"),
 ]
 
@@ -77,6 +81,9 @@ def _pin_calls(o):
     yield lambda: pins.test_accumulator_brute_force_rationals_rectangular(o)
     yield lambda: pins.test_accumulator_single_key_closed_form(o)
     yield lambda: pins.test_accumulators_add_over_key_partitions_and_tail_gives_attention(o, (0, 16, 32, 37))
+    yield lambda: pins.test_backward_against_central_differences(o)
+    yield lambda: pins.test_backward_against_library_autograd(o)
+    yield lambda: pins.test_backward_structure(o)
 
 
 @pytest.mark.parametrize("idx", range(len(MUTANTS)))

@@ -434,3 +434,65 @@ def test_tail_of_zero_accumulator_is_zero(oracle):
     np.testing.assert_array_equal(out[0, 0, 0], 0.0)
     np.testing.assert_array_equal(out[0, 0, 2], 0.0)
     np.testing.assert_array_equal(out[0, 0, 1], [1.5, 0.0, -2.0, 0.5])
+
+
+# ---------------------------------------------------------------- backward (derived, not in the paper)
+def _loss(oracle, Q, K, V, dO):
+    return float((oracle.spherical_attention(Q, K, V) * dO).sum())
+
+
+def test_backward_against_central_differences(oracle):
+    """Every gradient entry of a small problem against (L(x+h) - L(x-h)) / 2h of the forward
+    oracle, L = sum(O * dO).  Catches a wrong sign or factor in the term through z, a missing
+    r, swapped q/k in dK, and index slips."""
+    Q, K, V, dO = (_rand((1, 2, 5, 3), s) for s in (110, 111, 112, 113))
+    dQ, dK, dV = oracle.spherical_attention_bwd(Q, K, V, dO)
+    h = 1e-6
+    for name, X, G in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV)):
+        for idx in np.ndindex(X.shape):
+            old = X[idx]
+            X[idx] = old + h
+            up = _loss(oracle, Q, K, V, dO)
+            X[idx] = old - h
+            dn = _loss(oracle, Q, K, V, dO)
+            X[idx] = old
+            assert G[idx] == pytest.approx((up - dn) / (2 * h), rel=2e-6, abs=2e-8), (name, idx)
+
+
+def test_backward_against_library_autograd(oracle):
+    """torch.autograd through a plain fp64 statement of Definition 2 (matmul, square, sum, sqrt)."""
+    import torch
+    Qn, Kn, Vn, Gn = (_rand((2, 3, 19, 8), s) for s in (114, 115, 116, 117))
+    Q, K, V = (torch.tensor(x, requires_grad=True) for x in (Qn, Kn, Vn))
+    S = Q @ K.transpose(-1, -2)
+    O = (S @ V) / S.pow(2).sum(-1, keepdim=True).sqrt()
+    (O * torch.tensor(Gn)).sum().backward()
+    dQ, dK, dV = oracle.spherical_attention_bwd(Qn, Kn, Vn, Gn)
+    np.testing.assert_allclose(dQ, Q.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dK, K.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dV, V.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_backward_structure(oracle):
+    """dV = W^T dO with the forward oracle's weights (O is linear in V); Euler's identity for
+    the scale invariances of the forward: q_i . dQ_i = 0 for every row and
+    sum_j k_j . dK_j = 0 for every head."""
+    Q, K, V, dO = (_rand((1, 2, 23, 6), s) for s in (118, 119, 120, 121))
+    dQ, dK, dV = oracle.spherical_attention_bwd(Q, K, V, dO)
+    _, W, _ = oracle.spherical_attention_full(Q, K, V)
+    np.testing.assert_allclose(dV, np.einsum("bhij,bhik->bhjk", W, dO), rtol=1e-11, atol=1e-13)
+    scale = np.abs(dQ).max() * np.abs(Q).max()
+    assert np.abs((Q * dQ).sum(-1)).max() <= 1e-12 * scale * Q.shape[-1]
+    assert np.abs((K * dK).sum((-1, -2))).max() <= 1e-12 * np.abs(dK).max() * np.abs(K).max() * K.shape[-1] * K.shape[-2]
+
+
+def test_backward_takes_stored_formats(oracle):
+    import torch
+    import synthetic_inputs as si
+    q, k, v = si.make_qkv(1, 2, 17, 8, "bf16", seed=122)
+    g = torch.randn(q.shape, generator=torch.Generator().manual_seed(123)).to(torch.bfloat16)
+    bits = [si.storage_bits(t)[0] for t in (q, k, v, g)]
+    a = oracle.spherical_attention_bwd(*bits, kinds=("bf16",) * 4)
+    b = oracle.spherical_attention_bwd(*(t.double().numpy() for t in (q, k, v, g)))
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x, y)
