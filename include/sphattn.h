@@ -196,6 +196,29 @@ size_t sphattn_splitkv_workspace_bytes(int B, int H, int N, int d, int n_splits)
  * 8 tiles.  Host-only arithmetic. */
 int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype);
 
+/*
+ * Backward of sphattn_fwd.  The paper states no backward pass; this is the chain rule on its
+ * definition.  With r_i = 1/sqrt(z_i) and delta_i = dO[b,h,i,:] . O[b,h,i,:]:
+ *
+ *     dV[b,h,j,:] = sum_i r_i s_ij dO[b,h,i,:]
+ *     ds_ij       = r_i (dO[b,h,i,:] . V[b,h,j,:]) - delta_i r_i^2 s_ij
+ *     dQ[b,h,i,:] = sum_j ds_ij K[b,h,j,:]          dK[b,h,j,:] = sum_i ds_ij Q[b,h,i,:]
+ *
+ * (rows with z_i == 0 contribute nothing).  The scores are recomputed tile by tile; nothing
+ * N x N is stored and no atomics are used, so results do not depend on the launch.
+ *
+ *   Q, K, V, O, dO : [B,H,N,d] in the 16-bit format of `dtype` (SPHATTN_BF16 or SPHATTN_F16;
+ *                    anything else returns SPHATTN_ERR_DTYPE); O and Z as sphattn_fwd_z wrote them.
+ *   Z              : [B,H,N] fp32, the row aggregates z_i.
+ *   dQ, dK, dV     : [B,H,N,d] in the same 16-bit format, written in full.
+ *   delta          : [B,H,N] fp32 scratch from the caller; receives delta_i.
+ * Outputs and scratch must not overlap each other or the inputs.  Two launches on `stream`.
+ * Other arguments and errors as sphattn_fwd.
+ */
+int sphattn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* Z,
+                void* dQ, void* dK, void* dV, float* delta,
+                int B, int H, int N, int d, int dtype, void* stream);
+
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* sphattn_strerror(int code);
 

@@ -1,0 +1,347 @@
+// Backward of spherical attention for gfx950, 16-bit storage (bf16 or fp16).
+//
+// The paper gives no backward pass; this is the chain rule on its definition (Appendix A.1,
+// Definition 2 with a1 = id, a2 = square, b = sqrt).  With r_i = z_i^(-1/2) (z from the
+// forward), O_i = r_i sum_j s_ij v_j, upstream gradient dO and delta_i = dO_i . O_i:
+//
+//     dV_j  = sum_i (r_i s_ij) dO_i
+//     ds_ij = r_i (dO_i . v_j) - delta_i r_i^2 s_ij
+//     dQ_i  = sum_j ds_ij k_j            dK_j = sum_i ds_ij q_i
+//
+// Nothing N x N is stored: the scores are recomputed tile by tile, as in the forward.  Two
+// kernels, no atomics, so the result does not depend on the launch:
+//   bwd_dq_kernel   a workgroup owns 256 query rows and streams the keys: S^T = K Q^T,
+//                   G^T = V dO^T, dS^T in registers, dQ^T += K^T dS^T.  Also writes delta.
+//   bwd_dkv_kernel  a workgroup owns 128 keys and streams the queries: S = Q K^T, G = dO V^T,
+//                   W and dS in registers, dV^T += dO^T W, dK^T += Q^T dS.
+// Both use the forward's building blocks: 16x16x32 matrix instructions with the product
+// arranged so that the accumulator registers of the first contraction are, after the
+// elementwise step, directly a B operand of the second (k-slot e of lane group g = key or
+// query 4g + e, or 16 + 4g + e - 4); the streamed operand's tiles copied from HBM/L2 straight
+// into LDS as 1 KB blocks of 16 rows x 64 bytes, which serve both as row-major A operands
+// (lane reads 16 bytes at 64 n16 + 16 g) and, through ds_read_b64_tr_b16, as transposed A
+// operands; two LDS buffers, one barrier per streamed tile.
+#pragma once
+#include "sphattn_pipelined.hpp"
+
+namespace sphattn {
+
+// fp32 value of one 16-bit storage element held in the low half of `bits`
+template <bool HALF>
+__device__ __forceinline__ float widen16(unsigned bits)
+{
+    if constexpr (HALF) return (float)__builtin_bit_cast(_Float16, (unsigned short)bits);
+    else return __builtin_bit_cast(float, bits << 16);
+}
+
+// sum over the 8 elements of two 16-byte fragments of the products a_e * b_e, in fp32
+template <bool HALF>
+__device__ __forceinline__ float dot8(i32x4 a, i32x4 b, float acc)
+{
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const unsigned x = (unsigned)a[w], y = (unsigned)b[w];
+        acc = __builtin_fmaf(widen16<HALF>(x & 0xffff), widen16<HALF>(y & 0xffff), acc);
+        acc = __builtin_fmaf(widen16<HALF>(x >> 16), widen16<HALF>(y >> 16), acc);
+    }
+    return acc;
+}
+
+// ---------------------------------------------------------------------------
+// dQ.  Workgroup = 4 waves x 64 query rows (four blocks of 16).  Streams K/V tiles of 64 keys.
+// ---------------------------------------------------------------------------
+template <int D, bool HALF>
+__global__ __launch_bounds__(kThreads, 1)
+void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, const void* __restrict__ Vv,
+                   const void* __restrict__ Ov, const void* __restrict__ dOv, const float* __restrict__ Z,
+                   void* __restrict__ dQv, float* __restrict__ delta, int N, int n_qtiles, int n_wg)
+{
+    constexpr int BC = kBC, NQ = 4, BR = kWaves * 16 * NQ;
+    constexpr int ROWB = D * 2, TILE = BC * ROWB;
+    constexpr int KK = D / 32, DB = D / 16, KBLK = ROWB / 64;
+    constexpr int VLDS = TILE;                     // V tile behind the K tile
+    constexpr int BUF_BYTES = 2 * TILE;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n16 = lane & 15, g = lane >> 4;
+    const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
+    const int bh = lid / n_qtiles, qt = lid % n_qtiles;
+    const size_t head_off = (size_t)bh * N * D;
+    const int q0 = qt * BR + wave * 16 * NQ;
+
+    // own rows: Q and dO as B operands (lane: row q0 + 16qb + n16, elements 32kk + 8g .. +7);
+    // r and delta of the lane's query of every block
+    i32x4 qf[NQ][KK], gf[NQ][KK];
+    float c1[NQ], c2[NQ];                          // r_i and delta_i r_i^2
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+        int row = q0 + qb * 16 + n16;
+        const bool live = row < N;
+        row = live ? row : N - 1;
+        const size_t off = (head_off + (size_t)row * D) * 2 + 16 * g;
+        float dsum = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            qf[qb][kk] = *reinterpret_cast<const i32x4*>((const unsigned char*)Qv + off + kk * 64);
+            gf[qb][kk] = *reinterpret_cast<const i32x4*>((const unsigned char*)dOv + off + kk * 64);
+            const i32x4 of = *reinterpret_cast<const i32x4*>((const unsigned char*)Ov + off + kk * 64);
+            dsum = dot8<HALF>(gf[qb][kk], of, dsum);
+        }
+        dsum = sum_across_groups(dsum);            // delta_i = dO_i . O_i
+        const float z = Z[(size_t)bh * N + row];
+        const float r = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
+        c1[qb] = r;
+        c2[qb] = dsum * r * r;
+        if (live && g == 0) delta[(size_t)bh * N + row] = dsum;
+    }
+
+    f32x4 dq[DB][NQ];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) dq[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // tile copies: wave w brings rows 16w .. 16w+15 of the K and of the V tile (KBLK blocks each)
+    const i32x4 krw = rsrc_words((const unsigned char*)Kv + head_off * 2, (uint32_t)N * ROWB);
+    const i32x4 vrw = rsrc_words((const unsigned char*)Vv + head_off * 2, (uint32_t)N * ROWB);
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int ld_lane = (16 * wave + (lane >> 2)) * ROWB + (lane & 3) * 16;
+    auto copy_tile = [&](int tile, uint32_t buf) {
+#pragma unroll
+        for (int c = 0; c < KBLK; ++c) {
+            copy_to_lds(krw, buf + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
+            copy_to_lds(vrw, buf + VLDS + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
+        }
+    };
+    const int alane = n16 * 64 + g * 16;                           // row-major A operand
+    const int tlane = (4 * g + (n16 >> 2)) * 64 + (n16 & 3) * 8;   // transposed A operand
+
+    const int n_tiles = (N + BC - 1) / BC;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    copy_tile(0, lds0);
+    for (int j = 0; j < n_tiles; ++j) {
+        const uint32_t cur = (j & 1) * BUF_BYTES;
+        // tile j has landed (own copies), every wave is done with the other buffer
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        copy_tile(j + 1, lds0 + BUF_BYTES - cur);
+        const SPH_LDS unsigned char* kb_ = smem + cur;
+        const SPH_LDS unsigned char* vb_ = smem + cur + VLDS;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            i32x4 dsp[NQ];                         // dS^T of 32 keys as B operands
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const int rb = 2 * sub + kb;
+                f32x4 s[NQ], gg[NQ];
+#pragma unroll
+                for (int qb = 0; qb < NQ; ++qb) { s[qb] = f32x4{0, 0, 0, 0}; gg[qb] = f32x4{0, 0, 0, 0}; }
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) {
+                    const i32x4 ka = lds_read_b128(kb_ + (rb * KBLK + kk) * 1024 + alane);
+                    const i32x4 va = lds_read_b128(vb_ + (rb * KBLK + kk) * 1024 + alane);
+#pragma unroll
+                    for (int qb = 0; qb < NQ; ++qb) {
+                        s[qb] = mfma16x16<HALF>(ka, qf[qb][kk], s[qb]);
+                        gg[qb] = mfma16x16<HALF>(va, gf[qb][kk], gg[qb]);
+                    }
+                }
+#pragma unroll
+                for (int qb = 0; qb < NQ; ++qb) {
+                    const f32x4 ds = gg[qb] * c1[qb] - s[qb] * c2[qb];
+                    dsp[qb][2 * kb] = pack2<HALF>(ds[0], ds[1]);
+                    dsp[qb][2 * kb + 1] = pack2<HALF>(ds[2], ds[3]);
+                }
+            }
+            // dQ^T[db][qb] += K^T (16 columns of d x 32 keys) dS^T
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const SPH_LDS unsigned char* a = kb_ + (2 * sub * KBLK + db / 2) * 1024 + (db & 1) * 32 + tlane;
+                const i32x2 lo = lds_read_tr64(a);
+                const i32x2 hi = lds_read_tr64(a + KBLK * 1024);
+                const i32x4 kt = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+#pragma unroll
+                for (int qb = 0; qb < NQ; ++qb) dq[db][qb] = mfma16x16<HALF>(kt, dsp[qb], dq[db][qb]);
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // the copy of the tile past the end (zeros)
+
+    unsigned short* dQh = (unsigned short*)dQv + head_off;
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+        const int row = q0 + qb * 16 + n16;
+        if (row < N) {
+            unsigned short* dst = dQh + (size_t)row * D + 4 * g;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const i32x2 o4 = {pack2<HALF>(dq[db][qb][0], dq[db][qb][1]), pack2<HALF>(dq[db][qb][2], dq[db][qb][3])};
+                *reinterpret_cast<i32x2*>(dst + db * 16) = o4;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// dK and dV.  Workgroup = 4 waves x 32 keys (two blocks of 16).  Streams Q/dO tiles of 64
+// queries together with their z and delta.
+// ---------------------------------------------------------------------------
+template <int D, bool HALF>
+__global__ __launch_bounds__(kThreads, 1)
+void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, const void* __restrict__ Vv,
+                    const void* __restrict__ dOv, const float* __restrict__ Z, const float* __restrict__ delta,
+                    void* __restrict__ dKv, void* __restrict__ dVv, int N, int n_ktiles, int n_wg)
+{
+    constexpr int BC = kBC, NK = 2, BKEYS = kWaves * 16 * NK;
+    constexpr int ROWB = D * 2, TILE = BC * ROWB;
+    constexpr int KK = D / 32, DB = D / 16, KBLK = ROWB / 64;
+    constexpr int GLDS = TILE, ZLDS = 2 * TILE, DLDS = 2 * TILE + BC * 4;   // Q tile, dO tile, z, delta
+    constexpr int BUF_BYTES = 2 * TILE + 2 * BC * 4;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n16 = lane & 15, g = lane >> 4;
+    const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
+    const int bh = lid / n_ktiles, kt = lid % n_ktiles;
+    const size_t head_off = (size_t)bh * N * D;
+    const int k0 = kt * BKEYS + wave * 16 * NK;
+
+    // own keys: K and V as B operands (lane: key k0 + 16kb + n16, elements 32kk + 8g .. +7)
+    i32x4 kf[NK][KK], vf[NK][KK];
+#pragma unroll
+    for (int kb = 0; kb < NK; ++kb) {
+        int row = k0 + kb * 16 + n16;
+        row = row < N ? row : N - 1;               // keys past the end are computed and dropped
+        const size_t off = (head_off + (size_t)row * D) * 2 + 16 * g;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            kf[kb][kk] = *reinterpret_cast<const i32x4*>((const unsigned char*)Kv + off + kk * 64);
+            vf[kb][kk] = *reinterpret_cast<const i32x4*>((const unsigned char*)Vv + off + kk * 64);
+        }
+    }
+    f32x4 dk[DB][NK], dv[DB][NK];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int kb = 0; kb < NK; ++kb) { dk[db][kb] = f32x4{0, 0, 0, 0}; dv[db][kb] = f32x4{0, 0, 0, 0}; }
+
+    const i32x4 qrw = rsrc_words((const unsigned char*)Qv + head_off * 2, (uint32_t)N * ROWB);
+    const i32x4 grw = rsrc_words((const unsigned char*)dOv + head_off * 2, (uint32_t)N * ROWB);
+    const i32x4 zrw = rsrc_words(Z + (size_t)bh * N, (uint32_t)N * 4);
+    const i32x4 drw = rsrc_words(delta + (size_t)bh * N, (uint32_t)N * 4);
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int ld_lane = (16 * wave + (lane >> 2)) * ROWB + (lane & 3) * 16;
+    auto copy_tile = [&](int tile, uint32_t buf) {
+#pragma unroll
+        for (int c = 0; c < KBLK; ++c) {
+            copy_to_lds(qrw, buf + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
+            copy_to_lds(grw, buf + GLDS + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
+        }
+        // 64 z and 64 delta values: 16 lanes x 16 bytes each; queries past N arrive as 0
+        if (wave == 0 && lane < BC / 4) copy_to_lds(zrw, buf + ZLDS, lane * 16, tile * BC * 4);
+        if (wave == 1 && lane < BC / 4) copy_to_lds(drw, buf + DLDS, lane * 16, tile * BC * 4);
+    };
+    const int alane = n16 * 64 + g * 16;
+    const int tlane = (4 * g + (n16 >> 2)) * 64 + (n16 & 3) * 8;
+
+    const int n_tiles = (N + BC - 1) / BC;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    copy_tile(0, lds0);
+    for (int j = 0; j < n_tiles; ++j) {
+        const uint32_t cur = (j & 1) * BUF_BYTES;
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        copy_tile(j + 1, lds0 + BUF_BYTES - cur);
+        const SPH_LDS unsigned char* qb_ = smem + cur;
+        const SPH_LDS unsigned char* gb_ = smem + cur + GLDS;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            // S[qb][kb] = Q K^T, G[qb][kb] = dO V^T: lane owns key column n16 of block kb and
+            // queries 16qb + 4g + t of the sub-step
+            f32x4 s[2][NK], gg[2][NK];
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int kb = 0; kb < NK; ++kb) { s[qb][kb] = f32x4{0, 0, 0, 0}; gg[qb][kb] = f32x4{0, 0, 0, 0}; }
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const int rb = 2 * sub + qb;
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) {
+                    const i32x4 qa = lds_read_b128(qb_ + (rb * KBLK + kk) * 1024 + alane);
+                    const i32x4 ga = lds_read_b128(gb_ + (rb * KBLK + kk) * 1024 + alane);
+#pragma unroll
+                    for (int kb = 0; kb < NK; ++kb) {
+                        s[qb][kb] = mfma16x16<HALF>(qa, kf[kb][kk], s[qb][kb]);
+                        gg[qb][kb] = mfma16x16<HALF>(ga, vf[kb][kk], gg[qb][kb]);
+                    }
+                }
+            }
+            // per query: r and delta r^2
+            i32x4 wp[NK], dsp[NK];
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const int qoff = (32 * sub + 16 * qb + 4 * g) * 4;
+                const f32x4 zq = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + ZLDS + qoff));
+                const f32x4 dq_ = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + DLDS + qoff));
+                f32x4 r, c;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    r[t] = zq[t] > 0.f ? 1.0f / __builtin_sqrtf(zq[t]) : 0.f;
+                    c[t] = dq_[t] * r[t] * r[t];
+                }
+#pragma unroll
+                for (int kb = 0; kb < NK; ++kb) {
+                    const f32x4 w = s[qb][kb] * r;
+                    const f32x4 ds = gg[qb][kb] * r - s[qb][kb] * c;
+                    wp[kb][2 * qb] = pack2<HALF>(w[0], w[1]);
+                    wp[kb][2 * qb + 1] = pack2<HALF>(w[2], w[3]);
+                    dsp[kb][2 * qb] = pack2<HALF>(ds[0], ds[1]);
+                    dsp[kb][2 * qb + 1] = pack2<HALF>(ds[2], ds[3]);
+                }
+            }
+            // dV^T[db][kb] += dO^T W,  dK^T[db][kb] += Q^T dS  (A: 16 columns of d x 32 queries)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const int boff = (2 * sub * KBLK + db / 2) * 1024 + (db & 1) * 32 + tlane;
+                const i32x2 glo = lds_read_tr64(gb_ + boff), ghi = lds_read_tr64(gb_ + boff + KBLK * 1024);
+                const i32x2 qlo = lds_read_tr64(qb_ + boff), qhi = lds_read_tr64(qb_ + boff + KBLK * 1024);
+                const i32x4 gt = __builtin_shufflevector(glo, ghi, 0, 1, 2, 3);
+                const i32x4 qt_ = __builtin_shufflevector(qlo, qhi, 0, 1, 2, 3);
+#pragma unroll
+                for (int kb = 0; kb < NK; ++kb) {
+                    dv[db][kb] = mfma16x16<HALF>(gt, wp[kb], dv[db][kb]);
+                    dk[db][kb] = mfma16x16<HALF>(qt_, dsp[kb], dk[db][kb]);
+                }
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+
+    unsigned short* dKh = (unsigned short*)dKv + head_off;
+    unsigned short* dVh = (unsigned short*)dVv + head_off;
+#pragma unroll
+    for (int kb = 0; kb < NK; ++kb) {
+        const int row = k0 + kb * 16 + n16;
+        if (row < N) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const i32x2 k4 = {pack2<HALF>(dk[db][kb][0], dk[db][kb][1]), pack2<HALF>(dk[db][kb][2], dk[db][kb][3])};
+                const i32x2 v4 = {pack2<HALF>(dv[db][kb][0], dv[db][kb][1]), pack2<HALF>(dv[db][kb][2], dv[db][kb][3])};
+                *reinterpret_cast<i32x2*>(dKh + (size_t)row * D + 4 * g + db * 16) = k4;
+                *reinterpret_cast<i32x2*>(dVh + (size_t)row * D + 4 * g + db * 16) = v4;
+            }
+        }
+    }
+}
+
+}  // namespace sphattn

@@ -530,6 +530,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         SPH_LDS unsigned char* t = bprv; bprv = bcur; bcur = bnxt; bnxt = bnn; bnn = t;
     }
     __builtin_amdgcn_sched_barrier(0);
+    // the copies of the two tiles past the end (all zeros) must not outlive the workgroup's LDS
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
 
     // ---- drain: stage C of the last sub-step (V of the last tile, sub 1, now at bprv)
     {

@@ -173,6 +173,29 @@ def test_splitkv_heuristic_splits_only_underfilled_launches(lib):
     assert h(0, 1, 8192, 128, 1) == 1                 # nonsense in, 1 out
 
 
+def test_backward_argument_errors(lib):
+    P = ctypes.c_void_p
+    base = dict(Q=0x1000000, K=0x2000000, V=0x3000000, O=0x4000000, dO=0x5000000, Z=0x6000000,
+                dQ=0x7000000, dK=0x8000000, dV=0x9000000, delta=0xA000000)
+
+    def call(B=1, H=2, N=300, d=64, dtype=1, **over):
+        a = dict(base, **over)
+        return lib.sphattn_bwd(P(a["Q"]), P(a["K"]), P(a["V"]), P(a["O"]), P(a["dO"]), P(a["Z"]),
+                               P(a["dQ"]), P(a["dK"]), P(a["dV"]), P(a["delta"]), B, H, N, d, dtype, None)
+    for name in base:
+        assert call(**{name: 0}) == -1
+    assert call(N=0) == -2
+    assert call(d=96) == -3
+    assert call(dtype=0) == -4                 # fp32 and fp8 storage have no backward
+    assert call(dtype=2) == -4
+    assert call(dtype=9) == -4
+    assert call(dK=0x8000008) == -5
+    assert call(delta=0xA000002) == -5
+    assert call(dQ=0x1000000) == -7            # dQ is Q
+    assert call(dV=0x8000000) == -7            # dV is dK
+    assert call(delta=0x6000000) == -7         # delta is Z
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys

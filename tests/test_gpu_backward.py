@@ -1,0 +1,128 @@
+"""GPU parity of the backward pass (sphattn_bwd, through the C ABI) against the fp64 CPU oracle.
+
+The backward takes what the forward leaves behind on the GPU (O in the storage type, z in
+fp32).  Tolerance: the gradients are sums of products of one operand rounded to the 16-bit
+type (W or dS, 2^-9 relative per term for bfloat16) and are stored in the 16-bit type
+(half an ulp, 2^-9 relative for bfloat16, of entries that reach about 5 rms: 1e-2 of the rms
+by itself); measured 1.3e-2 .. 2.0e-2 for bfloat16 and 1.5e-3 .. 2.3e-3 for half.  The bound is
+2.5e-2 of the rms of the reference for bfloat16 and 5e-3 for half, per gradient tensor.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2.5e-2, "f16": 5e-3}
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2505_09326_amd as p
+    p.load_library()
+    return p
+
+
+def _rel_err(got, ref):
+    return np.abs(got - ref).max() / np.sqrt((ref ** 2).mean())
+
+
+def _inputs(B, H, N, d, dtype, seed):
+    q, k, v = si.make_qkv(B, H, N, d, dtype, seed=seed)
+    g = torch.Generator(device="cpu").manual_seed(seed + 7)
+    dO = torch.randn((B, H, N, d), generator=g, dtype=torch.float32).to(q.dtype)
+    return q, k, v, dO
+
+
+def _run(pkg, q, k, v, dO, dtype):
+    qd, kd, vd, gd = (t.to(DEV) for t in (q, k, v, dO))
+    O, Z = pkg.sphattn_fwd_z(qd, kd, vd, dtype=dtype)
+    dQ, dK, dV = pkg.sphattn_bwd(qd, kd, vd, O, gd, Z, dtype=dtype)
+    torch.cuda.synchronize()
+    return tuple(t.cpu().double().numpy() for t in (dQ, dK, dV))
+
+
+CASES = [
+    (1, 2, 300, 64, "bf16"), (2, 1, 257, 128, "bf16"), (1, 1, 2, 64, "bf16"), (1, 2, 64, 128, "bf16"),
+    (1, 1, 1000, 128, "bf16"), (2, 2, 129, 64, "bf16"), (1, 3, 33, 128, "bf16"), (1, 1, 2048, 64, "bf16"),
+    (1, 2, 300, 128, "f16"), (1, 1, 515, 64, "f16"),
+]
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", CASES)
+def test_backward_full_compare(pkg, oracle, B, H, N, d, dtype):
+    """dQ, dK, dV element by element over several tiles of both kernels and ragged tails."""
+    print(f"case bwd B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    q, k, v, dO = _inputs(B, H, N, d, dtype, 2000 + N + d)
+    got = _run(pkg, q, k, v, dO, dtype)
+    bits = [si.storage_bits(t)[0] for t in (q, k, v, dO)]
+    kind = si.storage_bits(q)[1]
+    ref = oracle.spherical_attention_bwd(*bits, kinds=(kind,) * 4)
+    for name, a, b in zip(("dQ", "dK", "dV"), got, ref):
+        assert np.all(np.isfinite(a)), name
+        err = _rel_err(a, b)
+        print(f"  {name}: max|err|/rms = {err:.3e}", flush=True)
+        assert err <= TOL[dtype], name
+
+
+def test_backward_single_key(pkg):
+    """N = 1: O = sign(s) v does not depend on the size of q or k, so dQ = dK = 0 (two equal
+    terms cancel: the result must be small against either of them) and dV = sign(s) dO."""
+    B, H, N, d = 1, 3, 1, 128
+    q, k, v, dO = _inputs(B, H, N, d, "bf16", 2050)
+    dQ, dK, dV = _run(pkg, q, k, v, dO, "bf16")
+    qf, kf, vf, gf = (t.double().numpy() for t in (q, k, v, dO))
+    s = (qf * kf).sum(-1, keepdims=True)
+    term = np.abs((gf * vf).sum(-1, keepdims=True) / s)            # |r (dO.v)|
+    assert np.all(np.abs(dQ) <= 2.0 ** -6 * term * np.abs(kf).max())
+    assert np.all(np.abs(dK) <= 2.0 ** -6 * term * np.abs(qf).max())
+    np.testing.assert_allclose(dV, np.sign(s) * gf, rtol=2.0 ** -7, atol=0)
+
+
+def test_backward_one_long_head(pkg, oracle):
+    """One head of 4096 keys and queries at d = 128: 16 query tiles x 64 key tiles in the dQ
+    kernel, 32 key tiles x 64 query tiles in the dK/dV kernel."""
+    B, H, N, d = 1, 1, 4096, 128
+    q, k, v, dO = _inputs(B, H, N, d, "bf16", 2100)
+    got = _run(pkg, q, k, v, dO, "bf16")
+    bits = [si.storage_bits(t)[0] for t in (q, k, v, dO)]
+    ref = oracle.spherical_attention_bwd(*bits, kinds=("bf16",) * 4)
+    for name, a, b in zip(("dQ", "dK", "dV"), got, ref):
+        err = _rel_err(a, b)
+        print(f"  {name}: max|err|/rms = {err:.3e}", flush=True)
+        assert err <= TOL["bf16"], name
+
+
+def test_backward_zero_query_row_and_determinism(pkg):
+    """A query row of zeros has z = 0: its dQ row is 0 and it adds nothing to dK, dV; two runs
+    give the same bits (no atomics)."""
+    B, H, N, d = 1, 2, 700, 128
+    q, k, v, dO = _inputs(B, H, N, d, "bf16", 2200)
+    q[0, 1, 5] = 0
+    a = _run(pkg, q, k, v, dO, "bf16")
+    b = _run(pkg, q, k, v, dO, "bf16")
+    assert all(np.all(np.isfinite(x)) for x in a)
+    assert np.all(a[0][0, 1, 5] == 0.0)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_backward_does_not_write_outside_its_outputs(pkg):
+    B, H, N, d = 1, 2, 333, 64
+    q, k, v, dO = _inputs(B, H, N, d, "bf16", 2300)
+    qd, kd, vd, gd = (t.to(DEV) for t in (q, k, v, dO))
+    O, Z = pkg.sphattn_fwd_z(qd, kd, vd, dtype="bf16")
+    n = B * H * N * d
+    pad = 4096
+    bufs = [torch.full((n + 2 * pad,), 7.0, dtype=torch.bfloat16, device=DEV) for _ in range(3)]
+    outs = [b[pad:pad + n].view(B, H, N, d) for b in bufs]
+    dbuf = torch.full((B * H * N + 2 * pad,), 7.0, dtype=torch.float32, device=DEV)
+    pkg.sphattn_bwd(qd, kd, vd, O, gd, Z, dQ=outs[0], dK=outs[1], dV=outs[2],
+                    delta=dbuf[pad:pad + B * H * N].view(B, H, N), dtype="bf16")
+    torch.cuda.synchronize()
+    for b in bufs:
+        assert bool((b[:pad] == 7.0).all()) and bool((b[pad + n:] == 7.0).all())
+    assert bool((dbuf[:pad] == 7.0).all()) and bool((dbuf[pad + B * H * N:] == 7.0).all())
