@@ -86,6 +86,7 @@ def main() -> int:
     ap.add_argument("--splitkv", type=int, default=0, metavar="HEADS",
                     help="also time the split-key forward against the unsplit call on the first HEADS "
                          "heads of batch 0 of the workload (few heads leave CUs idle; the split fills them)")
+    ap.add_argument("--bwd", action="store_true", help="also time the backward pass (sphattn_bwd) on the workload")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run a plain 256 MiB device copy (untimed), as the known-size "
                          "reference that HBM byte counters are scaled by when profiling")
@@ -192,6 +193,26 @@ def main() -> int:
             "workspace_bytes": ws.numel(), "unsplit_ms_avg": ms_u, "split_ms_avg": ms_s,
             "unsplit_tflops": fl / (ms_u * 1e-3) / 1e12, "split_tflops": fl / (ms_s * 1e-3) / 1e12,
             "split_speedup": ms_u / ms_s,
+        }
+
+    if args.bwd:
+        if w.dtype not in ("bf16", "f16"):
+            print("--bwd needs a 16-bit workload", file=sys.stderr)
+            return 2
+        g = torch.Generator(device="cpu").manual_seed(w.seed + 2000)
+        dO = torch.randn(q.shape, generator=g, dtype=torch.float32).to(q.dtype).to(dev)
+        Zf = torch.empty(qd.shape[:3], dtype=torch.float32, device=dev)
+        pkg.sphattn_fwd_z(qd, kd, vd, out, Zf, dtype=w.dtype)
+        dQ, dK, dV = (torch.empty_like(qd) for _ in range(3))
+        delta = torch.empty_like(Zf)
+        _, per_b = time_launches(lambda: pkg.sphattn_bwd(qd, kd, vd, out, dO, Zf, dQ, dK, dV, delta, dtype=w.dtype),
+                                 max(10, args.steps // 4), max(5, args.warmup // 4))
+        ms_b = sum(per_b) / len(per_b)
+        result["backward"] = {
+            "ms_avg": ms_b, "kernels": 2,
+            "tflops_10N2d": 2.5 * w.flops / (ms_b * 1e-3) / 1e12,       # five N x N x d contractions
+            "tflops_executed_14N2d": 3.5 * w.flops / (ms_b * 1e-3) / 1e12,   # scores recomputed in both kernels
+            "vs_forward": ms_b / ms_kernel,
         }
 
     if args.copy_reference:
