@@ -65,6 +65,8 @@ def _load():
         lib.oracle_spherical_accumulate.argtypes = [vp, ip, vp, ip, vp, ip, dp, dp, dp, ip, ip, ip, ip, ip, ip]
         lib.oracle_spherical_bwd.restype = ip
         lib.oracle_spherical_bwd.argtypes = [vp, ip, vp, ip, vp, ip, vp, ip, dp, dp, dp, ip, ip, ip, ip]
+        lib.oracle_spherical_bwd_grn.restype = ip
+        lib.oracle_spherical_bwd_grn.argtypes = [vp, ip, vp, ip, vp, ip, vp, ip, dp, dp, dp, dp, ip, ip, ip, ip, ip]
         lib.oracle_widen.restype = None
         lib.oracle_widen.argtypes = [vp, ip, ctypes.c_size_t, ctypes.c_size_t, dp]
         lib.oracle_num_threads.restype = ip
@@ -310,4 +312,28 @@ def spherical_attention_bwd(Q, K, V, dO, kinds=None):
         _dptr(dQ), _dptr(dK), _dptr(dV), B, H, N, d)
     if rc != 0:
         raise RuntimeError(f"oracle_spherical_bwd failed with {rc}")
+    return dQ, dK, dV
+
+
+def grn_attention_bwd(Q, K, V, dO, mult=None, kinds=None):
+    """Gradients (dQ [B,H,N,d], dK, dV [B,H_kv,N,d]) of sum(O * dO) for the gene-regulatory-network
+    variant O = grn_attention(Q, K, V, mult); kinds = (q, k, v, dO) stored formats."""
+    kq, kk, kv, kg = kinds if kinds is not None else (None, None, None, None)
+    Q, kq = _prep(Q, kq)
+    K, kk = _prep(K, kk)
+    V, kv = _prep(V, kv)
+    dO, kg = _prep(dO, kg)
+    B, H, N, d = Q.shape
+    if K.shape != V.shape or K.shape[0] != B or K.shape[2:] != (N, d) or dO.shape != Q.shape:
+        raise ValueError("K, V must be [B,H_kv,N,d] and dO like Q")
+    H_kv = K.shape[1]
+    m = _prep_mult(mult, B, N)
+    dQ = np.empty((B, H, N, d), dtype=np.float64)
+    dK, dV = (np.empty((B, H_kv, N, d), dtype=np.float64) for _ in range(2))
+    rc = _load().oracle_spherical_bwd_grn(
+        Q.ctypes.data_as(ctypes.c_void_p), _KINDS[kq], K.ctypes.data_as(ctypes.c_void_p), _KINDS[kk],
+        V.ctypes.data_as(ctypes.c_void_p), _KINDS[kv], dO.ctypes.data_as(ctypes.c_void_p), _KINDS[kg],
+        _dptr(m) if m is not None else None, _dptr(dQ), _dptr(dK), _dptr(dV), B, H, H_kv, N, d)
+    if rc != 0:
+        raise RuntimeError(f"oracle_spherical_bwd_grn failed with {rc}")
     return dQ, dK, dV

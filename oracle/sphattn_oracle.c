@@ -453,26 +453,37 @@ int oracle_spherical_accumulate(const void *Q, int q_kind, const void *K, int k_
  * given upstream gradient dO:
  *     dV_j  = sum_i r_i s_ij dO_i
  *     ds_ij = r_i (dO_i . v_j) - (dO_i . O_i) r_i^2 s_ij     (through o, and through r via z)
- *     dQ_i  = sum_j ds_ij k_j          dK_j = sum_i ds_ij q_i
- * A row with z_i = 0 has O_i = 0 by definition and contributes no gradient.
- * Q, K, V, dO: [B,H,N,d] in their stored formats; dQ, dK, dV: [B,H,N,d] fp64.
- * Two passes per head, as the formulas read: rows i in parallel for dQ (and the row
- * quantities), then keys j in parallel for dK and dV. */
-int oracle_spherical_bwd(const void *Q, int q_kind, const void *K, int k_kind,
-                         const void *V, int v_kind, const void *dO, int g_kind,
-                         double *dQ, double *dK, double *dV, int B, int H, int N, int d)
+ *     dQ_i  = sum_j ds_ij m_j k_j      dK_j = m_j sum_i ds_ij q_i
+ * for the gene-regulatory-network variant s_ij = m_j (q_i . k_j) (m = 1 without multiplicities;
+ * the multiplicities are data and get no gradient); with shared K/V heads the sums over i run
+ * over the query rows of every head of the group.  A row with z_i = 0 has O_i = 0 by
+ * definition and contributes no gradient.
+ * Q, dO: [B,H,N,d], K, V: [B,H_kv,N,d] in their stored formats; mult: [B,N] or NULL;
+ * dQ: [B,H,N,d], dK, dV: [B,H_kv,N,d] fp64.
+ * Per query head, as the formulas read: rows i in parallel for dQ (and the row quantities),
+ * then keys j in parallel, adding into dK and dV of the head's K/V head. */
+int oracle_spherical_bwd_grn(const void *Q, int q_kind, const void *K, int k_kind,
+                             const void *V, int v_kind, const void *dO, int g_kind,
+                             const double *mult, double *dQ, double *dK, double *dV,
+                             int B, int H, int H_kv, int N, int d)
 {
-    if (!Q || !K || !V || !dO || !dQ || !dK || !dV || B <= 0 || H <= 0 || N <= 0 || d <= 0)
+    if (!Q || !K || !V || !dO || !dQ || !dK || !dV || B <= 0 || H <= 0 || H_kv <= 0 || H % H_kv ||
+        N <= 0 || d <= 0)
         return -1;
     size_t head = (size_t)N * d;
     double *Qh = malloc(head * sizeof *Qh), *Kh = malloc(head * sizeof *Kh);
     double *Vh = malloc(head * sizeof *Vh), *Gh = malloc(head * sizeof *Gh);
     double *r = malloc((size_t)N * sizeof *r), *delta = malloc((size_t)N * sizeof *delta);
     int status = (Qh && Kh && Vh && Gh && r && delta) ? 0 : -1;
+    if (status == 0)
+        memset(dK, 0, (size_t)B * H_kv * head * sizeof *dK), memset(dV, 0, (size_t)B * H_kv * head * sizeof *dV);
     for (int bh = 0; bh < B * H && status == 0; ++bh) {
+        const int b = bh / H, h = bh % H;
+        const size_t kvh = (size_t)b * H_kv + h / (H / H_kv);
+        const double *m = mult ? mult + (size_t)b * N : NULL;
         oracle_widen(Q, q_kind, bh * head, head, Qh);
-        oracle_widen(K, k_kind, bh * head, head, Kh);
-        oracle_widen(V, v_kind, bh * head, head, Vh);
+        oracle_widen(K, k_kind, kvh * head, head, Kh);
+        oracle_widen(V, v_kind, kvh * head, head, Vh);
         oracle_widen(dO, g_kind, bh * head, head, Gh);
         /* rows: r_i, delta_i = dO_i . O_i, dQ_i */
 #pragma omp parallel for schedule(static)
@@ -486,6 +497,8 @@ int oracle_spherical_bwd(const void *Q, int q_kind, const void *K, int k_kind,
                     s += q[k] * Kh[(size_t)j * d + k];
                     gv += g[k] * Vh[(size_t)j * d + k];
                 }
+                if (m)
+                    s *= m[j];
                 z += s * s;
                 go += s * gv;
             }
@@ -499,18 +512,20 @@ int oracle_spherical_bwd(const void *Q, int q_kind, const void *K, int k_kind,
                     s += q[k] * Kh[(size_t)j * d + k];
                     gv += g[k] * Vh[(size_t)j * d + k];
                 }
+                if (m)
+                    s *= m[j];
                 double ds = r[i] * gv - delta[i] * r[i] * r[i] * s;
+                if (m)
+                    ds *= m[j];                      /* d s_ij / d (q_i . k_j) */
                 for (int k = 0; k < d; ++k)
                     dq[k] += ds * Kh[(size_t)j * d + k];
             }
         }
-        /* keys: dK_j, dV_j */
+        /* keys: this head's share of dK_j, dV_j */
 #pragma omp parallel for schedule(static)
         for (int j = 0; j < N; ++j) {
             const double *kj = Kh + (size_t)j * d, *vj = Vh + (size_t)j * d;
-            double *dk = dK + bh * head + (size_t)j * d, *dv = dV + bh * head + (size_t)j * d;
-            for (int k = 0; k < d; ++k)
-                dk[k] = dv[k] = 0.0;
+            double *dk = dK + kvh * head + (size_t)j * d, *dv = dV + kvh * head + (size_t)j * d;
             for (int i = 0; i < N; ++i) {
                 const double *q = Qh + (size_t)i * d, *g = Gh + (size_t)i * d;
                 double s = 0.0, gv = 0.0;
@@ -518,8 +533,12 @@ int oracle_spherical_bwd(const void *Q, int q_kind, const void *K, int k_kind,
                     s += q[k] * kj[k];
                     gv += g[k] * vj[k];
                 }
+                if (m)
+                    s *= m[j];
                 double w = r[i] * s;
                 double ds = r[i] * gv - delta[i] * r[i] * r[i] * s;
+                if (m)
+                    ds *= m[j];
                 for (int k = 0; k < d; ++k) {
                     dv[k] += w * g[k];
                     dk[k] += ds * q[k];
@@ -529,6 +548,14 @@ int oracle_spherical_bwd(const void *Q, int q_kind, const void *K, int k_kind,
     }
     free(Qh); free(Kh); free(Vh); free(Gh); free(r); free(delta);
     return status;
+}
+
+/* The plain case: no multiplicities, one K/V head per query head. */
+int oracle_spherical_bwd(const void *Q, int q_kind, const void *K, int k_kind,
+                         const void *V, int v_kind, const void *dO, int g_kind,
+                         double *dQ, double *dK, double *dV, int B, int H, int N, int d)
+{
+    return oracle_spherical_bwd_grn(Q, q_kind, K, k_kind, V, v_kind, dO, g_kind, NULL, dQ, dK, dV, B, H, H, N, d);
 }
 
 int oracle_num_threads(void)

@@ -36,8 +36,12 @@ MUTANTS = [
     ("accumulator forgets the multiplicity", "x += q[k] * (m ? m[j] * Kh[(size_t)j * d + k] : Kh[(size_t)j * d + k]);\n                        z +=",
      "x += q[k] * Kh[(size_t)j * d + k];\n                        z +="),
     ("accumulator indexes K/V rows with N_q", "const double *m = mult ? mult + (size_t)b * N_k : NULL;", "const double *m = mult ? mult + (size_t)b * N_q : NULL;"),
-    ("backward: the term through z has the wrong power of r", "double ds = r[i] * gv - delta[i] * r[i] * r[i] * s;\n                for (int k = 0; k < d; ++k)\n                    dq[k]",
-     "double ds = r[i] * gv - delta[i] * r[i] * s;\n                for (int k = 0; k < d; ++k)\n                    dq[k]"),
+    ("backward: the term through z has the wrong power of r", "double ds = r[i] * gv - delta[i] * r[i] * r[i] * s;\n                if (m)\n                    ds *= m[j];                      /* d s_ij",
+     "double ds = r[i] * gv - delta[i] * r[i] * s;\n                if (m)\n                    ds *= m[j];                      /* d s_ij"),
+    ("backward: multiplicity missing on the way from ds to dK", "                if (m)\n                    ds *= m[j];\n                for (int k = 0; k < d; ++k) {\n                    dv[k]",
+     "                for (int k = 0; k < d; ++k) {\n                    dv[k]"),
+    ("backward: K/V gradients of a group overwrite each other", "double *dk = dK + kvh * head + (size_t)j * d, *dv = dV + kvh * head + (size_t)j * d;\n            for (int i = 0; i < N; ++i) {",
+     "double *dk = dK + kvh * head + (size_t)j * d, *dv = dV + kvh * head + (size_t)j * d;\n            for (int k = 0; k < d; ++k) dk[k] = dv[k] = 0.0;\n            for (int i = 0; i < N; ++i) {"),
     ("backward: dK built from k instead of q", "dk[k] += ds * q[k];", "dk[k] += ds * kj[k];"),
     ("backward: dV forgets the normalisation", "double w = r[i] * s;", "double w = s;"),
     ("softmax without max shift and with wrong scale", "double c = 1.0 / sqrt((double)d);", "double c = 1.0 / (double)d;"),
@@ -84,6 +88,7 @@ def _pin_calls(o):
     yield lambda: pins.test_backward_against_central_differences(o)
     yield lambda: pins.test_backward_against_library_autograd(o)
     yield lambda: pins.test_backward_structure(o)
+    yield lambda: pins.test_grn_backward_against_central_differences_and_autograd(o)
 
 
 @pytest.mark.parametrize("idx", range(len(MUTANTS)))

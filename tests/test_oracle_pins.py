@@ -496,3 +496,37 @@ def test_backward_takes_stored_formats(oracle):
     b = oracle.spherical_attention_bwd(*(t.double().numpy() for t in (q, k, v, g)))
     for x, y in zip(a, b):
         np.testing.assert_array_equal(x, y)
+
+
+def test_grn_backward_against_central_differences_and_autograd(oracle):
+    """Multiplicities and shared K/V heads in the backward: central differences of the forward
+    oracle on a tiny problem, library autograd on a larger one.  Catches a multiplicity applied
+    once instead of twice on the way to dQ/dK, and K/V gradients not summed over a group."""
+    import torch
+    Q, dO = _rand((1, 4, 5, 3), 130), _rand((1, 4, 5, 3), 131)
+    K, V = _rand((1, 2, 5, 3), 132), _rand((1, 2, 5, 3), 133)
+    m = np.array([[2.0, 0.0, 1.0, 3.0, 0.5]])
+    dQ, dK, dV = oracle.grn_attention_bwd(Q, K, V, dO, m)
+    loss = lambda: float((oracle.grn_attention(Q, K, V, m) * dO).sum())
+    h = 1e-6
+    for name, X, G in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV)):
+        for idx in np.ndindex(X.shape):
+            old = X[idx]
+            X[idx] = old + h
+            up = loss()
+            X[idx] = old - h
+            dn = loss()
+            X[idx] = old
+            assert G[idx] == pytest.approx((up - dn) / (2 * h), rel=2e-6, abs=2e-8), (name, idx)
+    Qn, Gn = _rand((2, 6, 17, 8), 134), _rand((2, 6, 17, 8), 135)
+    Kn, Vn = _rand((2, 3, 17, 8), 136), _rand((2, 3, 17, 8), 137)
+    mn = np.random.default_rng(138).uniform(0.5, 3.0, size=(2, 17))
+    Qt, Kt, Vt = (torch.tensor(x, requires_grad=True) for x in (Qn, Kn, Vn))
+    Ke, Ve = Kt.repeat_interleave(2, dim=1), Vt.repeat_interleave(2, dim=1)
+    S = (Qt @ Ke.transpose(-1, -2)) * torch.tensor(mn)[:, None, None, :]
+    O = (S @ Ve) / S.pow(2).sum(-1, keepdim=True).sqrt()
+    (O * torch.tensor(Gn)).sum().backward()
+    dQ, dK, dV = oracle.grn_attention_bwd(Qn, Kn, Vn, Gn, mn)
+    np.testing.assert_allclose(dQ, Qt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dK, Kt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dV, Vt.grad.numpy(), rtol=1e-10, atol=1e-12)
