@@ -219,6 +219,24 @@ int sphattn_bwd(const void* Q, const void* K, const void* V, const void* O, cons
                 void* dQ, void* dK, void* dV, float* delta,
                 int B, int H, int N, int d, int dtype, void* stream);
 
+/*
+ * Backward of sphattn_grn_fwd: with s_ij = mult[b,j] (q_i . k_j) and K/V heads shared by groups
+ * of H / H_kv query heads,
+ *
+ *     dQ[b,h,i,:] = sum_j ds_ij mult[b,j] K[b,g,j,:]
+ *     dK[b,g,j,:] = mult[b,j] sum_{h in group g} sum_i ds_ij Q[b,h,i,:]
+ *     dV[b,g,j,:] = sum_{h in group g} sum_i r_i s_ij dO[b,h,i,:]
+ *
+ * with ds_ij, r_i, delta_i as in sphattn_bwd.  The multiplicities are data: no gradient.
+ *   Q, O, dO, dQ : [B,H,N,d];  K, V, dK, dV : [B,H_kv,N,d];  Z, delta : [B,H,N] fp32;
+ *   mult : [B,N] fp32 or NULL (all ones).
+ * Everything else as sphattn_bwd, which is this call with mult == NULL and H_kv == H.
+ */
+int sphattn_grn_bwd(const void* Q, const void* K, const void* V, const float* mult,
+                    const void* O, const void* dO, const float* Z,
+                    void* dQ, void* dK, void* dV, float* delta,
+                    int B, int H, int H_kv, int N, int d, int dtype, void* stream);
+
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* sphattn_strerror(int code);
 

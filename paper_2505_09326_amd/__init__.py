@@ -22,7 +22,7 @@ _DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN
 
 EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_fwd_z", "sphattn_grn_fwd", "sphattn_normalized_fwd",
                     "sphattn_softmax_fwd", "sphattn_partial_fwd", "sphattn_combine", "sphattn_splitkv_fwd",
-                    "sphattn_splitkv_workspace_bytes", "sphattn_splitkv_heuristic", "sphattn_bwd",
+                    "sphattn_splitkv_workspace_bytes", "sphattn_splitkv_heuristic", "sphattn_bwd", "sphattn_grn_bwd",
                     "sphattn_strerror", "sphattn_version")
 
 NORMALIZERS = {"l2": 0, "softmax": 1, "l1": 2, "sqrelu": 3}
@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
         lib.sphattn_splitkv_heuristic.argtypes = [ip, ip, ip, ip, ip]
         lib.sphattn_bwd.restype = ip
         lib.sphattn_bwd.argtypes = [vp] * 10 + [ip, ip, ip, ip, ip, vp]
+        lib.sphattn_grn_bwd.restype = ip
+        lib.sphattn_grn_bwd.argtypes = [vp] * 11 + [ip, ip, ip, ip, ip, ip, vp]
         lib.sphattn_strerror.restype = ctypes.c_char_p
         lib.sphattn_strerror.argtypes = [ip]
         lib.sphattn_version.restype = ip
@@ -280,6 +282,26 @@ def sphattn_bwd(Q, K, V, O, dO, Z, dQ=None, dK=None, dV=None, delta=None, dtype=
     rc = lib.sphattn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), Z.data_ptr(),
                          dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), delta.data_ptr(),
                          B, H, N, d, _dtype_code(dtype), ctypes.c_void_p(_stream_of(Q, stream)))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return dQ, dK, dV
+
+
+def sphattn_grn_bwd(Q, K, V, mult, O, dO, Z, dQ=None, dK=None, dV=None, delta=None, dtype="bf16", stream=None):
+    """Gradients (dQ, dK, dV) of sum(O * dO) for O = sphattn_grn_fwd(Q, K, V, mult): per-gene
+    multiplicities mult[B,N] (or None) and K, V of shape [B,H_kv,N,d]."""
+    import torch
+    lib = load_library()
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    if delta is None:
+        delta = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    _check_device("all arguments", Q, K, V, mult, O, dO, Z, dQ, dK, dV, delta)
+    B, H, N, d = Q.shape
+    rc = lib.sphattn_grn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(mult), O.data_ptr(), dO.data_ptr(),
+                             Z.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), delta.data_ptr(),
+                             B, H, K.shape[1], N, d, _dtype_code(dtype), ctypes.c_void_p(_stream_of(Q, stream)))
     if rc != 0:
         raise SphattnError(rc, sphattn_strerror(rc))
     return dQ, dK, dV

@@ -251,26 +251,41 @@ int launch_combine(const float* o_parts, const float* z_parts, int n_parts, void
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
-template <int D, bool HALF>
-int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* Z,
-               void* dQ, void* dK, void* dV, float* delta, int B, int H, int N, hipStream_t stream)
+struct BwdProblem {
+    const void* Q; const void* K; const void* V; const float* mult; const void* O; const void* dO;
+    const float* Z; void* dQ; void* dK; void* dV; float* delta;
+    int B, H, H_kv, N;
+    hipStream_t stream;
+};
+
+template <int D, bool HALF, bool MULT>
+int launch_bwd(const BwdProblem& p)
 {
     constexpr int tile = kBC * D * 2;
-    constexpr int lds_dq = 2 * 2 * tile, lds_dkv = 2 * (2 * tile + 2 * kBC * 4);
-    auto kq = bwd_dq_kernel<D, HALF>;
-    auto kkv = bwd_dkv_kernel<D, HALF>;
+    constexpr int lds_dq = 2 * (2 * tile + (MULT ? kBC * 4 : 0)), lds_dkv = 2 * (2 * tile + 2 * kBC * 4);
+    auto kq = bwd_dq_kernel<D, HALF, MULT>;
+    auto kkv = bwd_dkv_kernel<D, HALF, MULT>;
     static std::atomic<uint64_t> done_q{0}, done_kv{0};
     if (!raise_lds_limit(kq, lds_dq, done_q) || !raise_lds_limit(kkv, lds_dkv, done_kv)) return SPHATTN_ERR_LAUNCH;
-    const int n_qtiles = (N + 255) / 256, n_ktiles = (N + 127) / 128;
-    const long long wg_q = (long long)B * H * n_qtiles, wg_kv = (long long)B * H * n_ktiles;
-    if (wg_kv > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    const int n_qtiles = (p.N + 255) / 256, n_ktiles = (p.N + 127) / 128;
+    const long long wg_q = (long long)p.B * p.H * n_qtiles, wg_kv = (long long)p.B * p.H_kv * n_ktiles;
+    if (wg_q > 0x7fffffff || wg_kv > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    const int kv_group = p.H / p.H_kv;
     // delta is written by the first kernel and read by the second, in stream order
-    hipLaunchKernelGGL(kq, dim3((unsigned)wg_q), dim3(kThreads), lds_dq, stream,
-                       Q, K, V, O, dO, Z, dQ, delta, N, n_qtiles, (int)wg_q);
+    hipLaunchKernelGGL(kq, dim3((unsigned)wg_q), dim3(kThreads), lds_dq, p.stream,
+                       p.Q, p.K, p.V, p.mult, p.O, p.dO, p.Z, p.dQ, p.delta, p.N, p.H, kv_group, n_qtiles, (int)wg_q);
     if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
-    hipLaunchKernelGGL(kkv, dim3((unsigned)wg_kv), dim3(kThreads), lds_dkv, stream,
-                       Q, K, V, dO, Z, (const float*)delta, dK, dV, N, n_ktiles, (int)wg_kv);
+    hipLaunchKernelGGL(kkv, dim3((unsigned)wg_kv), dim3(kThreads), lds_dkv, p.stream,
+                       p.Q, p.K, p.V, p.mult, p.dO, p.Z, (const float*)p.delta, p.dK, p.dV,
+                       p.N, p.H, kv_group, n_ktiles, (int)wg_kv);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
+}
+
+template <bool MULT>
+int dispatch_bwd(const BwdProblem& p, int d, int dtype)
+{
+    if (dtype == SPHATTN_F16) return d == 128 ? launch_bwd<128, true, MULT>(p) : launch_bwd<64, true, MULT>(p);
+    return d == 128 ? launch_bwd<128, false, MULT>(p) : launch_bwd<64, false, MULT>(p);
 }
 
 size_t workspace_bytes(int B, int H, int N, int d, int n_splits)
@@ -424,35 +439,39 @@ int sphattn_splitkv_fwd(const void* Q, const void* K, const void* V, const float
                     : launch_combine<64>(o_parts, z_parts, plan.n_splits, O, Z, rows, dtype, (hipStream_t)stream);
 }
 
-int sphattn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* Z,
-                void* dQ, void* dK, void* dV, float* delta,
-                int B, int H, int N, int d, int dtype, void* stream)
+int sphattn_grn_bwd(const void* Q, const void* K, const void* V, const float* mult,
+                    const void* O, const void* dO, const float* Z,
+                    void* dQ, void* dK, void* dV, float* delta,
+                    int B, int H, int H_kv, int N, int d, int dtype, void* stream)
 {
     if (!Q || !K || !V || !O || !dO || !Z || !dQ || !dK || !dV || !delta) return SPHATTN_ERR_NULL;
-    const int rc = check_shape(B, H, H, N, N, d, dtype);
+    const int rc = check_shape(B, H, H_kv, N, N, d, dtype);
     if (rc != SPHATTN_OK) return rc;
     if (dtype != SPHATTN_BF16 && dtype != SPHATTN_F16) return SPHATTN_ERR_DTYPE;
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O | (uintptr_t)dO |
          (uintptr_t)dQ | (uintptr_t)dK | (uintptr_t)dV) & 15)
         return SPHATTN_ERR_ALIGN;
-    if (((uintptr_t)Z | (uintptr_t)delta) & 3) return SPHATTN_ERR_ALIGN;
-    const size_t tb = (size_t)B * H * N * d * 2, rb = (size_t)B * H * N * 4;
-    const void* ins[6] = {Q, K, V, O, dO, Z};
-    const size_t in_bytes[6] = {tb, tb, tb, tb, tb, rb};
+    if (((uintptr_t)Z | (uintptr_t)delta | (uintptr_t)mult) & 3) return SPHATTN_ERR_ALIGN;
+    const size_t tq = (size_t)B * H * N * d * 2, tkv = (size_t)B * H_kv * N * d * 2, rb = (size_t)B * H * N * 4;
+    const void* ins[7] = {Q, K, V, O, dO, Z, mult};
+    const size_t in_bytes[7] = {tq, tkv, tkv, tq, tq, rb, mult ? (size_t)B * N * 4 : 0};
     void* outs[4] = {dQ, dK, dV, delta};
-    const size_t out_bytes[4] = {tb, tb, tb, rb};
+    const size_t out_bytes[4] = {tq, tkv, tkv, rb};
     for (int o = 0; o < 4; ++o) {
-        for (int i = 0; i < 6; ++i)
-            if (overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return SPHATTN_ERR_ALIAS;
-        for (int p = o + 1; p < 4; ++p)
-            if (overlaps(outs[o], out_bytes[o], outs[p], out_bytes[p])) return SPHATTN_ERR_ALIAS;
+        for (int i = 0; i < 7; ++i)
+            if (ins[i] && overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return SPHATTN_ERR_ALIAS;
+        for (int q = o + 1; q < 4; ++q)
+            if (overlaps(outs[o], out_bytes[o], outs[q], out_bytes[q])) return SPHATTN_ERR_ALIAS;
     }
-    hipStream_t st = (hipStream_t)stream;
-    if (dtype == SPHATTN_F16)
-        return d == 128 ? launch_bwd<128, true>(Q, K, V, O, dO, Z, dQ, dK, dV, delta, B, H, N, st)
-                        : launch_bwd<64, true>(Q, K, V, O, dO, Z, dQ, dK, dV, delta, B, H, N, st);
-    return d == 128 ? launch_bwd<128, false>(Q, K, V, O, dO, Z, dQ, dK, dV, delta, B, H, N, st)
-                    : launch_bwd<64, false>(Q, K, V, O, dO, Z, dQ, dK, dV, delta, B, H, N, st);
+    const BwdProblem p{Q, K, V, mult, O, dO, Z, dQ, dK, dV, delta, B, H, H_kv, N, (hipStream_t)stream};
+    return mult ? dispatch_bwd<true>(p, d, dtype) : dispatch_bwd<false>(p, d, dtype);
+}
+
+int sphattn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* Z,
+                void* dQ, void* dK, void* dV, float* delta,
+                int B, int H, int N, int d, int dtype, void* stream)
+{
+    return sphattn_grn_bwd(Q, K, V, nullptr, O, dO, Z, dQ, dK, dV, delta, B, H, H, N, d, dtype, stream);
 }
 
 const char* sphattn_strerror(int code)

@@ -21,6 +21,11 @@
 // into LDS as 1 KB blocks of 16 rows x 64 bytes, which serve both as row-major A operands
 // (lane reads 16 bytes at 64 n16 + 16 g) and, through ds_read_b64_tr_b16, as transposed A
 // operands; two LDS buffers, one barrier per streamed tile.
+//
+// Gene-regulatory-network options (MULT, kv_group), as in the forward: s_ij = m_j (q_i . k_j),
+// so dQ_i = sum_j ds_ij m_j k_j and dK_j = m_j sum_i ds_ij q_i (the multiplicities are data and
+// get no gradient); kv_group query heads share a K/V head, whose dK and dV sum over the
+// group's query heads (the dK/dV workgroup streams them one after the other).
 #pragma once
 #include "sphattn_pipelined.hpp"
 
@@ -50,17 +55,20 @@ __device__ __forceinline__ float dot8(i32x4 a, i32x4 b, float acc)
 // ---------------------------------------------------------------------------
 // dQ.  Workgroup = 4 waves x 64 query rows (four blocks of 16).  Streams K/V tiles of 64 keys.
 // ---------------------------------------------------------------------------
-template <int D, bool HALF>
+template <int D, bool HALF, bool MULT>
 __global__ __launch_bounds__(kThreads, 1)
 void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, const void* __restrict__ Vv,
+                   const float* __restrict__ mult,
                    const void* __restrict__ Ov, const void* __restrict__ dOv, const float* __restrict__ Z,
-                   void* __restrict__ dQv, float* __restrict__ delta, int N, int n_qtiles, int n_wg)
+                   void* __restrict__ dQv, float* __restrict__ delta,
+                   int N, int H, int kv_group, int n_qtiles, int n_wg)
 {
     constexpr int BC = kBC, NQ = 4, BR = kWaves * 16 * NQ;
     constexpr int ROWB = D * 2, TILE = BC * ROWB;
     constexpr int KK = D / 32, DB = D / 16, KBLK = ROWB / 64;
     constexpr int VLDS = TILE;                     // V tile behind the K tile
-    constexpr int BUF_BYTES = 2 * TILE;
+    constexpr int MLDS = 2 * TILE;                 // then the tile's 64 multiplicities (MULT only)
+    constexpr int BUF_BYTES = 2 * TILE + (MULT ? BC * 4 : 0);
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
@@ -70,6 +78,8 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
     const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
     const int bh = lid / n_qtiles, qt = lid % n_qtiles;
     const size_t head_off = (size_t)bh * N * D;
+    const int bidx = bh / H;
+    const size_t kv_off = (size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * N * D;
     const int q0 = qt * BR + wave * 16 * NQ;
 
     // own rows: Q and dO as B operands (lane: row q0 + 16qb + n16, elements 32kk + 8g .. +7);
@@ -105,8 +115,9 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
         for (int qb = 0; qb < NQ; ++qb) dq[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // tile copies: wave w brings rows 16w .. 16w+15 of the K and of the V tile (KBLK blocks each)
-    const i32x4 krw = rsrc_words((const unsigned char*)Kv + head_off * 2, (uint32_t)N * ROWB);
-    const i32x4 vrw = rsrc_words((const unsigned char*)Vv + head_off * 2, (uint32_t)N * ROWB);
+    const i32x4 krw = rsrc_words((const unsigned char*)Kv + kv_off * 2, (uint32_t)N * ROWB);
+    const i32x4 vrw = rsrc_words((const unsigned char*)Vv + kv_off * 2, (uint32_t)N * ROWB);
+    const i32x4 mrw = rsrc_words(MULT ? mult + (size_t)bidx * N : nullptr, MULT ? (uint32_t)N * 4 : 0);
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int ld_lane = (16 * wave + (lane >> 2)) * ROWB + (lane & 3) * 16;
     auto copy_tile = [&](int tile, uint32_t buf) {
@@ -115,6 +126,7 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
             copy_to_lds(krw, buf + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
             copy_to_lds(vrw, buf + VLDS + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
         }
+        if (MULT && wave == 0 && lane < BC / 4) copy_to_lds(mrw, buf + MLDS, lane * 16, tile * BC * 4);
     };
     const int alane = n16 * 64 + g * 16;                           // row-major A operand
     const int tlane = (4 * g + (n16 >> 2)) * 64 + (n16 & 3) * 8;   // transposed A operand
@@ -151,9 +163,15 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
                         gg[qb] = mfma16x16<HALF>(va, gf[qb][kk], gg[qb]);
                     }
                 }
+                // multipliers of the lane's keys 16rb + 4g + t: on the score, and again on ds
+                f32x4 mk = {1.f, 1.f, 1.f, 1.f};
+                if constexpr (MULT)
+                    mk = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + MLDS + (16 * rb + 4 * g) * 4));
 #pragma unroll
                 for (int qb = 0; qb < NQ; ++qb) {
-                    const f32x4 ds = gg[qb] * c1[qb] - s[qb] * c2[qb];
+                    f32x4 ds;
+                    if constexpr (MULT) ds = (gg[qb] * c1[qb] - (s[qb] * mk) * c2[qb]) * mk;
+                    else ds = gg[qb] * c1[qb] - s[qb] * c2[qb];
                     dsp[qb][2 * kb] = pack2<HALF>(ds[0], ds[1]);
                     dsp[qb][2 * kb + 1] = pack2<HALF>(ds[2], ds[3]);
                 }
@@ -193,11 +211,13 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
 // ---------------------------------------------------------------------------
 // Two workgroups per CU (two waves per SIMD): the loop is not software-pipelined, so a second
 // wave fills the gaps between LDS reads and matrix instructions (C3 shape: 3.6 -> 2.5 ms).
-template <int D, bool HALF>
+template <int D, bool HALF, bool MULT>
 __global__ __launch_bounds__(kThreads, 2)
 void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, const void* __restrict__ Vv,
+                    const float* __restrict__ mult,
                     const void* __restrict__ dOv, const float* __restrict__ Z, const float* __restrict__ delta,
-                    void* __restrict__ dKv, void* __restrict__ dVv, int N, int n_ktiles, int n_wg)
+                    void* __restrict__ dKv, void* __restrict__ dVv,
+                    int N, int H, int kv_group, int n_ktiles, int n_wg)
 {
     constexpr int BC = kBC, NK = 2, BKEYS = kWaves * 16 * NK;
     constexpr int ROWB = D * 2, TILE = BC * ROWB;
@@ -211,16 +231,21 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, g = lane >> 4;
     const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
-    const int bh = lid / n_ktiles, kt = lid % n_ktiles;
-    const size_t head_off = (size_t)bh * N * D;
+    // lid counts (K/V head, key tile); the query heads h0 .. h0 + kv_group - 1 of batch bidx use it
+    const int kvh = lid / n_ktiles, kt = lid % n_ktiles;
+    const int H_kv = H / kv_group;
+    const int bidx = kvh / H_kv, h0 = (kvh % H_kv) * kv_group;
+    const size_t head_off = (size_t)kvh * N * D;   // of K, V, dK, dV
     const int k0 = kt * BKEYS + wave * 16 * NK;
 
     // own keys: K and V as B operands (lane: key k0 + 16kb + n16, elements 32kk + 8g .. +7)
     i32x4 kf[NK][KK], vf[NK][KK];
+    float mk[NK];                                  // the lane's keys' multiplicities
 #pragma unroll
     for (int kb = 0; kb < NK; ++kb) {
         int row = k0 + kb * 16 + n16;
         row = row < N ? row : N - 1;               // keys past the end are computed and dropped
+        mk[kb] = MULT ? mult[(size_t)bidx * N + row] : 1.f;
         const size_t off = (head_off + (size_t)row * D) * 2 + 16 * g;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
@@ -234,13 +259,18 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
 #pragma unroll
         for (int kb = 0; kb < NK; ++kb) { dk[db][kb] = f32x4{0, 0, 0, 0}; dv[db][kb] = f32x4{0, 0, 0, 0}; }
 
-    const i32x4 qrw = rsrc_words((const unsigned char*)Qv + head_off * 2, (uint32_t)N * ROWB);
-    const i32x4 grw = rsrc_words((const unsigned char*)dOv + head_off * 2, (uint32_t)N * ROWB);
-    const i32x4 zrw = rsrc_words(Z + (size_t)bh * N, (uint32_t)N * 4);
-    const i32x4 drw = rsrc_words(delta + (size_t)bh * N, (uint32_t)N * 4);
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int ld_lane = (16 * wave + (lane >> 2)) * ROWB + (lane & 3) * 16;
-    auto copy_tile = [&](int tile, uint32_t buf) {
+    const int n_tiles = (N + BC - 1) / BC;
+    // streamed tile `it` = tile it % n_tiles of query head h0 + it / n_tiles; each head has its
+    // own descriptors, so that rows past the end of a head arrive as zeros
+    auto copy_tile = [&](int it, uint32_t buf) {
+        const int hq = it / n_tiles, tile = it % n_tiles;
+        const size_t qh = (size_t)(bidx * H + h0 + (hq < kv_group ? hq : 0));
+        const i32x4 qrw = rsrc_words((const unsigned char*)Qv + qh * N * D * 2, (uint32_t)N * ROWB);
+        const i32x4 grw = rsrc_words((const unsigned char*)dOv + qh * N * D * 2, (uint32_t)N * ROWB);
+        const i32x4 zrw = rsrc_words(Z + qh * N, (uint32_t)N * 4);
+        const i32x4 drw = rsrc_words(delta + qh * N, (uint32_t)N * 4);
 #pragma unroll
         for (int c = 0; c < KBLK; ++c) {
             copy_to_lds(qrw, buf + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
@@ -253,16 +283,15 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
     const int alane = n16 * 64 + g * 16;
     const int tlane = (4 * g + (n16 >> 2)) * 64 + (n16 & 3) * 8;
 
-    const int n_tiles = (N + BC - 1) / BC;
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     copy_tile(0, lds0);
-    for (int j = 0; j < n_tiles; ++j) {
+    for (int j = 0; j < kv_group * n_tiles; ++j) {
         const uint32_t cur = (j & 1) * BUF_BYTES;
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0)
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        copy_tile(j + 1, lds0 + BUF_BYTES - cur);
+        copy_tile(j + 1, lds0 + BUF_BYTES - cur);  // past the last head: its first tile again, unused
         const SPH_LDS unsigned char* qb_ = smem + cur;
         const SPH_LDS unsigned char* gb_ = smem + cur + GLDS;
 #pragma unroll
@@ -303,8 +332,9 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
                 }
 #pragma unroll
                 for (int kb = 0; kb < NK; ++kb) {
-                    const f32x4 w = s[qb][kb] * r;
-                    const f32x4 ds = gg[qb][kb] * r - s[qb][kb] * c;
+                    const f32x4 sm = MULT ? s[qb][kb] * mk[kb] : s[qb][kb];
+                    const f32x4 w = sm * r;
+                    const f32x4 ds = gg[qb][kb] * r - sm * c;
                     wp[kb][2 * qb] = pack2<HALF>(w[0], w[1]);
                     wp[kb][2 * qb + 1] = pack2<HALF>(w[2], w[3]);
                     dsp[kb][2 * qb] = pack2<HALF>(ds[0], ds[1]);
@@ -337,6 +367,7 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
         if (row < N) {
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
+                if constexpr (MULT) dk[db][kb] *= mk[kb];
                 const i32x2 k4 = {pack2<HALF>(dk[db][kb][0], dk[db][kb][1]), pack2<HALF>(dk[db][kb][2], dk[db][kb][3])};
                 const i32x2 v4 = {pack2<HALF>(dv[db][kb][0], dv[db][kb][1]), pack2<HALF>(dv[db][kb][2], dv[db][kb][3])};
                 *reinterpret_cast<i32x2*>(dKh + (size_t)row * D + 4 * g + db * 16) = k4;

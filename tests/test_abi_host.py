@@ -195,6 +195,16 @@ def test_backward_argument_errors(lib):
     assert call(dV=0x8000000) == -7            # dV is dK
     assert call(delta=0x6000000) == -7         # delta is Z
 
+    def grn(mult=0xB000000, H_kv=1, **over):
+        a = dict(base, **over)
+        return lib.sphattn_grn_bwd(P(a["Q"]), P(a["K"]), P(a["V"]), P(mult), P(a["O"]), P(a["dO"]), P(a["Z"]),
+                                   P(a["dQ"]), P(a["dK"]), P(a["dV"]), P(a["delta"]), 1, 2, H_kv, 300, 64, 1, None)
+    assert grn(H_kv=3) == -2
+    assert grn(H_kv=0) == -2
+    assert grn(mult=0xB000002) == -5
+    assert grn(dK=0xB000000) == -7             # dK is mult
+    assert grn(Q=0) == -1
+
 
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
