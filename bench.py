@@ -86,6 +86,9 @@ def main() -> int:
     ap.add_argument("--splitkv", type=int, default=0, metavar="HEADS",
                     help="also time the split-key forward against the unsplit call on the first HEADS "
                          "heads of batch 0 of the workload (few heads leave CUs idle; the split fills them)")
+    ap.add_argument("--no-mfma-ceiling", action="store_true",
+                    help="skip the loops of nothing but bf16 matrix instructions on Gaussian operands (the "
+                         "rate the matrix pipes sustain at the power limit, reported next to the kernel's)")
     ap.add_argument("--bwd", action="store_true", help="also time the backward pass (sphattn_bwd) on the workload")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run a plain 256 MiB device copy (untimed), as the known-size "
@@ -138,6 +141,16 @@ def main() -> int:
 
     # short problems are bound by launch latency and occupancy, not by the matrix pipes: also
     # state what the launch achieves against the HBM roofline (algorithmic bytes / time)
+    if w.flops < 1e11:
+        # launch latency apart: 1000 launches back to back, one pair of events around them
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(1000):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        result["roofline"]["back_to_back_ms_avg_1000"] = e0.elapsed_time(e1) / 1000.0
     result["roofline"]["hbm_gbs_algorithmic"] = algo_bytes / (ms_kernel * 1e-3) / 1e9
     result["roofline"]["hbm_peak_gbs"] = HBM_PEAK_GBS
     # the paper's own figures, another machine: context only, never the baseline
@@ -194,6 +207,27 @@ def main() -> int:
             "unsplit_tflops": fl / (ms_u * 1e-3) / 1e12, "split_tflops": fl / (ms_s * 1e-3) / 1e12,
             "split_speedup": ms_u / ms_s,
         }
+
+    if not args.no_mfma_ceiling:
+        # what the matrix pipes sustain on Gaussian operands, matrix instructions only
+        g = torch.Generator(device="cpu").manual_seed(7)
+        ops = torch.randn(32768, generator=g, dtype=torch.float32).to(torch.bfloat16).to(dev)
+        clk = torch.zeros(3, dtype=torch.int64, device=dev)
+        ceil = {}
+        for form, name in ((0, "32x32x16_bf16"), (1, "16x16x32_bf16")):
+            iters = 100000
+            for _ in range(2):
+                flop = pkg.sphattn_mfma_probe(ops, clk, form, iters)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flop = pkg.sphattn_mfma_probe(ops, clk, form, iters)
+            e1.record()
+            torch.cuda.synchronize()
+            c = clk.cpu().tolist()
+            ceil[name] = {"tflops": flop / (e0.elapsed_time(e1) * 1e-3) / 1e12, "shader_ghz": 0.1 * c[0] / max(c[1], 1)}
+        result["mfma_only_ceiling_gaussian_operands"] = ceil
+        result["roofline"]["frac_of_mfma_only_ceiling"] = kern_tflops / ceil["16x16x32_bf16"]["tflops"]
 
     if args.bwd:
         if w.dtype not in ("bf16", "f16"):

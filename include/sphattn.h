@@ -237,6 +237,21 @@ int sphattn_grn_bwd(const void* Q, const void* K, const void* V, const float* mu
                     void* dQ, void* dK, void* dV, float* delta,
                     int B, int H, int H_kv, int N, int d, int dtype, void* stream);
 
+/*
+ * Measurement aid, not part of the method: one launch (256 workgroups of 256 threads, one per
+ * CU) of a loop of nothing but bf16 matrix instructions, to measure what the matrix pipes
+ * sustain on given operand values next to the attention kernels (on random data the part is
+ * power-bound well below its nominal peak).
+ *   operands : 64 KB of device memory, 16-byte aligned, read as bfloat16 operand values.
+ *   clocks   : 3 int64 on the device, 8-byte aligned; receives {shader clocks, 100 MHz reference
+ *              ticks} spent in the loop by workgroup 0 (the third is scratch).
+ *   form     : 0 = v_mfma_f32_32x32x16_bf16 (16 per iteration), 1 = v_mfma_f32_16x16x32_bf16 (32 per
+ *              iteration); either way 256 * 4 waves * iters * 16 * 32768 flop per launch.
+ *   iters    : 1 .. 2^24.
+ * Errors: SPHATTN_ERR_NULL, SPHATTN_ERR_SHAPE (form, iters), SPHATTN_ERR_ALIGN, SPHATTN_ERR_LAUNCH.
+ */
+int sphattn_mfma_probe(const void* operands, long long* clocks, int form, int iters, void* stream);
+
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* sphattn_strerror(int code);
 

@@ -22,7 +22,7 @@ _DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN
 
 EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_fwd_z", "sphattn_grn_fwd", "sphattn_normalized_fwd",
                     "sphattn_softmax_fwd", "sphattn_partial_fwd", "sphattn_combine", "sphattn_splitkv_fwd",
-                    "sphattn_splitkv_workspace_bytes", "sphattn_splitkv_heuristic", "sphattn_bwd", "sphattn_grn_bwd",
+                    "sphattn_splitkv_workspace_bytes", "sphattn_splitkv_heuristic", "sphattn_bwd", "sphattn_grn_bwd", "sphattn_mfma_probe",
                     "sphattn_strerror", "sphattn_version")
 
 NORMALIZERS = {"l2": 0, "softmax": 1, "l1": 2, "sqrelu": 3}
@@ -71,6 +71,8 @@ def load_library() -> ctypes.CDLL:
         lib.sphattn_bwd.argtypes = [vp] * 10 + [ip, ip, ip, ip, ip, vp]
         lib.sphattn_grn_bwd.restype = ip
         lib.sphattn_grn_bwd.argtypes = [vp] * 11 + [ip, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_mfma_probe.restype = ip
+        lib.sphattn_mfma_probe.argtypes = [vp, vp, ip, ip, vp]
         lib.sphattn_strerror.restype = ctypes.c_char_p
         lib.sphattn_strerror.argtypes = [ip]
         lib.sphattn_version.restype = ip
@@ -305,3 +307,16 @@ def sphattn_grn_bwd(Q, K, V, mult, O, dO, Z, dQ=None, dK=None, dV=None, delta=No
     if rc != 0:
         raise SphattnError(rc, sphattn_strerror(rc))
     return dQ, dK, dV
+
+
+def sphattn_mfma_probe(operands, clocks, form: int, iters: int, stream=None):
+    """Measurement aid: one launch of a loop of bf16 matrix instructions only (form 0: 32x32x16,
+    1: 16x16x32) on `operands` (64 KB device tensor); `clocks` (3 int64 on the device) receives
+    shader clocks and 100 MHz ticks of workgroup 0.  Returns the flop count of the launch."""
+    lib = load_library()
+    _check_device("operands, clocks", operands, clocks)
+    rc = lib.sphattn_mfma_probe(operands.data_ptr(), clocks.data_ptr(), int(form), int(iters),
+                                ctypes.c_void_p(_stream_of(operands, stream)))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return 256.0 * 4 * iters * 16 * 32768.0

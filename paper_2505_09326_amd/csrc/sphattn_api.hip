@@ -474,6 +474,20 @@ int sphattn_bwd(const void* Q, const void* K, const void* V, const void* O, cons
     return sphattn_grn_bwd(Q, K, V, nullptr, O, dO, Z, dQ, dK, dV, delta, B, H, H, N, d, dtype, stream);
 }
 
+int sphattn_mfma_probe(const void* operands, long long* clocks, int form, int iters, void* stream)
+{
+    if (!operands || !clocks) return SPHATTN_ERR_NULL;
+    if (iters <= 0 || iters > (1 << 24) || (form != 0 && form != 1)) return SPHATTN_ERR_SHAPE;
+    if (((uintptr_t)operands & 15) || ((uintptr_t)clocks & 7)) return SPHATTN_ERR_ALIGN;
+    if (form == 0)
+        hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(256), dim3(256), 0, (hipStream_t)stream,
+                           (const i32x4*)operands, clocks, iters);
+    else
+        hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(256), dim3(256), 0, (hipStream_t)stream,
+                           (const i32x4*)operands, clocks, iters);
+    return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
+}
+
 const char* sphattn_strerror(int code)
 {
     switch (code) {

@@ -323,4 +323,62 @@ void combine_kernel(const float* __restrict__ o_parts, const float* __restrict__
     }
 }
 
+// ---------------------------------------------------------------------------
+// Measurement aid: a loop of nothing but matrix instructions on operands taken from memory
+// (the benchmark fills them with Gaussian values), to measure what the matrix pipes sustain at
+// the power limit next to the attention kernel.  FORM 0: v_mfma_f32_32x32x16_bf16, 1:
+// v_mfma_f32_16x16x32_bf16 (twice as many, same flops).  Each lane keeps 16 operand pairs in
+// rotation; clocks[0] / clocks[1] of workgroup 0 = shader clocks / 100 MHz reference ticks.
+// ---------------------------------------------------------------------------
+template <int FORM>
+__global__ __launch_bounds__(256)
+void mfma_probe_kernel(const i32x4* __restrict__ operands, long long* __restrict__ clocks, int iters)
+{
+    constexpr int NP = 16;
+    i32x4 a[NP], b[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        a[i] = operands[(threadIdx.x * 8 + 2 * i) % 4096];
+        b[i] = operands[(threadIdx.x * 8 + 2 * i + 1) % 4096];
+    }
+    f32x16 c32[4];
+    f32x4 c16[16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) c32[i][e] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) c16[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const long long t0 = clock64(), w0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+        if constexpr (FORM == 0) {
+#pragma unroll
+            for (int i = 0; i < NP; ++i)
+                c32[i % 4] = mfma16<false>(a[i], b[i], c32[i % 4]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2 * NP; ++i)
+                c16[i % 16] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    __builtin_bit_cast(bf16x8, a[i % NP]), __builtin_bit_cast(bf16x8, b[(i + i / NP) % NP]), c16[i % 16], 0, 0, 0);
+        }
+        if ((it & 63) == 63) {                     // keep the sums finite
+#pragma unroll
+            for (int i = 0; i < 4; ++i) c32[i] *= 0.001f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c16[i] *= 0.001f;
+        }
+    }
+    const long long t1 = clock64(), w1 = wall_clock64();
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sum += c32[i][0] + c32[i][7];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sum += c16[i][0] + c16[i][3];
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        clocks[0] = t1 - t0;
+        clocks[1] = w1 - w0;
+    }
+    if (sum == 12345.678f) clocks[2] = 1;          // keeps the loop alive; never true in practice
+}
+
 }  // namespace sphattn

@@ -111,7 +111,7 @@ __device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes)
 __device__ __forceinline__ void copy_to_lds(i32x4 rsrc, uint32_t lds, int voff, int soff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+                 :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
 
 template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>

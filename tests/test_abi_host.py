@@ -206,6 +206,16 @@ def test_backward_argument_errors(lib):
     assert grn(Q=0) == -1
 
 
+def test_mfma_probe_argument_errors(lib):
+    P = ctypes.c_void_p
+    assert lib.sphattn_mfma_probe(P(0), P(0x2000), 0, 10, None) == -1
+    assert lib.sphattn_mfma_probe(P(0x1000), P(0), 0, 10, None) == -1
+    assert lib.sphattn_mfma_probe(P(0x1000), P(0x2000), 2, 10, None) == -2
+    assert lib.sphattn_mfma_probe(P(0x1000), P(0x2000), 0, 0, None) == -2
+    assert lib.sphattn_mfma_probe(P(0x1008), P(0x2000), 0, 10, None) == -5
+    assert lib.sphattn_mfma_probe(P(0x1000), P(0x2004), 0, 10, None) == -5
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
