@@ -264,9 +264,8 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
     const int n_tiles = (N + BC - 1) / BC;
     // streamed tile `it` = tile it % n_tiles of query head h0 + it / n_tiles; each head has its
     // own descriptors, so that rows past the end of a head arrive as zeros
-    auto copy_tile = [&](int it, uint32_t buf) {
-        const int hq = it / n_tiles, tile = it % n_tiles;
-        const size_t qh = (size_t)(bidx * H + h0 + (hq < kv_group ? hq : 0));
+    auto copy_tile = [&](int hq, int tile, uint32_t buf) {
+        const size_t qh = (size_t)(bidx * H + h0 + hq);
         const i32x4 qrw = rsrc_words((const unsigned char*)Qv + qh * N * D * 2, (uint32_t)N * ROWB);
         const i32x4 grw = rsrc_words((const unsigned char*)dOv + qh * N * D * 2, (uint32_t)N * ROWB);
         const i32x4 zrw = rsrc_words(Z + qh * N, (uint32_t)N * 4);
@@ -284,14 +283,17 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
     const int tlane = (4 * g + (n16 >> 2)) * 64 + (n16 & 3) * 8;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    copy_tile(0, lds0);
+    copy_tile(0, 0, lds0);
+    int next_hq = 0, next_tile = 0;                // head and tile of the copy issued in iteration j
     for (int j = 0; j < kv_group * n_tiles; ++j) {
         const uint32_t cur = (j & 1) * BUF_BYTES;
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0)
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        copy_tile(j + 1, lds0 + BUF_BYTES - cur);  // past the last head: its first tile again, unused
+        if (++next_tile == n_tiles) { next_tile = 0; ++next_hq; }
+        // past the last head: the first head's first tile again, unused
+        copy_tile(next_hq < kv_group ? next_hq : 0, next_tile, lds0 + BUF_BYTES - cur);
         const SPH_LDS unsigned char* qb_ = smem + cur;
         const SPH_LDS unsigned char* gb_ = smem + cur + GLDS;
 #pragma unroll
@@ -327,7 +329,7 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
                 f32x4 r, c;
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    r[t] = zq[t] > 0.f ? 1.0f / __builtin_sqrtf(zq[t]) : 0.f;
+                    r[t] = zq[t] > 0.f ? __builtin_amdgcn_rsqf(zq[t]) : 0.f;   // v_rsq_f32, 1 ulp
                     c[t] = dq_[t] * r[t] * r[t];
                 }
 #pragma unroll
