@@ -238,15 +238,44 @@ int sphattn_grn_bwd(const void* Q, const void* K, const void* V, const float* mu
                     int B, int H, int H_kv, int N, int d, int dtype, void* stream);
 
 /*
+ * Spherical attention with Q, K AND V stored in OCP E4M3 and both contractions on the fp8
+ * matrix instructions (paper, Section 1 and Section 3.1: without the row-wise exponential the
+ * whole operator can run at the matrix cores' low-precision rate).  Same function as
+ * sphattn_fwd on the stored values, O_i = (sum_j s_ij v_j) / sqrt(sum_j s_ij^2) with
+ * s_ij = q_i . k_j, except that the scores are rounded to E4M3 before they are used: row i is
+ * divided by the power of two 2^e_i with |q_i| max_j |k_j| / 440 = m 2^e_i, m in [0.5, 1), rounded
+ * to nearest even, and both sums are taken over the rounded values (the row factor cancels in
+ * the quotient).  The result carries the relative error of a 3-bit mantissa on every term
+ * of the sum: about 2.7 % of rms(O) in the root mean square and up to about 15 % of rms(O) on
+ * single elements, not the 2^-9 of the 16-bit paths.
+ *   Q, K, V  : device, [B,H,N,d] contiguous, one byte per element (E4M3, finite values),
+ *              16-byte aligned.  d must be 128 (anything else: SPHATTN_ERR_HEAD_DIM).
+ *   O        : device, [B,H,N,d] bfloat16, written by the call, must not overlap the inputs.
+ *   workspace: device scratch owned by the caller, 16-byte aligned, at least
+ *              sphattn_fp8_workspace_bytes(B, H, N, d) bytes (a transposed copy of V padded to
+ *              whole 128-key tiles, and the largest key norm of every head); overwritten by the
+ *              call, must not overlap Q, K, V or O.  A NULL, misaligned or short workspace
+ *              returns SPHATTN_ERR_WORKSPACE.  Calls that share a workspace must be ordered.
+ * Three launches on `stream` (clear, prepare, attention); no allocation, no synchronisation.
+ * Other errors as sphattn_fwd.  sphattn_fp8_workspace_bytes returns 0 for an invalid shape.
+ */
+size_t sphattn_fp8_workspace_bytes(int B, int H, int N, int d);
+int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O,
+                    void* workspace, size_t workspace_bytes,
+                    int B, int H, int N, int d, void* stream);
+
+/*
  * Measurement aid, not part of the method: one launch (256 workgroups of 256 threads, one per
- * CU) of a loop of nothing but bf16 matrix instructions, to measure what the matrix pipes
+ * CU) of a loop of nothing but matrix instructions, to measure what the matrix pipes
  * sustain on given operand values next to the attention kernels (on random data the part is
  * power-bound well below its nominal peak).
- *   operands : 64 KB of device memory, 16-byte aligned, read as bfloat16 operand values.
+ *   operands : 64 KB of device memory, 16-byte aligned, read as operand values (bfloat16 for
+ *              forms 0 and 1, E4M3 bytes for form 2).
  *   clocks   : 3 int64 on the device, 8-byte aligned; receives {shader clocks, 100 MHz reference
  *              ticks} spent in the loop by workgroup 0 (the third is scratch).
  *   form     : 0 = v_mfma_f32_32x32x16_bf16 (16 per iteration), 1 = v_mfma_f32_16x16x32_bf16 (32 per
- *              iteration); either way 256 * 4 waves * iters * 16 * 32768 flop per launch.
+ *              iteration), 2 = v_mfma_f32_16x16x128_f8f6f4 on E4M3 (8 per iteration); in every
+ *              form 256 * 4 waves * iters * 16 * 32768 flop per launch.
  *   iters    : 1 .. 2^24.
  * Errors: SPHATTN_ERR_NULL, SPHATTN_ERR_SHAPE (form, iters), SPHATTN_ERR_ALIGN, SPHATTN_ERR_LAUNCH.
  */

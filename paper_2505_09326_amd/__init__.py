@@ -22,7 +22,8 @@ _DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN
 
 EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_fwd_z", "sphattn_grn_fwd", "sphattn_normalized_fwd",
                     "sphattn_softmax_fwd", "sphattn_partial_fwd", "sphattn_combine", "sphattn_splitkv_fwd",
-                    "sphattn_splitkv_workspace_bytes", "sphattn_splitkv_heuristic", "sphattn_bwd", "sphattn_grn_bwd", "sphattn_mfma_probe",
+                    "sphattn_splitkv_workspace_bytes", "sphattn_splitkv_heuristic", "sphattn_bwd", "sphattn_grn_bwd",
+                    "sphattn_fp8_workspace_bytes", "sphattn_fp8_fwd", "sphattn_mfma_probe",
                     "sphattn_strerror", "sphattn_version")
 
 NORMALIZERS = {"l2": 0, "softmax": 1, "l1": 2, "sqrelu": 3}
@@ -71,6 +72,10 @@ def load_library() -> ctypes.CDLL:
         lib.sphattn_bwd.argtypes = [vp] * 10 + [ip, ip, ip, ip, ip, vp]
         lib.sphattn_grn_bwd.restype = ip
         lib.sphattn_grn_bwd.argtypes = [vp] * 11 + [ip, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_fp8_workspace_bytes.restype = ctypes.c_size_t
+        lib.sphattn_fp8_workspace_bytes.argtypes = [ip, ip, ip, ip]
+        lib.sphattn_fp8_fwd.restype = ip
+        lib.sphattn_fp8_fwd.argtypes = [vp, vp, vp, vp, vp, ctypes.c_size_t, ip, ip, ip, ip, vp]
         lib.sphattn_mfma_probe.restype = ip
         lib.sphattn_mfma_probe.argtypes = [vp, vp, ip, ip, vp]
         lib.sphattn_strerror.restype = ctypes.c_char_p
@@ -270,6 +275,28 @@ def sphattn_splitkv_fwd(Q, K, V, workspace, mult=None, O=None, Z=None, n_splits=
     return O
 
 
+def sphattn_fp8_workspace_bytes(B, H, N, d) -> int:
+    return int(load_library().sphattn_fp8_workspace_bytes(B, H, N, d))
+
+
+def sphattn_fp8_fwd(Q, K, V, workspace, O=None, stream=None):
+    """Spherical attention with Q, K and V all stored in E4M3 (float8_e4m3fn tensors [B,H,N,128])
+    and both contractions on the fp8 matrix instructions; O is bfloat16.  `workspace` is a
+    device byte tensor of at least sphattn_fp8_workspace_bytes(...)."""
+    import torch
+    lib = load_library()
+    if O is None:
+        O = torch.empty(Q.shape, dtype=torch.bfloat16, device=Q.device)
+    _check_device("Q, K, V, O, workspace", Q, K, V, O, workspace)
+    B, H, N, d = Q.shape
+    rc = lib.sphattn_fp8_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), workspace.data_ptr(),
+                             workspace.numel() * workspace.element_size(), B, H, N, d,
+                             ctypes.c_void_p(_stream_of(Q, stream)))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return O
+
+
 def sphattn_bwd(Q, K, V, O, dO, Z, dQ=None, dK=None, dV=None, delta=None, dtype="bf16", stream=None):
     """Gradients (dQ, dK, dV) of sum(O * dO) for O, Z = sphattn_fwd_z(Q, K, V); 16-bit storage."""
     import torch
@@ -310,8 +337,8 @@ def sphattn_grn_bwd(Q, K, V, mult, O, dO, Z, dQ=None, dK=None, dV=None, delta=No
 
 
 def sphattn_mfma_probe(operands, clocks, form: int, iters: int, stream=None):
-    """Measurement aid: one launch of a loop of bf16 matrix instructions only (form 0: 32x32x16,
-    1: 16x16x32) on `operands` (64 KB device tensor); `clocks` (3 int64 on the device) receives
+    """Measurement aid: one launch of a loop of matrix instructions only (form 0: bf16 32x32x16,
+    1: bf16 16x16x32, 2: E4M3 16x16x128) on `operands` (64 KB device tensor); `clocks` (3 int64 on the device) receives
     shader clocks and 100 MHz ticks of workgroup 0.  Returns the flop count of the launch."""
     lib = load_library()
     _check_device("operands, clocks", operands, clocks)

@@ -5,6 +5,7 @@
 #include "sphattn_pipelined.hpp"
 #include "sphattn_softmax32.hpp"
 #include "sphattn_backward.hpp"
+#include "sphattn_fp8.hpp"
 #include "../../include/sphattn.h"
 
 #include <stdint.h>
@@ -16,7 +17,7 @@ namespace {
 
 using namespace sphattn;
 
-constexpr int kVersion = 400;   // 0.4.0
+constexpr int kVersion = 500;   // 0.5.0
 
 bool overlaps(const void* a, size_t an, const void* b, size_t bn)
 {
@@ -474,16 +475,66 @@ int sphattn_bwd(const void* Q, const void* K, const void* V, const void* O, cons
     return sphattn_grn_bwd(Q, K, V, nullptr, O, dO, Z, dQ, dK, dV, delta, B, H, H, N, d, dtype, stream);
 }
 
+size_t sphattn_fp8_workspace_bytes(int B, int H, int N, int d)
+{
+    if (B <= 0 || H <= 0 || N <= 0 || d != kFp8D) return 0;
+    const size_t tiles = ((size_t)N + kFp8Tile - 1) / kFp8Tile;
+    return (size_t)B * H * d * tiles * kFp8Tile + (((size_t)B * H * 4 + 255) & ~(size_t)255);
+}
+
+int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O, void* workspace,
+                    size_t workspace_bytes, int B, int H, int N, int d, void* stream)
+{
+    if (d != kFp8D) return SPHATTN_ERR_HEAD_DIM;
+    if (!Q || !K || !V || !O) return SPHATTN_ERR_NULL;
+    const int rc = check_shape(B, H, H, N, N, d, SPHATTN_FP8QK_BF16V);
+    if (rc != SPHATTN_OK) return rc;
+    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return SPHATTN_ERR_ALIGN;
+    const size_t in_bytes = (size_t)B * H * N * d;
+    if (overlaps(O, in_bytes * 2, Q, in_bytes) || overlaps(O, in_bytes * 2, K, in_bytes) ||
+        overlaps(O, in_bytes * 2, V, in_bytes))
+        return SPHATTN_ERR_ALIAS;
+    const size_t need = sphattn_fp8_workspace_bytes(B, H, N, d);
+    if (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < need) return SPHATTN_ERR_WORKSPACE;
+    if (overlaps(workspace, need, Q, in_bytes) || overlaps(workspace, need, K, in_bytes) ||
+        overlaps(workspace, need, V, in_bytes) || overlaps(workspace, need, O, in_bytes * 2))
+        return SPHATTN_ERR_ALIAS;
+    const int heads = B * H;
+    const int n_tiles = (N + kFp8Tile - 1) / kFp8Tile;
+    const size_t kmax_bytes = ((size_t)heads * 4 + 255) & ~(size_t)255;
+    float* kmax = (float*)workspace;
+    unsigned char* VT = (unsigned char*)workspace + kmax_bytes;
+    hipStream_t st = (hipStream_t)stream;
+    if ((long long)heads * n_tiles > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    hipLaunchKernelGGL(fp8_clear_kernel, dim3((heads + 255) / 256), dim3(256), 0, st, kmax, heads);
+    hipLaunchKernelGGL(fp8_prepare_kernel, dim3((unsigned)(heads * n_tiles)), dim3(256), 0, st,
+                       (const unsigned char*)K, (const unsigned char*)V, VT, kmax, N, n_tiles);
+    constexpr int lds_bytes = 4 * 2 * kFp8Tile * kFp8D;
+    static std::atomic<uint64_t> done{0};
+    auto kern = fwd_fp8_kernel;
+    if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;
+    const int n_qtiles = (N + 255) / 256;
+    const long long n_wg = (long long)heads * n_qtiles;
+    if (n_wg > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, st,
+                       (const unsigned char*)Q, (const unsigned char*)K, (const unsigned char*)VT,
+                       (const float*)kmax, (unsigned short*)O, N, n_tiles, n_qtiles, (int)n_wg);
+    return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
+}
+
 int sphattn_mfma_probe(const void* operands, long long* clocks, int form, int iters, void* stream)
 {
     if (!operands || !clocks) return SPHATTN_ERR_NULL;
-    if (iters <= 0 || iters > (1 << 24) || (form != 0 && form != 1)) return SPHATTN_ERR_SHAPE;
+    if (iters <= 0 || iters > (1 << 24) || form < 0 || form > 2) return SPHATTN_ERR_SHAPE;
     if (((uintptr_t)operands & 15) || ((uintptr_t)clocks & 7)) return SPHATTN_ERR_ALIGN;
     if (form == 0)
         hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(256), dim3(256), 0, (hipStream_t)stream,
                            (const i32x4*)operands, clocks, iters);
-    else
+    else if (form == 1)
         hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(256), dim3(256), 0, (hipStream_t)stream,
+                           (const i32x4*)operands, clocks, iters);
+    else
+        hipLaunchKernelGGL(mfma_probe_kernel<2>, dim3(256), dim3(256), 0, (hipStream_t)stream,
                            (const i32x4*)operands, clocks, iters);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }

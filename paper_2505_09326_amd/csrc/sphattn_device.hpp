@@ -327,7 +327,8 @@ void combine_kernel(const float* __restrict__ o_parts, const float* __restrict__
 // Measurement aid: a loop of nothing but matrix instructions on operands taken from memory
 // (the benchmark fills them with Gaussian values), to measure what the matrix pipes sustain at
 // the power limit next to the attention kernel.  FORM 0: v_mfma_f32_32x32x16_bf16, 1:
-// v_mfma_f32_16x16x32_bf16 (twice as many, same flops).  Each lane keeps 16 operand pairs in
+// v_mfma_f32_16x16x32_bf16 (twice as many, same flops) or v_mfma_f32_16x16x128_f8f6f4 on E4M3
+// operands (half as many, same flops).  Each lane keeps 16 operand pairs in
 // rotation; clocks[0] / clocks[1] of workgroup 0 = shader clocks / 100 MHz reference ticks.
 // ---------------------------------------------------------------------------
 template <int FORM>
@@ -355,11 +356,20 @@ void mfma_probe_kernel(const i32x4* __restrict__ operands, long long* __restrict
 #pragma unroll
             for (int i = 0; i < NP; ++i)
                 c32[i % 4] = mfma16<false>(a[i], b[i], c32[i % 4]);
-        } else {
+        } else if constexpr (FORM == 1) {
 #pragma unroll
             for (int i = 0; i < 2 * NP; ++i)
                 c16[i % 16] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                     __builtin_bit_cast(bf16x8, a[i % NP]), __builtin_bit_cast(bf16x8, b[(i + i / NP) % NP]), c16[i % 16], 0, 0, 0);
+        } else {
+            // E4M3 operands, k = 128: 8 instructions carry the flops of 16 of the bf16 forms
+            typedef __attribute__((ext_vector_type(8))) int i32x8;
+#pragma unroll
+            for (int i = 0; i < NP / 2; ++i) {
+                const i32x8 a8 = __builtin_shufflevector(a[2 * i], a[2 * i + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+                const i32x8 b8 = __builtin_shufflevector(b[2 * i], b[2 * i + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+                c16[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, c16[i], 0, 0, 0, 0, 0, 0);
+            }
         }
         if ((it & 63) == 63) {                     // keep the sums finite
 #pragma unroll

@@ -1,0 +1,412 @@
+// All-E4M3 forward: Q, K, V stored in OCP E4M3, BOTH contractions on the fp8 matrix
+// instruction v_mfma_f32_16x16x128_f8f6f4 (k = 128), output in bf16, d = 128.
+//
+// The paper argues (Section 1; Section 3.1) that without the row-wise exponential the whole
+// of attention can run at the matrix cores' low-precision rate.  This kernel is that case
+// taken to its end: the scores, too, go back into the matrix cores as E4M3.
+//
+// What makes that possible for the spherical normaliser and not for SoftMax:
+//   * O_i = o_i / sqrt(z_i) does not change when every score of row i is multiplied by the
+//     same positive factor.  So the scores of a row can be brought into the E4M3 range by a
+//     per-row factor, and nothing has to be undone afterwards: o and z are both accumulated
+//     from the scaled scores and the tail is the plain one.
+//   * By Cauchy-Schwarz |s_ij| <= |q_i| max_j |k_j| =: bound_i.  The factor is the power of two
+//     2^-e_i with bound_i / 440 = m 2^e_i, m in [0.5, 1): every scaled score is inside +-440
+//     (the E4M3 maximum is 448, and the conversion overflows to NaN rather than saturating;
+//     the margin covers the fp32 rounding of the score itself), and the largest possible one
+//     is above 220.  |q_i| comes from the Q fragment in registers, max_j |k_j| of the head
+//     from the preparation pass.  The division by 2^e_i is part of the convert instruction
+//     (v_cvt_scalef32_pk_fp8_f32), which rounds to nearest even.
+//   * z_i = sum_j p_ij^2 is taken from the ROUNDED scores p_ij, on the matrix cores as well:
+//     it is the diagonal of P^T P, and P's register image serves as A and as B operand alike.
+//     One extra matrix instruction per query block and tile replaces 128 VALU FMAs, which
+//     a single wave per SIMD cannot issue in the shadow of the matrix instructions.
+//
+// Matrix-core mapping.  With k = 128 both contractions have the same shape,
+//     S^T block kb (16 keys x 16 queries) = K frag (A: 16 keys x 128 of d) * Q frag (B: 128 x 16 queries)
+//     O^T block db (16 cols of d x 16 queries) += V^T frag (A: 16 cols x 128 keys) * P (B: 128 keys x 16)
+// and lane (n16, g) of an A or B operand holds 32 consecutive k-slots 32g .. 32g+31 of row or
+// column n16.  In the accumulator lane (n16, g) holds query n16 and, in register t, row 4g + t
+// of the block.  The 16 rows of score block kb are therefore chosen to be the keys
+//     key(kb, p) = 32 (p / 4) + 4 kb + (p % 4),    p = 0..15,
+// of the 128-key tile: then register t of block kb in lane group g is key 32g + 4kb + t, and
+// the eight blocks' scores, packed four to a register, are exactly the 32 consecutive
+// k-slots that the second contraction wants from this lane.  Like the 16-bit kernels, the
+// scores never leave their registers.  V is needed as V^T with keys along the contiguous axis;
+// the preparation pass writes that copy once (2 N d bytes of traffic per head against
+// 4 N^2 d flop), so both operand streams are read from LDS with plain 16-byte reads and there
+// is no transposing read at all.
+//
+// Pipeline.  A slot = one score block row kb of the current tile (4 matrix instructions, one
+// per query block) + one V^T fragment db of the previous tile (4 more) + the conversion of the
+// block row finished in the slot before (two score registers read back and one convert
+// instruction behind every matrix instruction).  P is complete one slot into the next tile,
+// so the second contraction of tile T runs in slots 1..7 of tile T+1 and slot 0 of tile T+2.
+// Tiles of 128 keys rotate through four 32 KB LDS buffers, filled straight from HBM/L2
+// (buffer_load ... lds), with one workgroup barrier per tile.
+#pragma once
+#include "sphattn_pipelined.hpp"
+
+namespace sphattn {
+
+constexpr int kFp8Tile = 128;          // keys per tile (one k of the second contraction)
+constexpr int kFp8D = 128;             // head dimension
+
+// ---- preparation: V^T copy and the largest key norm per K/V head -------------------------
+//
+// grid = (heads) x (tiles of 128 keys).  VT[head][c][Np] (E4M3, Np = tiles * 128, zero past
+// N) receives V transposed; kmax[head] receives max_j |k_j| through an integer atomic max on
+// the bits of the non-negative float (kmax must be zero before the launch).
+__global__ __launch_bounds__(256)
+void fp8_prepare_kernel(const unsigned char* __restrict__ K, const unsigned char* __restrict__ V,
+                        unsigned char* __restrict__ VT, float* __restrict__ kmax, int N, int n_tiles)
+{
+    constexpr int D = kFp8D, T = kFp8Tile, LROW = D + 16;
+    __shared__ __attribute__((aligned(16))) unsigned char tile[T * LROW];
+    __shared__ float wmax[4];
+    const int tid = threadIdx.x;
+    const int head = blockIdx.x / n_tiles, kt = blockIdx.x % n_tiles;
+    const int key0 = kt * T;
+    const size_t Np = (size_t)n_tiles * T;
+    const unsigned char* Vh = V + (size_t)head * N * D;
+    const unsigned char* Kh = K + (size_t)head * N * D;
+
+    for (int id = tid; id < T * (D / 16); id += 256) {
+        const int row = id / (D / 16), c16 = id % (D / 16);
+        i32x4 v = {0, 0, 0, 0};
+        if (key0 + row < N) v = *reinterpret_cast<const i32x4*>(Vh + (size_t)(key0 + row) * D + 16 * c16);
+        *reinterpret_cast<i32x4*>(tile + row * LROW + 16 * c16) = v;
+    }
+    // |k_j|^2 of row tid/2, half tid%2
+    float ss = 0.f;
+    {
+        const int row = tid >> 1, half = tid & 1;
+        if (key0 + row < N) {
+            const unsigned char* src = Kh + (size_t)(key0 + row) * D + 64 * half;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const i32x4 w = *reinterpret_cast<const i32x4*>(src + 16 * c);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float a = __builtin_amdgcn_cvt_f32_fp8(w[r], 0), b = __builtin_amdgcn_cvt_f32_fp8(w[r], 1);
+                    const float c2 = __builtin_amdgcn_cvt_f32_fp8(w[r], 2), e = __builtin_amdgcn_cvt_f32_fp8(w[r], 3);
+                    ss += a * a + b * b + c2 * c2 + e * e;
+                }
+            }
+        }
+        ss += __shfl_xor(ss, 1);
+#pragma unroll
+        for (int m = 2; m < 64; m <<= 1) ss = fmaxf(ss, __shfl_xor(ss, m));
+        if ((tid & 63) == 0) wmax[tid >> 6] = ss;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const float m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+        atomicMax(reinterpret_cast<int*>(kmax + head), __float_as_int(__builtin_sqrtf(m)));
+    }
+    // 16-byte pieces of V^T: column c of d, keys key0 + 16q .. +15
+    unsigned char* VTh = VT + (size_t)head * D * Np;
+    for (int id = tid; id < D * (T / 16); id += 256) {
+        const int c = id / (T / 16), q = id % (T / 16);
+        i32x4 out;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            unsigned w = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w |= (unsigned)tile[(16 * q + 4 * r + e) * LROW + c] << (8 * e);
+            out[r] = (int)w;
+        }
+        *reinterpret_cast<i32x4*>(VTh + (size_t)c * Np + key0 + 16 * q) = out;
+    }
+}
+
+__global__ void fp8_clear_kernel(float* __restrict__ p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+// ---- the forward kernel ------------------------------------------------------------------
+//
+// One workgroup = 4 wavefronts = 256 query rows of one (b, h); a wavefront owns NQ = 4 blocks
+// of 16 rows.  VT and kmax come from fp8_prepare_kernel (same stream, earlier).
+__global__ __launch_bounds__(kThreads, 1)
+void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __restrict__ K,
+                    const unsigned char* __restrict__ VT, const float* __restrict__ kmax,
+                    unsigned short* __restrict__ O, int N, int n_tiles, int n_qtiles, int n_wg)
+{
+    constexpr int D = kFp8D, BC = kFp8Tile, NQ = 4;
+    constexpr int BR = kWaves * 16 * NQ;
+    constexpr int KTILE = BC * D;                  // 16 KB, also the V^T tile
+    constexpr int BUF_BYTES = 2 * KTILE;
+    constexpr int NBUF = 4;
+    constexpr int SLOTS = 8;                       // per tile: block rows kb = V^T fragments db
+    constexpr int PD = 2;                          // LDS prefetch distance in slots
+    constexpr int RING = 4;
+    constexpr int NCOPY = 8;                       // 1 KB copies per wave per tile: 4 of K, 4 of V^T
+    static_assert((2 * SLOTS) % RING == 0 && PD < RING, "ring indices must repeat");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    SPH_LDS unsigned char* smem = (SPH_LDS unsigned char*)smem_raw;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int n16 = lane & 15, g = lane >> 4;
+
+    const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
+    const int qt = lid % n_qtiles, bh = lid / n_qtiles;
+    const size_t Np = (size_t)n_tiles * BC;
+    const unsigned char* Qh = Q + (size_t)bh * N * D;
+    const int q0 = qt * BR + wave * 16 * NQ;
+
+    // LDS image of a tile: K blocks (kb, c) and V^T blocks (db, c), 16 rows x 64 bytes each,
+    // row-major, 1 KB, block (r, c) at (2r + c) KB; a fragment read (row n16, bytes 32g..32g+31)
+    // is linear in the lane id within its block: no padding, no bank conflicts.
+    const int flane = (g >> 1) * 1024 + n16 * 64 + (g & 1) * 32;
+    // copies: block 4 wave + c; lane l fills row l/4, bytes 16 (l%4) of the block's 64
+    //   K   block (kb, half): tile row key(kb, l/4), bytes 64 half + 16 (l%4) of the key row
+    //   V^T block (db, half): row 16db + l/4 of V^T, keys 64 half + 16 (l%4) of the tile
+    const int p = lane >> 2;
+    const int kld_lane = (32 * (p >> 2) + (p & 3) + 8 * wave) * D + (lane & 3) * 16;
+    const int vld_lane = (int)((32 * wave + p) * Np) + (lane & 3) * 16;
+
+    // ---- Q fragments and the row factors a_i
+    typedef __attribute__((ext_vector_type(8))) int frag_t;
+    frag_t qf[NQ];
+    float qdiv[NQ];                                // 2^e_i: the scores of row i are divided by it on conversion
+    const float km = kmax[bh];
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+        int row = q0 + qb * 16 + n16;
+        row = row < N ? row : N - 1;               // rows past the end are computed and dropped
+        const unsigned char* src = Qh + (size_t)row * D + 32 * g;
+        const i32x4 lo = *reinterpret_cast<const i32x4*>(src);
+        const i32x4 hi = *reinterpret_cast<const i32x4*>(src + 16);
+        qf[qb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        float qq = 0.f;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const float a = __builtin_amdgcn_cvt_f32_fp8(qf[qb][r], 0), b = __builtin_amdgcn_cvt_f32_fp8(qf[qb][r], 1);
+            const float c = __builtin_amdgcn_cvt_f32_fp8(qf[qb][r], 2), e = __builtin_amdgcn_cvt_f32_fp8(qf[qb][r], 3);
+            qq += a * a + b * b + c * c + e * e;
+        }
+        qq = sum_across_groups(qq);
+        const float bound = __builtin_sqrtf(qq) * km;   // >= |s_ij| for every key
+        int e = 0;
+        (void)__builtin_frexpf(bound * (1.0f / 440.f), &e);   // bound / 440 = m 2^e, m in [0.5, 1)
+        e = bound > 0.f ? min(max(e, -126), 127) : 0;
+        qdiv[qb] = __builtin_ldexpf(1.0f, e);
+    }
+
+    f32x4 oacc[SLOTS][NQ];
+#pragma unroll
+    for (int db = 0; db < SLOTS; ++db)
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) oacc[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const i32x4 krw = rsrc_words(K + (size_t)bh * N * D, (uint32_t)N * D);
+    const i32x4 vrw = rsrc_words(VT + (size_t)bh * D * Np, (uint32_t)(D * Np));
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    // copy c of this wave's share of tile `tile` into buffer `buf`: c < 4 K, else V^T.  K rows
+    // past the end of the head are out of the descriptor's range and arrive as zeros.
+    auto copy_chunk = [&](int c, int tile, SPH_LDS unsigned char* buf) {
+        const uint32_t base = (uint32_t)(uintptr_t)buf;
+        if (c < 4)
+            copy_to_lds(krw, base + (wave_u * 4 + c) * 1024, kld_lane, tile * KTILE + (c >> 1) * 4 * D + (c & 1) * 64);
+        else
+            copy_to_lds(vrw, base + KTILE + (wave_u * 4 + (c - 4)) * 1024, vld_lane,
+                        tile * BC + (int)(((c - 4) >> 1) * 16 * Np) + (c & 1) * 64);
+    };
+
+    // ---- prologue: buffer 3 plays the tiles before the first (zeros); tile 0 goes to buffer 0
+    // entirely and the first half of tile 1's copies to buffer 1
+    {
+        const i32x4 zero4 = {0, 0, 0, 0};
+        for (int i = tid; i < BUF_BYTES / 16; i += kThreads)
+            *reinterpret_cast<SPH_LDS i32x4*>(smem + (NBUF - 1) * BUF_BYTES + i * 16) = zero4;
+    }
+#pragma unroll
+    for (int c = 0; c < NCOPY; ++c) copy_chunk(c, 0, smem);
+#pragma unroll
+    for (int c = 0; c < 2 * PD; ++c) copy_chunk(c, 1, smem + BUF_BYTES);
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's copies have landed
+    __syncthreads();
+
+    auto mfma8 = [&](frag_t a, frag_t b, f32x4 c) -> f32x4 {
+        return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+    };
+    auto read_frag = [&](const SPH_LDS unsigned char* blk) -> frag_t {
+        const i32x4 lo = lds_read_b128(blk + flane), hi = lds_read_b128(blk + flane + 16);
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    // stage B on one block of scores: four of them rounded to E4M3 into one register of P; the
+    // sum of squares on the VALU (from the unrounded values) unless the matrix cores take it
+    // v_cvt_scalef32_pk_fp8_f32: two values divided by the power of two `div` and rounded to E4M3
+    // (nearest even) into one half of a register.  lo starts a register (no initial value
+    // needed: hi writes the other half), hi completes it.
+    typedef __attribute__((ext_vector_type(2))) short s16x2;
+    auto stage_b_lo = [&](f32x4 sc, float div) -> s16x2 {
+        s16x2 w;
+        asm volatile("" : "=v"(w));
+        return __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, sc[0], sc[1], div, false);
+    };
+    auto stage_b_hi = [&](s16x2 w, f32x4 sc, float div) -> int {
+        return __builtin_bit_cast(int, __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, sc[2], sc[3], div, true));
+    };
+    f32x4 zz[NQ];
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) zz[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // score block rows: SA is written in even slots and consumed in odd ones, SB the reverse
+    f32x4 SA[NQ], SB[NQ];
+    frag_t P0[NQ], P1[NQ];                         // P of even and of odd tiles
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+        SA[qb] = SB[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        P0[qb] = P1[qb] = frag_t{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+
+    // Fragment registers, as the two 16-byte halves that the LDS reads deliver.
+    i32x4 kfl[RING], kfh[RING], vfl[RING], vfh[RING];
+    auto whole = [](i32x4 lo, i32x4 hi) -> frag_t { return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7); };
+    // Read `part` (0, 1: K halves; 2, 3: V^T halves) for slot u, counted from the start of a tile
+    // T whose neighbours T-2 .. T+1 sit at bpp, bprv, bcur, bnxt:
+    //   K   fragment: block row u of tile T          (u >= 8: block row u-8 of tile T+1)
+    //   V^T fragment: u = 0: db 7 of tile T-2;  u in 1..7: db u-1 of tile T-1;
+    //                 u = 8: db 7 of tile T-1;  u > 8: db u-9 of tile T
+    auto read_part = [&](int u, int part, const SPH_LDS unsigned char* bpp, const SPH_LDS unsigned char* bprv,
+                         const SPH_LDS unsigned char* bcur, const SPH_LDS unsigned char* bnxt) {
+        const SPH_LDS unsigned char* vp = (u == 0 ? bpp : u <= 8 ? bprv : bcur) + KTILE + ((u + 7) % 8) * 2048 + flane;
+        const SPH_LDS unsigned char* kp = (u < 8 ? bcur : bnxt) + (u % 8) * 2048 + flane;
+        if (part == 0) kfl[u % RING] = lds_read_b128(kp);
+        else if (part == 1) kfh[u % RING] = lds_read_b128(kp + 16);
+        else if (part == 2) vfl[u % RING] = lds_read_b128(vp);
+        else vfh[u % RING] = lds_read_b128(vp + 16);
+    };
+
+    SPH_LDS unsigned char* bprv = smem + (NBUF - 1) * BUF_BYTES;
+    SPH_LDS unsigned char* bcur = smem;
+    SPH_LDS unsigned char* bnxt = smem + BUF_BYTES;
+    SPH_LDS unsigned char* bnn = smem + 2 * BUF_BYTES;
+#pragma unroll
+    for (int u = 0; u < PD; ++u)
+#pragma unroll
+        for (int part = 0; part < 4; ++part) read_part(u, part, bprv, bprv, bcur, bnxt);
+
+    // tiles are processed in pairs so that the P buffers alternate statically; a tile past the
+    // end has zero keys and adds nothing
+    const int n_pairs = (n_tiles + 1) / 2;
+    for (int jj = 0; jj < n_pairs; ++jj) {
+#pragma unroll
+        for (int s = 0; s < 2 * SLOTS; ++s) {
+            const int par = s / SLOTS, i = s % SLOTS;
+            const int tile = 2 * jj + par;
+            f32x4 (&Sn)[NQ] = i % 2 == 0 ? SA : SB;
+            f32x4 (&Sc)[NQ] = i % 2 == 0 ? SB : SA;
+            // stage B of slot 0 finishes the previous tile's P; stage C of slot 0 still uses
+            // the P of the tile before that, which lives in this tile's buffer
+            frag_t (&Pw)[NQ] = (i == 0) == (par == 0) ? P1 : P0;
+            frag_t (&Pr)[NQ] = (i == 0) == (par == 0) ? P0 : P1;
+            __builtin_amdgcn_sched_barrier(0);
+            // The one barrier per tile: tile T+1 becomes visible before its first read (the
+            // prefetch below).  Past it every wave has also finished slot 0 of this tile, the
+            // last reader of the buffer that the copies of tile T+2 overwrite.
+            if (i == SLOTS - PD) {
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
+            // Eight groups, one matrix instruction each, in exactly this order (the scheduler
+            // may not move anything across a group boundary): the matrix pipe never waits for
+            // the three or five VALU instructions and the one LDS read that follow it.
+            //   groups 0..3  A: block row i of this tile's scores, query block m
+            //   groups 4..7  C: V^T fragment (i+7)%8 of the previous tile (slot 0: of the one
+            //                   before), query block m - 4
+            //   every group  B: half a register of P from the block row finished in the
+            //                   previous slot (query block m / 2, values 2 (m % 2), + 1)
+            const frag_t kfr = whole(kfl[s % RING], kfh[s % RING]);
+            const frag_t vfr = whole(vfl[s % RING], vfh[s % RING]);
+            s16x2 wlo;
+#pragma unroll
+            for (int m = 0; m < 2 * NQ; ++m) {
+                if (m < NQ) {
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    Sn[m] = mfma8(kfr, qf[m], zero);
+                    read_part(i + PD, m, bnn, bprv, bcur, bnxt);
+                } else {
+                    oacc[(i + 7) % 8][m - NQ] = mfma8(vfr, Pr[m - NQ], oacc[(i + 7) % 8][m - NQ]);
+                }
+                const int qb = m / 2;
+                if (m % 2 == 0) wlo = stage_b_lo(Sc[qb], qdiv[qb]);
+                else Pw[qb][(i + 7) % 8] = stage_b_hi(wlo, Sc[qb], qdiv[qb]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // z of the previous tile as the diagonal of P^T P (P serves as A and as B operand:
+            // lane (n16, g) holds the k-slots 32g.. of row, or column, n16 either way)
+            if (i >= 1 && i <= NQ) zz[i - 1] = mfma8(Pr[i - 1], Pr[i - 1], zz[i - 1]);
+            // copies, two per slot: those of tile T+2 start behind the barrier and carry on in the
+            // first slots of the next tile (where the same tile is T+1)
+            if (i >= SLOTS - PD) {
+                copy_chunk(2 * (i - (SLOTS - PD)), tile + 2, bnn);
+                copy_chunk(2 * (i - (SLOTS - PD)) + 1, tile + 2, bnn);
+            }
+            if (i < NCOPY / 2 - PD) {
+                copy_chunk(2 * (i + PD), tile + 1, bnxt);
+                copy_chunk(2 * (i + PD) + 1, tile + 1, bnxt);
+            }
+            if (i == SLOTS - 1) {
+                SPH_LDS unsigned char* t = bprv; bprv = bcur; bcur = bnxt; bnxt = bnn; bnn = t;
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // copies past the end must not outlive the LDS
+
+    // ---- drain.  The last tile processed is an odd one (P1); its block row 7 sits in SB
+    // (written in slot 7), and V^T fragment 7 of the tile before it is still outstanding.
+    {
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) {
+            // bcur now is the tile after the last, bprv the last, and the one before it:
+            oacc[7][qb] = mfma8(whole(vfl[(2 * SLOTS) % RING], vfh[(2 * SLOTS) % RING]), P0[qb], oacc[7][qb]);
+        }
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb)
+            P1[qb][7] = stage_b_hi(stage_b_lo(SB[qb], qdiv[qb]), SB[qb], qdiv[qb]);
+        // the last tile's Gram product (the loop adds a tile's in the next tile's slots)
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) zz[qb] = mfma8(P1[qb], P1[qb], zz[qb]);
+#pragma unroll
+        for (int db = 0; db < SLOTS; ++db) {
+            const frag_t vfr = read_frag(bprv + KTILE + db * 2048);
+#pragma unroll
+            for (int qb = 0; qb < NQ; ++qb) oacc[db][qb] = mfma8(vfr, P1[qb], oacc[db][qb]);
+        }
+    }
+
+    // ---- tail: O_i = o_i / sqrt(z_i); the row factor cancels
+    unsigned short* Oh = O + (size_t)bh * N * D;
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+        // z_i: the diagonal element of query n16 (row 4g + t = n16) is held by lane group n16 / 4
+        // in register n16 % 4; the other three lanes of the query get it through the sum
+        const float dsel = (n16 & 3) == 0 ? zz[qb][0] : (n16 & 3) == 1 ? zz[qb][1] : (n16 & 3) == 2 ? zz[qb][2] : zz[qb][3];
+        const float z = sum_across_groups(g == (n16 >> 2) ? dsel : 0.f);
+        // o and z were both accumulated from the scores divided by 2^e_i: the factor cancels
+        const float inv = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
+        const int row = q0 + qb * 16 + n16;
+        if (row < N) {
+            unsigned short* dst = Oh + (size_t)row * D + 4 * g;
+#pragma unroll
+            for (int db = 0; db < SLOTS; ++db) {
+                const i32x2 o4 = {pack2<false>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
+                                  pack2<false>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
+                *reinterpret_cast<i32x2*>(dst + db * 16) = o4;
+            }
+        }
+    }
+}
+
+}  // namespace sphattn

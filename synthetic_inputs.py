@@ -32,7 +32,7 @@ class Workload:
     H: int
     N: int
     d: int
-    dtype: str          # "f32" | "bf16" | "f16" | "fp8qk_bf16v"
+    dtype: str          # "f32" | "bf16" | "f16" | "fp8qk_bf16v" | "fp8"
     factor: float = 1.0  # multiplies Q, K and V before the cast
 
     @property
@@ -89,6 +89,8 @@ def cast_storage(q, k, v, dtype: str):
         return q.to(torch.float16), k.to(torch.float16), v.to(torch.float16)
     if dtype == "fp8qk_bf16v":
         return to_e4m3fn(q), to_e4m3fn(k), v.to(torch.bfloat16)
+    if dtype == "fp8":
+        return to_e4m3fn(q), to_e4m3fn(k), to_e4m3fn(v)
     raise ValueError(f"unknown dtype {dtype!r}")
 
 

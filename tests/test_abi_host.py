@@ -206,11 +206,33 @@ def test_backward_argument_errors(lib):
     assert grn(Q=0) == -1
 
 
+def test_fp8_argument_errors_and_workspace_size(lib):
+    P = ctypes.c_void_p
+    wsb = lib.sphattn_fp8_workspace_bytes
+    # V^T padded to whole 128-key tiles (one byte per element) + one float per head, rounded up
+    assert wsb(2, 3, 300, 128) == 2 * 3 * 128 * 384 + 256
+    assert wsb(1, 1, 128, 128) == 128 * 128 + 256
+    assert wsb(1, 1, 128, 64) == 0 and wsb(0, 1, 128, 128) == 0 and wsb(1, 1, 0, 128) == 0
+    need = wsb(1, 2, 1000, 128)
+
+    def call(Q=0x1000000, K=0x2000000, V=0x3000000, O=0x4000000, ws=0x40000000, size=need, B=1, H=2, N=1000, d=128):
+        return lib.sphattn_fp8_fwd(P(Q), P(K), P(V), P(O), P(ws), size, B, H, N, d, None)
+    assert call(Q=0) == -1 and call(K=0) == -1 and call(V=0) == -1 and call(O=0) == -1
+    assert call(N=0) == -2 and call(H=0) == -2
+    assert call(d=64) == -3 and call(d=96) == -3           # d = 128 only
+    assert call(V=0x3000008) == -5
+    assert call(O=0x1000000) == -7                         # O is Q
+    assert call(O=0x3000000 - 256) == -7                   # O runs into V
+    assert call(ws=0) == -9 and call(ws=0x40000004) == -9 and call(size=need - 1) == -9
+    assert call(ws=0x2000000) == -7                        # workspace is K
+    assert call(ws=0x4000000 + 4096) == -7                 # workspace inside O
+
+
 def test_mfma_probe_argument_errors(lib):
     P = ctypes.c_void_p
     assert lib.sphattn_mfma_probe(P(0), P(0x2000), 0, 10, None) == -1
     assert lib.sphattn_mfma_probe(P(0x1000), P(0), 0, 10, None) == -1
-    assert lib.sphattn_mfma_probe(P(0x1000), P(0x2000), 2, 10, None) == -2
+    assert lib.sphattn_mfma_probe(P(0x1000), P(0x2000), 3, 10, None) == -2
     assert lib.sphattn_mfma_probe(P(0x1000), P(0x2000), 0, 0, None) == -2
     assert lib.sphattn_mfma_probe(P(0x1008), P(0x2000), 0, 10, None) == -5
     assert lib.sphattn_mfma_probe(P(0x1000), P(0x2004), 0, 10, None) == -5
