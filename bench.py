@@ -89,6 +89,9 @@ def main() -> int:
     ap.add_argument("--no-mfma-ceiling", action="store_true",
                     help="skip the loops of nothing but bf16 matrix instructions on Gaussian operands (the "
                          "rate the matrix pipes sustain at the power limit, reported next to the kernel's)")
+    ap.add_argument("--fp8-all", action="store_true",
+                    help="also time the all-E4M3 forward (sphattn_fp8_fwd: V and the scores in E4M3, too) on "
+                         "the workload's shape (d = 128 only)")
     ap.add_argument("--bwd", action="store_true", help="also time the backward pass (sphattn_bwd) on the workload")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run a plain 256 MiB device copy (untimed), as the known-size "
@@ -214,8 +217,13 @@ def main() -> int:
         ops = torch.randn(32768, generator=g, dtype=torch.float32).to(torch.bfloat16).to(dev)
         clk = torch.zeros(3, dtype=torch.int64, device=dev)
         ceil = {}
-        for form, name in ((0, "32x32x16_bf16"), (1, "16x16x32_bf16")):
+        ops8 = si.to_e4m3fn(torch.randn(65536, generator=g, dtype=torch.float32)).view(torch.uint8).to(dev)
+        for form, name in ((0, "32x32x16_bf16"), (1, "16x16x32_bf16"), (2, "16x16x128_e4m3")):
             iters = 100000
+            if form == 2:
+                if not args.fp8_all:
+                    continue
+                ops = ops8
             for _ in range(2):
                 flop = pkg.sphattn_mfma_probe(ops, clk, form, iters)
             torch.cuda.synchronize()
@@ -228,6 +236,26 @@ def main() -> int:
             ceil[name] = {"tflops": flop / (e0.elapsed_time(e1) * 1e-3) / 1e12, "shader_ghz": 0.1 * c[0] / max(c[1], 1)}
         result["mfma_only_ceiling_gaussian_operands"] = ceil
         result["roofline"]["frac_of_mfma_only_ceiling"] = kern_tflops / ceil["16x16x32_bf16"]["tflops"]
+
+    if args.fp8_all:
+        if w.d != 128:
+            print("--fp8-all needs d = 128", file=sys.stderr)
+            return 2
+        q8, k8, v8 = (si.to_e4m3fn(t.to(torch.float32)).to(dev) if t.dtype != torch.float8_e4m3fn else t.to(dev)
+                      for t in (q, k, v))
+        ws8 = torch.empty(pkg.sphattn_fp8_workspace_bytes(w.B, w.H, w.N, w.d), dtype=torch.uint8, device=dev)
+        out8 = torch.empty((w.B, w.H, w.N, w.d), dtype=torch.bfloat16, device=dev)
+        _, per_8 = time_launches(lambda: pkg.sphattn_fp8_fwd(q8, k8, v8, ws8, O=out8),
+                                 max(10, args.steps // 4), max(5, args.warmup // 4))
+        ms_8 = sum(per_8) / len(per_8)
+        tf8 = w.flops / (ms_8 * 1e-3) / 1e12
+        result["fp8_all_variant"] = {
+            "storage": "Q, K, V E4M3; scores rounded to E4M3; O bf16", "launches": 3,
+            "ms_avg": ms_8, "tflops": tf8, "frac_of_fp8_mfma_peak": tf8 / 5000.0,
+            "workspace_bytes": ws8.numel(), "speedup_over_headline_kernel": ms_kernel / ms_8,
+        }
+        if not args.no_mfma_ceiling:
+            result["fp8_all_variant"]["frac_of_mfma_only_ceiling"] = tf8 / ceil["16x16x128_e4m3"]["tflops"]
 
     if args.bwd:
         if w.dtype not in ("bf16", "f16"):

@@ -25,13 +25,16 @@
 // Matrix-core mapping.  With k = 128 both contractions have the same shape,
 //     S^T block kb (16 keys x 16 queries) = K frag (A: 16 keys x 128 of d) * Q frag (B: 128 x 16 queries)
 //     O^T block db (16 cols of d x 16 queries) += V^T frag (A: 16 cols x 128 keys) * P (B: 128 keys x 16)
-// and lane (n16, g) of an A or B operand holds 32 consecutive k-slots 32g .. 32g+31 of row or
-// column n16.  In the accumulator lane (n16, g) holds query n16 and, in register t, row 4g + t
-// of the block.  The 16 rows of score block kb are therefore chosen to be the keys
-//     key(kb, p) = 32 (p / 4) + 4 kb + (p % 4),    p = 0..15,
-// of the 128-key tile: then register t of block kb in lane group g is key 32g + 4kb + t, and
-// the eight blocks' scores, packed four to a register, are exactly the 32 consecutive
-// k-slots that the second contraction wants from this lane.  Like the 16-bit kernels, the
+// and lane (n16, g) of an A or B operand holds 32 of the 128 k-slots of row or column n16.
+// Which 32 is free as long as A and B agree; here group g takes bytes 16g .. 16g+15 and
+// 64+16g .. 64+16g+15 of the 128-byte row (every LDS read then takes one 16-byte piece from
+// each row of a 1 KB block, which the banks serve at full rate).  In the accumulator lane
+// (n16, g) holds query n16 and, in register t, row 4g + t of the block.  The 16 rows of score
+// block kb are therefore chosen to be the keys
+//     key(kb, p) = 64 (kb / 4) + 16 (p / 4) + 4 (kb % 4) + (p % 4),    p = 0..15,
+// of the 128-key tile: then register t of block kb in lane group g is key
+// 64 (kb/4) + 16g + 4 (kb%4) + t, and the eight blocks' scores, packed four to a register, are
+// exactly the k-slots that the second contraction wants from this lane.  Like the 16-bit kernels, the
 // scores never leave their registers.  V is needed as V^T with keys along the contiguous axis;
 // the preparation pass writes that copy once (2 N d bytes of traffic per head against
 // 4 N^2 d flop), so both operand streams are read from LDS with plain 16-byte reads and there
@@ -159,15 +162,18 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     const unsigned char* Qh = Q + (size_t)bh * N * D;
     const int q0 = qt * BR + wave * 16 * NQ;
 
-    // LDS image of a tile: K blocks (kb, c) and V^T blocks (db, c), 16 rows x 64 bytes each,
-    // row-major, 1 KB, block (r, c) at (2r + c) KB; a fragment read (row n16, bytes 32g..32g+31)
-    // is linear in the lane id within its block: no padding, no bank conflicts.
-    const int flane = (g >> 1) * 1024 + n16 * 64 + (g & 1) * 32;
-    // copies: block 4 wave + c; lane l fills row l/4, bytes 16 (l%4) of the block's 64
-    //   K   block (kb, half): tile row key(kb, l/4), bytes 64 half + 16 (l%4) of the key row
-    //   V^T block (db, half): row 16db + l/4 of V^T, keys 64 half + 16 (l%4) of the tile
+    // LDS image of a tile: K blocks (kb, h) and V^T blocks (db, h), 16 rows x 64 bytes each
+    // (half h of the 128-byte rows), row-major, 1 KB, block (r, h) at (2r + h) KB.  The 32
+    // k-slots of lane group g are the bytes 16g .. 16g+15 of both halves of the row (see the
+    // key order above), so each of a fragment's two 16-byte reads takes one piece from every row
+    // of one block: the 64 lanes cover the block's 1 KB exactly once.
+    const int flane = n16 * 64 + g * 16;
+    constexpr int HALF1 = 1024;                    // second half of the rows: the next block
+    // copies: block 4 wave + c = (r = 2 wave + c/2, h = c%2); lane l fills row l/4, bytes 16 (l%4)
+    //   K   block (kb, h): tile row key(kb, l/4), bytes 64 h + 16 (l%4) of the key row
+    //   V^T block (db, h): row 16db + l/4 of V^T, keys 64 h + 16 (l%4) of the tile
     const int p = lane >> 2;
-    const int kld_lane = (32 * (p >> 2) + (p & 3) + 8 * wave) * D + (lane & 3) * 16;
+    const int kld_lane = (16 * (p >> 2) + (p & 3) + 64 * (wave >> 1) + 8 * (wave & 1)) * D + (lane & 3) * 16;
     const int vld_lane = (int)((32 * wave + p) * Np) + (lane & 3) * 16;
 
     // ---- Q fragments and the row factors a_i
@@ -179,9 +185,9 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     for (int qb = 0; qb < NQ; ++qb) {
         int row = q0 + qb * 16 + n16;
         row = row < N ? row : N - 1;               // rows past the end are computed and dropped
-        const unsigned char* src = Qh + (size_t)row * D + 32 * g;
+        const unsigned char* src = Qh + (size_t)row * D + 16 * g;
         const i32x4 lo = *reinterpret_cast<const i32x4*>(src);
-        const i32x4 hi = *reinterpret_cast<const i32x4*>(src + 16);
+        const i32x4 hi = *reinterpret_cast<const i32x4*>(src + 64);
         qf[qb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         float qq = 0.f;
 #pragma unroll
@@ -236,7 +242,7 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
         return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
     };
     auto read_frag = [&](const SPH_LDS unsigned char* blk) -> frag_t {
-        const i32x4 lo = lds_read_b128(blk + flane), hi = lds_read_b128(blk + flane + 16);
+        const i32x4 lo = lds_read_b128(blk + flane), hi = lds_read_b128(blk + flane + HALF1);
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
@@ -280,9 +286,9 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
         const SPH_LDS unsigned char* vp = (u == 0 ? bpp : u <= 8 ? bprv : bcur) + KTILE + ((u + 7) % 8) * 2048 + flane;
         const SPH_LDS unsigned char* kp = (u < 8 ? bcur : bnxt) + (u % 8) * 2048 + flane;
         if (part == 0) kfl[u % RING] = lds_read_b128(kp);
-        else if (part == 1) kfh[u % RING] = lds_read_b128(kp + 16);
+        else if (part == 1) kfh[u % RING] = lds_read_b128(kp + HALF1);
         else if (part == 2) vfl[u % RING] = lds_read_b128(vp);
-        else vfh[u % RING] = lds_read_b128(vp + 16);
+        else vfh[u % RING] = lds_read_b128(vp + HALF1);
     };
 
     SPH_LDS unsigned char* bprv = smem + (NBUF - 1) * BUF_BYTES;
