@@ -43,7 +43,7 @@ enum {
     SPHATTN_OK = 0,
     SPHATTN_ERR_NULL = -1,        /* a required pointer is NULL */
     SPHATTN_ERR_SHAPE = -2,       /* B, H, N (or H_kv) not positive, H_kv not dividing H, or sizes overflow */
-    SPHATTN_ERR_HEAD_DIM = -3,    /* d is not 64 or 128 */
+    SPHATTN_ERR_HEAD_DIM = -3,    /* d is not 64 or 128 (sphattn_fp8_fwd: not 128) */
     SPHATTN_ERR_DTYPE = -4,       /* dtype is not a sphattn_dtype value */
     SPHATTN_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned */
     SPHATTN_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch */

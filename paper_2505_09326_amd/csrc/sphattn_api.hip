@@ -545,13 +545,13 @@ const char* sphattn_strerror(int code)
     case SPHATTN_OK: return "success";
     case SPHATTN_ERR_NULL: return "a required pointer is NULL";
     case SPHATTN_ERR_SHAPE: return "B, H, N must be positive, H_kv must divide H, and sizes must not overflow";
-    case SPHATTN_ERR_HEAD_DIM: return "head dimension d must be 64 or 128";
+    case SPHATTN_ERR_HEAD_DIM: return "head dimension d must be 64 or 128 (128 for the all-E4M3 forward)";
     case SPHATTN_ERR_DTYPE: return "unsupported dtype for this entry point";
     case SPHATTN_ERR_ALIGN: return "Q, K, V and O must be 16-byte aligned";
     case SPHATTN_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
     case SPHATTN_ERR_ALIAS: return "O must not overlap Q, K or V";
     case SPHATTN_ERR_NORMALIZER: return "normalizer is not a sphattn_normalizer value";
-    case SPHATTN_ERR_WORKSPACE: return "workspace is NULL, misaligned or smaller than sphattn_splitkv_workspace_bytes";
+    case SPHATTN_ERR_WORKSPACE: return "workspace is NULL, misaligned or smaller than the entry point's *_workspace_bytes";
     default: return "unknown sphattn error code";
     }
 }
