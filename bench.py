@@ -218,9 +218,10 @@ def main() -> int:
         clk = torch.zeros(3, dtype=torch.int64, device=dev)
         ceil = {}
         ops8 = si.to_e4m3fn(torch.randn(65536, generator=g, dtype=torch.float32)).view(torch.uint8).to(dev)
-        for form, name in ((0, "32x32x16_bf16"), (1, "16x16x32_bf16"), (2, "16x16x128_e4m3")):
+        for form, name in ((0, "32x32x16_bf16"), (1, "16x16x32_bf16"), (2, "16x16x128_e4m3"),
+                           (3, "16x16x128_e4m3_with_l2_stage_b_mix"), (4, "16x16x128_e4m3_with_softmax_stage_b_mix")):
             iters = 100000
-            if form == 2:
+            if form >= 2:
                 if not args.fp8_all:
                     continue
                 ops = ops8
@@ -256,6 +257,12 @@ def main() -> int:
         }
         if not args.no_mfma_ceiling:
             result["fp8_all_variant"]["frac_of_mfma_only_ceiling"] = tf8 / ceil["16x16x128_e4m3"]["tflops"]
+            # what the exponential costs at the fp8 matrix rate (paper, Section 1): the same loop
+            # of matrix instructions with an L2 kernel's, or a SoftMax kernel's, other per-score
+            # instructions pinned behind each of them
+            result["fp8_all_variant"]["l2_over_softmax_instruction_mix"] = (
+                ceil["16x16x128_e4m3_with_l2_stage_b_mix"]["tflops"]
+                / ceil["16x16x128_e4m3_with_softmax_stage_b_mix"]["tflops"])
 
     if args.bwd:
         if w.dtype not in ("bf16", "f16"):

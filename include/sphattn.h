@@ -270,12 +270,18 @@ int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O,
  * sustain on given operand values next to the attention kernels (on random data the part is
  * power-bound well below its nominal peak).
  *   operands : 64 KB of device memory, 16-byte aligned, read as operand values (bfloat16 for
- *              forms 0 and 1, E4M3 bytes for form 2).
+ *              forms 0 and 1, E4M3 bytes for forms 2 to 4).
  *   clocks   : 3 int64 on the device, 8-byte aligned; receives {shader clocks, 100 MHz reference
  *              ticks} spent in the loop by workgroup 0 (the third is scratch).
  *   form     : 0 = v_mfma_f32_32x32x16_bf16 (16 per iteration), 1 = v_mfma_f32_16x16x32_bf16 (32 per
  *              iteration), 2 = v_mfma_f32_16x16x128_f8f6f4 on E4M3 (8 per iteration); in every
- *              form 256 * 4 waves * iters * 16 * 32768 flop per launch.
+ *              form 256 * 4 waves * iters * 16 * 32768 flop per launch.  Forms 3 and 4 are form 2
+ *              with, pinned behind every matrix instruction, the other instructions that one wave
+ *              of an all-E4M3 attention kernel issues per matrix instruction: a 16-byte LDS read
+ *              and, 3: one scaled convert and two register moves (L2 normaliser); 4: scale-and-
+ *              shift, exponential, running max and sum for two scores and one convert (SoftMax,
+ *              without its cross-lane maximum and rescaling).  Their ratio is what the
+ *              exponential costs at the fp8 matrix rate (paper, Section 1).
  *   iters    : 1 .. 2^24.
  * Errors: SPHATTN_ERR_NULL, SPHATTN_ERR_SHAPE (form, iters), SPHATTN_ERR_ALIGN, SPHATTN_ERR_LAUNCH.
  */

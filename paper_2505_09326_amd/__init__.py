@@ -338,7 +338,8 @@ def sphattn_grn_bwd(Q, K, V, mult, O, dO, Z, dQ=None, dK=None, dV=None, delta=No
 
 def sphattn_mfma_probe(operands, clocks, form: int, iters: int, stream=None):
     """Measurement aid: one launch of a loop of matrix instructions only (form 0: bf16 32x32x16,
-    1: bf16 16x16x32, 2: E4M3 16x16x128) on `operands` (64 KB device tensor); `clocks` (3 int64 on the device) receives
+    1: bf16 16x16x32, 2: E4M3 16x16x128; 3, 4: form 2 with an L2 / a SoftMax kernel's other
+    instructions pinned behind every matrix instruction) on `operands` (64 KB device tensor); `clocks` (3 int64 on the device) receives
     shader clocks and 100 MHz ticks of workgroup 0.  Returns the flop count of the launch."""
     lib = load_library()
     _check_device("operands, clocks", operands, clocks)

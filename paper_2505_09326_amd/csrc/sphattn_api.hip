@@ -525,7 +525,7 @@ int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O, void* 
 int sphattn_mfma_probe(const void* operands, long long* clocks, int form, int iters, void* stream)
 {
     if (!operands || !clocks) return SPHATTN_ERR_NULL;
-    if (iters <= 0 || iters > (1 << 24) || form < 0 || form > 2) return SPHATTN_ERR_SHAPE;
+    if (iters <= 0 || iters > (1 << 24) || form < 0 || form > 4) return SPHATTN_ERR_SHAPE;
     if (((uintptr_t)operands & 15) || ((uintptr_t)clocks & 7)) return SPHATTN_ERR_ALIGN;
     if (form == 0)
         hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(256), dim3(256), 0, (hipStream_t)stream,
@@ -533,8 +533,14 @@ int sphattn_mfma_probe(const void* operands, long long* clocks, int form, int it
     else if (form == 1)
         hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(256), dim3(256), 0, (hipStream_t)stream,
                            (const i32x4*)operands, clocks, iters);
-    else
+    else if (form == 2)
         hipLaunchKernelGGL(mfma_probe_kernel<2>, dim3(256), dim3(256), 0, (hipStream_t)stream,
+                           (const i32x4*)operands, clocks, iters);
+    else if (form == 3)
+        hipLaunchKernelGGL(mfma_probe_kernel<3>, dim3(256), dim3(256), 0, (hipStream_t)stream,
+                           (const i32x4*)operands, clocks, iters);
+    else
+        hipLaunchKernelGGL(mfma_probe_kernel<4>, dim3(256), dim3(256), 0, (hipStream_t)stream,
                            (const i32x4*)operands, clocks, iters);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }

@@ -350,6 +350,20 @@ void mfma_probe_kernel(const i32x4* __restrict__ operands, long long* __restrict
         for (int e = 0; e < 16; ++e) c32[i][e] = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) c16[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // forms 3, 4: state of the instructions pinned behind the matrix instructions
+    __shared__ __attribute__((aligned(16))) unsigned char mix_lds[FORM >= 3 ? 16384 : 16];
+    i32x4 mix_ld = {0, 0, 0, 0};
+    float mix_x0 = 0.25f, mix_x1 = 0.5f, mix_e0 = 0.f, mix_e1 = 0.f, mix_m = 0.f, mix_s = 0.f;
+    const float mix_c = 1.0f;
+    int mix_w = 0;
+    uint32_t mix_addr = 0;
+    if constexpr (FORM >= 3) {
+        for (int i = threadIdx.x; i < 1024; i += 256)
+            reinterpret_cast<i32x4*>(mix_lds)[i] = i32x4{0, 0, 0, 0};
+        __syncthreads();
+        const int l = threadIdx.x & 63;            // rows of 64 bytes, as the kernels' fragment reads
+        mix_addr = (uint32_t)(uintptr_t)(SPH_LDS unsigned char*)mix_lds + (l & 15) * 64 + (l >> 4) * 16;
+    }
     const long long t0 = clock64(), w0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
         if constexpr (FORM == 0) {
@@ -362,13 +376,39 @@ void mfma_probe_kernel(const i32x4* __restrict__ operands, long long* __restrict
                 c16[i % 16] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                     __builtin_bit_cast(bf16x8, a[i % NP]), __builtin_bit_cast(bf16x8, b[(i + i / NP) % NP]), c16[i % 16], 0, 0, 0);
         } else {
-            // E4M3 operands, k = 128: 8 instructions carry the flops of 16 of the bf16 forms
+            // E4M3 operands, k = 128: 8 instructions carry the flops of 16 of the bf16 forms.
+            // Forms 3 and 4 put, behind every matrix instruction and pinned there, what one
+            // wave has to issue per matrix instruction in an attention kernel whose scores go
+            // back to the matrix cores as E4M3: one 16-byte LDS read and
+            //   form 3 (L2 normaliser): one scaled convert and two register moves;
+            //   form 4 (SoftMax): scale-and-shift, exponential, running max and running sum
+            //                     for two scores, and one convert
+            // -- without the cross-lane maximum and the rescaling that a real SoftMax adds.
             typedef __attribute__((ext_vector_type(8))) int i32x8;
 #pragma unroll
             for (int i = 0; i < NP / 2; ++i) {
                 const i32x8 a8 = __builtin_shufflevector(a[2 * i], a[2 * i + 1], 0, 1, 2, 3, 4, 5, 6, 7);
                 const i32x8 b8 = __builtin_shufflevector(b[2 * i], b[2 * i + 1], 0, 1, 2, 3, 4, 5, 6, 7);
                 c16[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, c16[i], 0, 0, 0, 0, 0, 0);
+                if constexpr (FORM >= 3) {
+                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(mix_ld) : "v"(mix_addr), "n"(i * 2048));
+                    if constexpr (FORM == 4) {
+                        asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(mix_e0) : "v"(mix_x0), "v"(mix_c), "v"(mix_x1));
+                        asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(mix_e1) : "v"(mix_x1), "v"(mix_c), "v"(mix_x0));
+                        asm volatile("v_exp_f32 %0, %1" : "=v"(mix_x0) : "v"(mix_e0));
+                        asm volatile("v_exp_f32 %0, %1" : "=v"(mix_x1) : "v"(mix_e1));
+                        asm volatile("v_max_f32 %0, %1, %2" : "=v"(mix_m) : "v"(mix_e0), "v"(mix_m));
+                        asm volatile("v_add_f32 %0, %1, %2" : "=v"(mix_s) : "v"(mix_x0), "v"(mix_s));
+                    } else {
+                        asm volatile("v_mov_b32 %0, %1" : "=v"(mix_e0) : "v"(mix_w));
+                        asm volatile("v_mov_b32 %0, %1" : "=v"(mix_e1) : "v"(mix_e0));
+                    }
+                    asm volatile("v_cvt_scalef32_pk_fp8_f32 %0, %1, %2, %3" : "+v"(mix_w) : "v"(mix_x0), "v"(mix_x1), "v"(mix_c));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if constexpr (FORM >= 3) {
+                if ((it & 3) == 3) asm volatile("s_waitcnt lgkmcnt(0)");
             }
         }
         if ((it & 63) == 63) {                     // keep the sums finite
@@ -378,8 +418,9 @@ void mfma_probe_kernel(const i32x4* __restrict__ operands, long long* __restrict
             for (int i = 0; i < 16; ++i) c16[i] *= 0.001f;
         }
     }
+    if constexpr (FORM >= 3) asm volatile("s_waitcnt lgkmcnt(0)");
     const long long t1 = clock64(), w1 = wall_clock64();
-    float sum = 0.f;
+    float sum = (float)mix_ld[0] + mix_x0 + mix_x1 + mix_e0 + mix_e1 + mix_m + mix_s + (float)mix_w;
 #pragma unroll
     for (int i = 0; i < 4; ++i) sum += c32[i][0] + c32[i][7];
 #pragma unroll

@@ -232,7 +232,7 @@ def test_mfma_probe_argument_errors(lib):
     P = ctypes.c_void_p
     assert lib.sphattn_mfma_probe(P(0), P(0x2000), 0, 10, None) == -1
     assert lib.sphattn_mfma_probe(P(0x1000), P(0), 0, 10, None) == -1
-    assert lib.sphattn_mfma_probe(P(0x1000), P(0x2000), 3, 10, None) == -2
+    assert lib.sphattn_mfma_probe(P(0x1000), P(0x2000), 5, 10, None) == -2
     assert lib.sphattn_mfma_probe(P(0x1000), P(0x2000), 0, 0, None) == -2
     assert lib.sphattn_mfma_probe(P(0x1008), P(0x2000), 0, 10, None) == -5
     assert lib.sphattn_mfma_probe(P(0x1000), P(0x2004), 0, 10, None) == -5
