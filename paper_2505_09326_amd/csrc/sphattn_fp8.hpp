@@ -64,7 +64,9 @@ __global__ __launch_bounds__(256)
 void fp8_prepare_kernel(const unsigned char* __restrict__ K, const unsigned char* __restrict__ V,
                         unsigned char* __restrict__ VT, float* __restrict__ kmax, int N, int n_tiles)
 {
-    constexpr int D = kFp8D, T = kFp8Tile, LROW = D + 16;
+    // rows of 132 bytes: the 16 rows that one output piece gathers from then start 8 banks apart
+    // (with a 16-byte-aligned stride they would all start in the same bank)
+    constexpr int D = kFp8D, T = kFp8Tile, LROW = D + 4;
     __shared__ __attribute__((aligned(16))) unsigned char tile[T * LROW];
     __shared__ float wmax[4];
     const int tid = threadIdx.x;
@@ -78,7 +80,8 @@ void fp8_prepare_kernel(const unsigned char* __restrict__ K, const unsigned char
         const int row = id / (D / 16), c16 = id % (D / 16);
         i32x4 v = {0, 0, 0, 0};
         if (key0 + row < N) v = *reinterpret_cast<const i32x4*>(Vh + (size_t)(key0 + row) * D + 16 * c16);
-        *reinterpret_cast<i32x4*>(tile + row * LROW + 16 * c16) = v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) *reinterpret_cast<int*>(tile + row * LROW + 16 * c16 + 4 * r) = v[r];
     }
     // |k_j|^2 of row tid/2, half tid%2
     float ss = 0.f;
