@@ -384,3 +384,22 @@ def test_one_long_head(pkg, oracle):
     ref = oracle.spherical_attention_rows(*bits, 0, rows, kinds)
     assert np.abs(got[0, 0, rows] - ref).max() / np.sqrt((ref ** 2).mean()) <= TOL["bf16"]
     assert _rel_err(got, _gram_reference(q, k, v)) <= TOL["bf16"]
+
+
+def test_very_long_head(pkg, oracle):
+    """N = 1 000 003 (ragged), d = 128: 256 MB per tensor, buffer offsets up to 2^28 bytes, 15 626
+    key tiles per workgroup.  Sampled rows against the oracle plus the Gram closed form on the
+    whole tensor."""
+    B, H, N, d = 1, 1, 1000003, 128
+    print(f"case very long head N={N}", flush=True)
+    q, k, v = si.make_qkv(B, H, N, d, "bf16", seed=41)
+    got = _gpu(pkg, q, k, v, "bf16").to(torch.float64).numpy()
+    assert np.all(np.isfinite(got))
+    bits, kinds = _kinds(q, k, v)
+    rows = np.sort(np.random.default_rng(42).choice(N, size=48, replace=False)).astype(np.int32)
+    rows[0], rows[1], rows[-2], rows[-1] = 0, 255, N - 2, N - 1
+    ref = oracle.spherical_attention_rows(*bits, 0, rows, kinds)
+    err = np.abs(got[0, 0, rows] - ref).max() / np.sqrt((ref ** 2).mean())
+    print(f"very long head sampled rows max|err|/rms={err:.3e}", flush=True)
+    assert err <= TOL["bf16"]
+    assert _rel_err(got, _gram_reference(q, k, v)) <= TOL["bf16"]
