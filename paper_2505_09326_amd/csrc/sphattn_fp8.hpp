@@ -42,8 +42,8 @@
 //
 // Pipeline.  A slot = one score block row kb of the current tile (4 matrix instructions, one
 // per query block) + one V^T fragment db of the previous tile (4 more) + the conversion of the
-// block row finished in the slot before (two score registers read back and one convert
-// instruction behind every matrix instruction).  P is complete one slot into the next tile,
+// block row finished in the slot before (one convert instruction and at most one LDS read
+// behind every matrix instruction, in a fixed order).  P is complete one slot into the next tile,
 // so the second contraction of tile T runs in slots 1..7 of tile T+1 and slot 0 of tile T+2.
 // Tiles of 128 keys rotate through four 32 KB LDS buffers, filled straight from HBM/L2
 // (buffer_load ... lds), with one workgroup barrier per tile.
@@ -228,7 +228,7 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     };
 
     // ---- prologue: buffer 3 plays the tiles before the first (zeros); tile 0 goes to buffer 0
-    // entirely and the first half of tile 1's copies to buffer 1
+    // entirely, and of tile 1 the copies that the loop would have issued before its first slot
     {
         const i32x4 zero4 = {0, 0, 0, 0};
         for (int i = tid; i < BUF_BYTES / 16; i += kThreads)
@@ -249,8 +249,7 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
-    // stage B on one block of scores: four of them rounded to E4M3 into one register of P; the
-    // sum of squares on the VALU (from the unrounded values) unless the matrix cores take it
+    // stage B on one block of scores: four of them rounded to E4M3 into one register of P.
     // v_cvt_scalef32_pk_fp8_f32: two values divided by the power of two `div` and rounded to E4M3
     // (nearest even) into one half of a register.  lo starts a register (no initial value
     // needed: hi writes the other half), hi completes it.
