@@ -144,48 +144,67 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
         copy_tile(j + 1, lds0 + BUF_BYTES - cur);
         const SPH_LDS unsigned char* kb_ = smem + cur;
         const SPH_LDS unsigned char* vb_ = smem + cur + VLDS;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            i32x4 dsp[NQ];                         // dS^T of 32 keys as B operands
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const int rb = 2 * sub + kb;
-                f32x4 s[NQ], gg[NQ];
-#pragma unroll
-                for (int qb = 0; qb < NQ; ++qb) { s[qb] = f32x4{0, 0, 0, 0}; gg[qb] = f32x4{0, 0, 0, 0}; }
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk) {
-                    const i32x4 ka = lds_read_b128(kb_ + (rb * KBLK + kk) * 1024 + alane);
-                    const i32x4 va = lds_read_b128(vb_ + (rb * KBLK + kk) * 1024 + alane);
-#pragma unroll
-                    for (int qb = 0; qb < NQ; ++qb) {
-                        s[qb] = mfma16x16<HALF>(ka, qf[qb][kk], s[qb]);
-                        gg[qb] = mfma16x16<HALF>(va, gf[qb][kk], gg[qb]);
-                    }
-                }
-                // multipliers of the lane's keys 16rb + 4g + t: on the score, and again on ds
-                f32x4 mk = {1.f, 1.f, 1.f, 1.f};
-                if constexpr (MULT)
-                    mk = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + MLDS + (16 * rb + 4 * g) * 4));
-#pragma unroll
-                for (int qb = 0; qb < NQ; ++qb) {
-                    f32x4 ds;
-                    if constexpr (MULT) ds = (gg[qb] * c1[qb] - (s[qb] * mk) * c2[qb]) * mk;
-                    else ds = gg[qb] * c1[qb] - s[qb] * c2[qb];
-                    dsp[qb][2 * kb] = pack2<HALF>(ds[0], ds[1]);
-                    dsp[qb][2 * kb + 1] = pack2<HALF>(ds[2], ds[3]);
-                }
-            }
-            // dQ^T[db][qb] += K^T (16 columns of d x 32 keys) dS^T
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
+        // The tile is worked off in a fixed sequence of steps, each with its own fragments:
+        //   per 32-key sub-step: 2 KK score steps (key block kb, k-step kk: a K and a V fragment,
+        //   8 matrix instructions) and then DB output steps (a K^T fragment, 4 matrix instructions).
+        // The fragments of step st+1 are read from LDS before the matrix instructions of step st
+        // are issued, and the VALU work on a key block's scores is issued behind the first
+        // matrix instructions of the following step, so that neither the LDS latency nor the
+        // matrix pipeline's is waited for in the open.
+        constexpr int QG = 2 * KK, PER_SUB = QG + DB, STEPS = 2 * PER_SUB;
+        i32x4 fa[2], fb[2];
+        auto load_step = [&](int st) {
+            const int sub = st / PER_SUB, u = st % PER_SUB;
+            if (u < QG) {
+                const int rb = 2 * sub + u / KK, kk = u % KK;
+                fa[st & 1] = lds_read_b128(kb_ + (rb * KBLK + kk) * 1024 + alane);
+                fb[st & 1] = lds_read_b128(vb_ + (rb * KBLK + kk) * 1024 + alane);
+            } else {
+                const int db = u - QG;
                 const SPH_LDS unsigned char* a = kb_ + (2 * sub * KBLK + db / 2) * 1024 + (db & 1) * 32 + tlane;
                 const i32x2 lo = lds_read_tr64(a);
                 const i32x2 hi = lds_read_tr64(a + KBLK * 1024);
-                const i32x4 kt = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
-#pragma unroll
-                for (int qb = 0; qb < NQ; ++qb) dq[db][qb] = mfma16x16<HALF>(kt, dsp[qb], dq[db][qb]);
+                fa[st & 1] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
             }
+        };
+        f32x4 sc[2][NQ], gg[2][NQ];                // scores and dO V^T of key block kb
+        i32x4 dsp[NQ];                             // dS^T of 32 keys as B operands
+        // ds of key block kb of sub-step sub: registers 2kb, 2kb+1 of dsp
+        auto finish_block = [&](int sub, int kb) {
+            const int rb = 2 * sub + kb;
+            f32x4 mk = {1.f, 1.f, 1.f, 1.f};       // multipliers of the lane's keys 16rb + 4g + t
+            if constexpr (MULT)
+                mk = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + MLDS + (16 * rb + 4 * g) * 4));
+#pragma unroll
+            for (int qb = 0; qb < NQ; ++qb) {
+                f32x4 ds;
+                if constexpr (MULT) ds = (gg[kb][qb] * c1[qb] - (sc[kb][qb] * mk) * c2[qb]) * mk;
+                else ds = gg[kb][qb] * c1[qb] - sc[kb][qb] * c2[qb];
+                dsp[qb][2 * kb] = pack2<HALF>(ds[0], ds[1]);
+                dsp[qb][2 * kb + 1] = pack2<HALF>(ds[2], ds[3]);
+            }
+        };
+        load_step(0);
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+            const int sub = st / PER_SUB, u = st % PER_SUB;
+            if (st + 1 < STEPS) load_step(st + 1);
+            if (u < QG) {
+                const int kb = u / KK, kk = u % KK;
+                const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int qb = 0; qb < NQ; ++qb) {
+                    sc[kb][qb] = mfma16x16<HALF>(fa[st & 1], qf[qb][kk], kk == 0 ? zero : sc[kb][qb]);
+                    gg[kb][qb] = mfma16x16<HALF>(fb[st & 1], gf[qb][kk], kk == 0 ? zero : gg[kb][qb]);
+                }
+                if (kb == 1 && kk == 0) finish_block(sub, 0);      // behind the next block's first step
+                if (u == QG - 1) finish_block(sub, 1);             // the output steps need it now
+            } else {
+                const int db = u - QG;
+#pragma unroll
+                for (int qb = 0; qb < NQ; ++qb) dq[db][qb] = mfma16x16<HALF>(fa[st & 1], dsp[qb], dq[db][qb]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);            // the copy of the tile past the end (zeros)
