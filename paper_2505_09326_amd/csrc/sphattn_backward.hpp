@@ -315,67 +315,77 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
         copy_tile(next_hq < kv_group ? next_hq : 0, next_tile, lds0 + BUF_BYTES - cur);
         const SPH_LDS unsigned char* qb_ = smem + cur;
         const SPH_LDS unsigned char* gb_ = smem + cur + GLDS;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            // S[qb][kb] = Q K^T, G[qb][kb] = dO V^T: lane owns key column n16 of block kb and
-            // queries 16qb + 4g + t of the sub-step
-            f32x4 s[2][NK], gg[2][NK];
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                for (int kb = 0; kb < NK; ++kb) { s[qb][kb] = f32x4{0, 0, 0, 0}; gg[qb][kb] = f32x4{0, 0, 0, 0}; }
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                const int rb = 2 * sub + qb;
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk) {
-                    const i32x4 qa = lds_read_b128(qb_ + (rb * KBLK + kk) * 1024 + alane);
-                    const i32x4 ga = lds_read_b128(gb_ + (rb * KBLK + kk) * 1024 + alane);
-#pragma unroll
-                    for (int kb = 0; kb < NK; ++kb) {
-                        s[qb][kb] = mfma16x16<HALF>(qa, kf[kb][kk], s[qb][kb]);
-                        gg[qb][kb] = mfma16x16<HALF>(ga, vf[kb][kk], gg[qb][kb]);
-                    }
-                }
-            }
-            // per query: r and delta r^2
-            i32x4 wp[NK], dsp[NK];
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                const int qoff = (32 * sub + 16 * qb + 4 * g) * 4;
-                const f32x4 zq = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + ZLDS + qoff));
-                const f32x4 dq_ = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + DLDS + qoff));
-                f32x4 r, c;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    r[t] = zq[t] > 0.f ? __builtin_amdgcn_rsqf(zq[t]) : 0.f;   // v_rsq_f32, 1 ulp
-                    c[t] = dq_[t] * r[t] * r[t];
-                }
-#pragma unroll
-                for (int kb = 0; kb < NK; ++kb) {
-                    const f32x4 sm = MULT ? s[qb][kb] * mk[kb] : s[qb][kb];
-                    const f32x4 w = sm * r;
-                    const f32x4 ds = gg[qb][kb] * r - sm * c;
-                    wp[kb][2 * qb] = pack2<HALF>(w[0], w[1]);
-                    wp[kb][2 * qb + 1] = pack2<HALF>(w[2], w[3]);
-                    dsp[kb][2 * qb] = pack2<HALF>(ds[0], ds[1]);
-                    dsp[kb][2 * qb + 1] = pack2<HALF>(ds[2], ds[3]);
-                }
-            }
-            // dV^T[db][kb] += dO^T W,  dK^T[db][kb] += Q^T dS  (A: 16 columns of d x 32 queries)
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
+        // Fixed sequence of steps, each with a Q-side and a dO-side fragment and 2 NK matrix
+        // instructions; the fragments of step st+1 are read from LDS before the matrix
+        // instructions of step st are issued.  Per 32-query sub-step:
+        //   2 KK score steps (query block qb, k-step kk): S = Q K^T, G = dO V^T
+        //   DB output steps (column block db): dV^T += dO^T W, dK^T += Q^T dS
+        constexpr int QG = 2 * KK, PER_SUB = QG + DB, STEPS = 2 * PER_SUB;
+        i32x4 fa[2], fb[2];
+        auto load_step = [&](int st) {
+            const int sub = st / PER_SUB, u = st % PER_SUB;
+            if (u < QG) {
+                const int rb = 2 * sub + u / KK, kk = u % KK;
+                fa[st & 1] = lds_read_b128(qb_ + (rb * KBLK + kk) * 1024 + alane);
+                fb[st & 1] = lds_read_b128(gb_ + (rb * KBLK + kk) * 1024 + alane);
+            } else {
+                const int db = u - QG;
                 const int boff = (2 * sub * KBLK + db / 2) * 1024 + (db & 1) * 32 + tlane;
-                const i32x2 glo = lds_read_tr64(gb_ + boff), ghi = lds_read_tr64(gb_ + boff + KBLK * 1024);
                 const i32x2 qlo = lds_read_tr64(qb_ + boff), qhi = lds_read_tr64(qb_ + boff + KBLK * 1024);
-                const i32x4 gt = __builtin_shufflevector(glo, ghi, 0, 1, 2, 3);
-                const i32x4 qt_ = __builtin_shufflevector(qlo, qhi, 0, 1, 2, 3);
+                const i32x2 glo = lds_read_tr64(gb_ + boff), ghi = lds_read_tr64(gb_ + boff + KBLK * 1024);
+                fa[st & 1] = __builtin_shufflevector(qlo, qhi, 0, 1, 2, 3);
+                fb[st & 1] = __builtin_shufflevector(glo, ghi, 0, 1, 2, 3);
+            }
+        };
+        // S[qb][kb], G[qb][kb]: lane owns key column n16 of block kb and queries 16qb + 4g + t
+        f32x4 s[2][NK], gg[2][NK];
+        i32x4 wp[NK], dsp[NK];
+        // W and dS of query block qb of sub-step sub: registers 2qb, 2qb+1 of wp and dsp
+        auto finish_block = [&](int sub, int qb) {
+            const int qoff = (32 * sub + 16 * qb + 4 * g) * 4;
+            const f32x4 zq = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + ZLDS + qoff));
+            const f32x4 dq_ = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + DLDS + qoff));
+            f32x4 r, c;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                r[t] = zq[t] > 0.f ? __builtin_amdgcn_rsqf(zq[t]) : 0.f;   // v_rsq_f32, 1 ulp
+                c[t] = dq_[t] * r[t] * r[t];
+            }
+#pragma unroll
+            for (int kb = 0; kb < NK; ++kb) {
+                const f32x4 sm = MULT ? s[qb][kb] * mk[kb] : s[qb][kb];
+                const f32x4 w = sm * r;
+                const f32x4 ds = gg[qb][kb] * r - sm * c;
+                wp[kb][2 * qb] = pack2<HALF>(w[0], w[1]);
+                wp[kb][2 * qb + 1] = pack2<HALF>(w[2], w[3]);
+                dsp[kb][2 * qb] = pack2<HALF>(ds[0], ds[1]);
+                dsp[kb][2 * qb + 1] = pack2<HALF>(ds[2], ds[3]);
+            }
+        };
+        load_step(0);
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+            const int sub = st / PER_SUB, u = st % PER_SUB;
+            if (st + 1 < STEPS) load_step(st + 1);
+            if (u < QG) {
+                const int qb = u / KK, kk = u % KK;
+                const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kb = 0; kb < NK; ++kb) {
-                    dv[db][kb] = mfma16x16<HALF>(gt, wp[kb], dv[db][kb]);
-                    dk[db][kb] = mfma16x16<HALF>(qt_, dsp[kb], dk[db][kb]);
+                    s[qb][kb] = mfma16x16<HALF>(fa[st & 1], kf[kb][kk], kk == 0 ? zero : s[qb][kb]);
+                    gg[qb][kb] = mfma16x16<HALF>(fb[st & 1], vf[kb][kk], kk == 0 ? zero : gg[qb][kb]);
+                }
+                if (qb == 1 && kk == 0) finish_block(sub, 0);      // behind the next block's first step
+                if (u == QG - 1) finish_block(sub, 1);             // the output steps need it now
+            } else {
+                const int db = u - QG;
+#pragma unroll
+                for (int kb = 0; kb < NK; ++kb) {
+                    dv[db][kb] = mfma16x16<HALF>(fb[st & 1], wp[kb], dv[db][kb]);
+                    dk[db][kb] = mfma16x16<HALF>(fa[st & 1], dsp[kb], dk[db][kb]);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
