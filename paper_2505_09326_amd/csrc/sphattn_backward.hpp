@@ -228,8 +228,9 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
 // dK and dV.  Workgroup = 4 waves x 32 keys (two blocks of 16).  Streams Q/dO tiles of 64
 // queries together with their z and delta.
 // ---------------------------------------------------------------------------
-// Two workgroups per CU (two waves per SIMD): the loop is not software-pipelined, so a second
-// wave fills the gaps between LDS reads and matrix instructions (C3 shape: 3.6 -> 2.5 ms).
+// Two workgroups per CU (two waves per SIMD): a fragment feeds only two matrix instructions
+// here, so a second wave fills the gaps that the LDS reads leave (one wave per SIMD with the
+// same step sequence measured slower at d = 128).
 template <int D, bool HALF, bool MULT>
 __global__ __launch_bounds__(kThreads, 2)
 void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, const void* __restrict__ Vv,
