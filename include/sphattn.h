@@ -73,6 +73,11 @@ typedef enum {
  *
  * Returns SPHATTN_OK or a negative SPHATTN_ERR_* code; on error nothing is
  * enqueued and O is untouched.  Never throws or aborts.
+ *
+ * 16-bit launches use workgroups of 256 query rows, or of 128 when 256-row tiles would
+ * leave CUs without work.  The environment variable SPHATTN_TILE_ROWS=128 or =256, read at
+ * every call, overrides that choice (for tests and measurements); the result is the same
+ * function of the inputs either way.
  */
 int sphattn_fwd(const void* Q, const void* K, const void* V, void* O,
                 int B, int H, int N, int d, int dtype, void* stream);
