@@ -150,8 +150,10 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                                                    // issued a tile earlier, measured no faster)
     constexpr int PD = 3;                          // LDS prefetch distance in slots (2: no faster)
     constexpr int RING = 4;                        // fragment registers in rotation
-    // VALU instructions issued behind each MFMA (measured best of 1..4; SoftMax: of 0..6)
-    constexpr int VALU_PER_MFMA = NORM == Norm::Softmax ? 3 : MULT ? 2 : 1;
+    // VALU instructions issued behind each MFMA (measured best of 1..4; SoftMax: of 0..6).  At
+    // d = 64 a slot has 12 VALU instructions for its 8 matrix instructions, so 1 leaves a third
+    // of them to the end of the slot.
+    constexpr int VALU_PER_MFMA = NORM == Norm::Softmax ? 3 : (MULT || D == 64) ? 2 : 1;
     static_assert(NBUF == 4, "tiles j-1 .. j+2 are resident");
     static_assert(D == 64 || D == 128, "head dimension 128 or 64");
     static_assert(NQ == 4 || NQ == 2, "64 or 32 query rows per wave");
