@@ -137,6 +137,21 @@ int sphattn_softmax_fwd(const void* Q, const void* K, const void* V, void* O,
                         int B, int H, int N, int d, int dtype, void* stream);
 
 /*
+ * Spherical attention between N_q query rows and N_k keys (Theorem 1 keeps the query and the
+ * key axis apart; a chunk of queries against a longer key/value sequence is the case in mind):
+ *
+ *     O[b,h,i,:] = (sum_j s_ij V[b,g,j,:]) / sqrt(sum_j s_ij^2),   i < N_q, j < N_k,
+ *
+ * with s_ij as in sphattn_grn_fwd (mult NULL: all ones; H_kv == H: no sharing).
+ *   Q, O : [B,H,N_q,d];   K, V : [B,H_kv,N_k,d];   mult : [B,N_k] fp32 or NULL;
+ *   Z    : [B,H,N_q] fp32 or NULL, receives z_i as in sphattn_fwd_z.
+ * sphattn_grn_fwd is this call with N_q == N_k and Z == NULL.  Errors as sphattn_grn_fwd
+ * (SPHATTN_ERR_SHAPE also for N_q or N_k <= 0).
+ */
+int sphattn_cross_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O, float* Z,
+                      int B, int H, int H_kv, int N_q, int N_k, int d, int dtype, void* stream);
+
+/*
  * The accumulator of Lemma 1 (Appendix A.1) over one set of keys, WITHOUT the tail: for query
  * rows Q[b,h,0..N_q) against the N_k keys/values given,
  *

@@ -21,7 +21,7 @@ _DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN
                 "f16": SPHATTN_F16}
 
 EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_fwd_z", "sphattn_grn_fwd", "sphattn_normalized_fwd",
-                    "sphattn_softmax_fwd", "sphattn_partial_fwd", "sphattn_combine", "sphattn_splitkv_fwd",
+                    "sphattn_softmax_fwd", "sphattn_cross_fwd", "sphattn_partial_fwd", "sphattn_combine", "sphattn_splitkv_fwd",
                     "sphattn_splitkv_workspace_bytes", "sphattn_splitkv_heuristic", "sphattn_bwd", "sphattn_grn_bwd",
                     "sphattn_fp8_workspace_bytes", "sphattn_fp8_fwd", "sphattn_mfma_probe",
                     "sphattn_strerror", "sphattn_version")
@@ -57,6 +57,8 @@ def load_library() -> ctypes.CDLL:
         lib.sphattn_normalized_fwd.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, vp]
         lib.sphattn_fwd_z.restype = ip
         lib.sphattn_fwd_z.argtypes = [vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_cross_fwd.restype = ip
+        lib.sphattn_cross_fwd.argtypes = [vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, ip, vp]
         lib.sphattn_partial_fwd.restype = ip
         lib.sphattn_partial_fwd.argtypes = [vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, ip, vp]
         lib.sphattn_combine.restype = ip
@@ -212,6 +214,23 @@ def sphattn_fwd_z(Q, K, V, O=None, Z=None, dtype="bf16", stream=None):
     if rc != 0:
         raise SphattnError(rc, sphattn_strerror(rc))
     return O, Z
+
+
+def sphattn_cross_fwd(Q, K, V, mult=None, O=None, Z=None, dtype="bf16", stream=None):
+    """Spherical attention of Q [B,H,N_q,d] over the keys K, V [B,H_kv,N_k,d] (optional
+    multiplicities mult [B,N_k], optional row aggregates Z [B,H,N_q]); returns O [B,H,N_q,d]."""
+    import torch
+    lib = load_library()
+    if O is None:
+        O = torch.empty(Q.shape, dtype=V.dtype, device=Q.device)
+    _check_device("Q, K, V, mult, O, Z", Q, K, V, mult, O, Z)
+    B, H, Nq, d = Q.shape
+    rc = lib.sphattn_cross_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(mult), O.data_ptr(), _ptr(Z),
+                               B, H, K.shape[1], Nq, K.shape[2], d, _dtype_code(dtype),
+                               ctypes.c_void_p(_stream_of(Q, stream)))
+    if rc != 0:
+        raise SphattnError(rc, sphattn_strerror(rc))
+    return O
 
 
 def sphattn_partial_fwd(Q, K, V, mult=None, o_part=None, z_part=None, dtype="bf16", stream=None):

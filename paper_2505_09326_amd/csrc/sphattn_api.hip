@@ -324,6 +324,16 @@ int sphattn_grn_fwd(const void* Q, const void* K, const void* V, const float* mu
                 : dispatch<Norm::Spherical, false>(p, d, dtype);
 }
 
+int sphattn_cross_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O, float* Z,
+                      int B, int H, int H_kv, int N_q, int N_k, int d, int dtype, void* stream)
+{
+    const int rc = check_args(Q, K, V, O, out_bytes_of(B, H, N_q, d, dtype), mult, Z, B, H, H_kv, N_q, N_k, d, dtype);
+    if (rc != SPHATTN_OK) return rc;
+    const Problem p{Q, K, V, O, mult, Z, B, H, H_kv, N_q, N_k, (hipStream_t)stream};
+    return mult ? dispatch<Norm::Spherical, true>(p, d, dtype)
+                : dispatch<Norm::Spherical, false>(p, d, dtype);
+}
+
 int sphattn_normalized_fwd(const void* Q, const void* K, const void* V, void* O,
                            int B, int H, int N, int d, int dtype, int normalizer, void* stream)
 {

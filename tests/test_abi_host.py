@@ -206,6 +206,22 @@ def test_backward_argument_errors(lib):
     assert grn(Q=0) == -1
 
 
+def test_cross_argument_errors(lib):
+    P = ctypes.c_void_p
+
+    def call(Q=0x1000000, K=0x2000000, V=0x3000000, mult=0, O=0x4000000, Z=0, B=1, H=4, H_kv=2, Nq=100, Nk=300,
+             d=64, dtype=1):
+        return lib.sphattn_cross_fwd(P(Q), P(K), P(V), P(mult), P(O), P(Z), B, H, H_kv, Nq, Nk, d, dtype, None)
+    assert call(Q=0) == -1 and call(O=0) == -1
+    assert call(Nq=0) == -2 and call(Nk=0) == -2 and call(H_kv=3) == -2
+    assert call(d=32) == -3 and call(dtype=7) == -4
+    assert call(K=0x2000004) == -5 and call(Z=0x5000002) == -5
+    assert call(O=0x1000000) == -7
+    assert call(O=0x2000000 + 300 * 64 * 2) == -7          # O inside K (N_k rows of it)
+    assert call(Z=0x4000000) == -7                         # Z is O
+    assert call(mult=0x4000000 + 64) == -7                 # mult inside O
+
+
 def test_fp8_argument_errors_and_workspace_size(lib):
     P = ctypes.c_void_p
     wsb = lib.sphattn_fp8_workspace_bytes

@@ -251,3 +251,35 @@ def test_splitkv_few_heads_at_full_length(pkg, oracle):
         worst = max(worst, np.abs(got.reshape(B * H, N, d)[bh, rows] - ref).max())
     print(f"splitkv full length: max|err| = {worst:.3e} (outputs have unit variance)", flush=True)
     assert worst <= TOL_O["bf16"]
+
+
+CROSS_SHAPES = [(1, 2, 2, 1, 700, 128, "bf16", False), (2, 4, 2, 300, 77, 64, "bf16", True),
+                (1, 2, 1, 513, 2049, 128, "f16", True), (1, 3, 3, 64, 1000, 64, "fp8qk_bf16v", False),
+                (2, 2, 1, 257, 130, 128, "f32", True), (1, 1, 1, 1000, 1, 64, "bf16", False)]
+
+
+@pytest.mark.parametrize("B,H,H_kv,Nq,Nk,d,dtype,with_mult", CROSS_SHAPES)
+def test_cross_forward_parity(pkg, oracle, B, H, H_kv, Nq, Nk, d, dtype, with_mult):
+    """N_q query rows against N_k keys (sphattn_cross_fwd), with and without multiplicities and
+    shared K/V heads; O and z against the oracle's accumulator followed by its tail."""
+    print(f"case cross B={B} H={H} H_kv={H_kv} Nq={Nq} Nk={Nk} d={d} {dtype} mult={with_mult}", flush=True)
+    q, _, _ = si.make_qkv(B, H, Nq, d, dtype, seed=700 + Nq)
+    _, k, v = si.make_qkv(B, H_kv, Nk, d, dtype, seed=800 + Nk)
+    mult = None
+    if with_mult:
+        g = torch.Generator(device="cpu").manual_seed(900 + Nk)
+        mult = torch.poisson(torch.full((B, Nk), 1.5), generator=g).to(torch.float32)
+        mult[:, 0] = 2.0
+    bits, kinds = _bits(q, k, v)
+    o_raw, z_ref = oracle.spherical_accumulate(*bits, mult=None if mult is None else mult.numpy(), kinds=kinds)
+    ref = oracle.spherical_tail(o_raw[None], z_ref[None])
+    Z = torch.empty(B, H, Nq, dtype=torch.float32, device=DEV)
+    O = pkg.sphattn_cross_fwd(q.to(DEV), k.to(DEV), v.to(DEV), None if mult is None else mult.to(DEV), Z=Z, dtype=dtype)
+    torch.cuda.synchronize()
+    got = O.cpu().to(torch.float64).numpy()
+    assert got.shape == (B, H, Nq, d) and np.all(np.isfinite(got))
+    assert _rel_err(got, ref) <= TOL_O[dtype]
+    # a score that nearly cancels (|s| << |q||k|) carries the fp32 rounding of its d products,
+    # about d 2^-24 |q||k|, which a row with a single key does not average out: absolute slack
+    # of 1e-7 of the largest z on top of the relative tolerance
+    np.testing.assert_allclose(Z.cpu().to(torch.float64).numpy(), z_ref, rtol=Z_RTOL, atol=1e-7 * z_ref.max())
