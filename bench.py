@@ -166,7 +166,7 @@ def main() -> int:
     if not args.no_twin and w.dtype == "bf16":
         def twin():
             pkg.sphattn_softmax_fwd(qd, kd, vd, out, dtype=w.dtype)
-        _, per_t = time_launches(twin, max(10, args.steps // 4), max(5, args.warmup // 4))
+        _, per_t = time_launches(twin, max(30, args.steps // 2), max(10, args.warmup // 2))
         ms_t = sum(per_t) / len(per_t)
         result["softmax_twin"] = {"kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12,
                                   "spherical_speedup": ms_t / ms_kernel,
@@ -174,7 +174,7 @@ def main() -> int:
 
         def twin16():
             pkg.sphattn_normalized_fwd(qd, kd, vd, out, dtype=w.dtype, normalizer="softmax")
-        _, per_t = time_launches(twin16, max(10, args.steps // 4), max(5, args.warmup // 4))
+        _, per_t = time_launches(twin16, max(30, args.steps // 2), max(10, args.warmup // 2))
         ms_t = sum(per_t) / len(per_t)
         result["softmax_twin_same_instructions"] = {
             "kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12, "spherical_speedup": ms_t / ms_kernel,
@@ -187,7 +187,7 @@ def main() -> int:
 
         def grn():
             pkg.sphattn_grn_fwd(qd, kg, vg, mult, out, dtype=w.dtype)
-        _, per_g = time_launches(grn, max(10, args.steps // 4), max(5, args.warmup // 4))
+        _, per_g = time_launches(grn, max(30, args.steps // 2), max(10, args.warmup // 2))
         ms_g = sum(per_g) / len(per_g)
         result["grn_variant"] = {"H_kv": args.grn, "multiplicities": "Poisson(1.5)", "kernel_ms_avg": ms_g,
                                  "tflops": w.flops / (ms_g * 1e-3) / 1e12}
@@ -199,9 +199,9 @@ def main() -> int:
         n_splits = pkg.sphattn_splitkv_heuristic(1, hs, w.N, w.d, w.dtype)
         ws = torch.empty(pkg.sphattn_splitkv_workspace_bytes(1, hs, w.N, w.d, n_splits), dtype=torch.uint8, device=dev)
         _, per_u = time_launches(lambda: pkg.sphattn_fwd(qs, ks, vs, outs, dtype=w.dtype),
-                                 max(10, args.steps // 4), max(5, args.warmup // 4))
+                                 max(30, args.steps // 2), max(10, args.warmup // 2))
         _, per_s = time_launches(lambda: pkg.sphattn_splitkv_fwd(qs, ks, vs, ws, O=outs, n_splits=n_splits, dtype=w.dtype),
-                                 max(10, args.steps // 4), max(5, args.warmup // 4))
+                                 max(30, args.steps // 2), max(10, args.warmup // 2))
         ms_u, ms_s = sum(per_u) / len(per_u), sum(per_s) / len(per_s)
         fl = 4.0 * hs * w.N * w.N * w.d
         result["splitkv_variant"] = {
@@ -247,7 +247,7 @@ def main() -> int:
         ws8 = torch.empty(pkg.sphattn_fp8_workspace_bytes(w.B, w.H, w.N, w.d), dtype=torch.uint8, device=dev)
         out8 = torch.empty((w.B, w.H, w.N, w.d), dtype=torch.bfloat16, device=dev)
         _, per_8 = time_launches(lambda: pkg.sphattn_fp8_fwd(q8, k8, v8, ws8, O=out8),
-                                 max(10, args.steps // 4), max(5, args.warmup // 4))
+                                 max(30, args.steps // 2), max(10, args.warmup // 2))
         ms_8 = sum(per_8) / len(per_8)
         tf8 = w.flops / (ms_8 * 1e-3) / 1e12
         result["fp8_all_variant"] = {
@@ -275,7 +275,7 @@ def main() -> int:
         dQ, dK, dV = (torch.empty_like(qd) for _ in range(3))
         delta = torch.empty_like(Zf)
         _, per_b = time_launches(lambda: pkg.sphattn_bwd(qd, kd, vd, out, dO, Zf, dQ, dK, dV, delta, dtype=w.dtype),
-                                 max(10, args.steps // 4), max(5, args.warmup // 4))
+                                 max(30, args.steps // 2), max(10, args.warmup // 2))
         ms_b = sum(per_b) / len(per_b)
         result["backward"] = {
             "ms_avg": ms_b, "kernels": 2,
