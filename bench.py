@@ -180,6 +180,15 @@ def main() -> int:
             "kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12, "spherical_speedup": ms_t / ms_kernel,
             "form": "16x16x32 MFMA, the spherical kernel with exp/max/rescale in stage B"}
 
+    if not args.no_twin and w.dtype == "fp8qk_bf16v":
+        def twin8():
+            pkg.sphattn_normalized_fwd(qd, kd, vd, out, dtype=w.dtype, normalizer="softmax")
+        _, per_t = time_launches(twin8, max(30, args.steps // 2), max(10, args.warmup // 2))
+        ms_t = sum(per_t) / len(per_t)
+        result["softmax_twin_same_instructions"] = {
+            "kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12, "spherical_speedup": ms_t / ms_kernel,
+            "form": "the spherical kernel (fp8 16x16x128 scores, bf16 16x16x32 output) with exp/max/rescale in stage B"}
+
     if args.grn:
         g = torch.Generator(device="cpu").manual_seed(w.seed + 1000)
         mult = torch.poisson(torch.full((w.B, w.N), 1.5), generator=g).to(torch.float32).to(dev)

@@ -117,7 +117,9 @@ int sphattn_grn_fwd(const void* Q, const void* K, const void* V, const float* mu
  * sphattn_softmax_fwd computes, on the family's kernel (the same matrix instructions as the
  * spherical case) instead of the SoftMax-specific one.
  * A row whose aggregate sum_j a2(s_ij) is 0 gives 0.  dtype must be SPHATTN_BF16 unless the
- * normalizer is SPHATTN_NORM_L2.  Other arguments, layout, ownership and errors as sphattn_fwd;
+ * normalizer is SPHATTN_NORM_L2; SPHATTN_NORM_SOFTMAX also takes SPHATTN_FP8QK_BF16V (the
+ * comparison twin of the fp8-Q/K path: scores from the fp8 matrix instructions, then the same
+ * exponential, running maximum and rescaling).  Other arguments, layout, ownership and errors as sphattn_fwd;
  * an unknown normalizer returns SPHATTN_ERR_NORMALIZER.
  */
 int sphattn_normalized_fwd(const void* Q, const void* K, const void* V, void* O,

@@ -195,6 +195,12 @@ int dispatch(const Problem& p, int d, int dtype)
         if (d == 128) return launch_pipelined<128, 4, QKType::Bf16, NORM, MULT>(p);
         return launch_pipelined<64, 4, QKType::Bf16, NORM, MULT>(p);
     }
+    if constexpr (NORM == Norm::Softmax && !MULT) {
+        if (dtype == SPHATTN_FP8QK_BF16V) {
+            if (d == 128) return launch_pipelined<128, 4, QKType::Fp8, NORM, MULT>(p);
+            return launch_pipelined<64, 4, QKType::Fp8, NORM, MULT>(p);
+        }
+    }
     if constexpr (NORM == Norm::Spherical) {
         if (dtype == SPHATTN_F16) {
             if (d == 128) return launch_pipelined<128, 4, QKType::F16, NORM, MULT>(p);
@@ -340,7 +346,9 @@ int sphattn_normalized_fwd(const void* Q, const void* K, const void* V, void* O,
     const int rc = check_args(Q, K, V, O, out_bytes_of(B, H, N, d, dtype), nullptr, nullptr, B, H, H, N, N, d, dtype);
     if (rc != SPHATTN_OK) return rc;
     if (normalizer < SPHATTN_NORM_L2 || normalizer > SPHATTN_NORM_SQRELU) return SPHATTN_ERR_NORMALIZER;
-    if (normalizer != SPHATTN_NORM_L2 && dtype != SPHATTN_BF16) return SPHATTN_ERR_DTYPE;
+    if (normalizer != SPHATTN_NORM_L2 && dtype != SPHATTN_BF16 &&
+        !(normalizer == SPHATTN_NORM_SOFTMAX && dtype == SPHATTN_FP8QK_BF16V))
+        return SPHATTN_ERR_DTYPE;
     const Problem p{Q, K, V, O, nullptr, nullptr, B, H, H, N, N, (hipStream_t)stream};
     switch (normalizer) {
     case SPHATTN_NORM_L2: return dispatch<Norm::Spherical, false>(p, d, dtype);

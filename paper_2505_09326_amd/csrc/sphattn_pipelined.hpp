@@ -162,7 +162,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     static_assert(PAIRS >= 1 && NST <= SLOTS + PD - 1, "slot plan");
     static_assert(KCH >= 1 && VCH >= 1, "rows are whole 16-byte chunks");
     static_assert((2 * SLOTS) % RING == 0 && PD < RING && PD <= SLOTS, "ring indices must repeat");
-    static_assert(QKT == QKType::Bf16 || NORM == Norm::Spherical, "fp8 and fp16 storage: spherical only");
+    static_assert(QKT == QKType::Bf16 || NORM == Norm::Spherical || (QKT == QKType::Fp8 && NORM == Norm::Softmax),
+                  "fp16 storage: spherical only; fp8 Q/K: spherical and the SoftMax twin");
     static_assert(!MULT || NORM == Norm::Spherical, "multiplicities belong to the spherical variant");
     static_assert(!PARTIAL || NORM == Norm::Spherical, "partial accumulators: spherical only");
 

@@ -88,7 +88,7 @@ def test_normalized_entry_argument_errors(lib):
                                           1, 1, 128, d, dtype, normalizer, None)
     assert call(normalizer=4) == -8
     assert call(normalizer=-1) == -8
-    assert call(normalizer=2, dtype=2) == -4       # fp8 Q/K only with the L2 normalizer
+    assert call(normalizer=2, dtype=2) == -4       # fp8 Q/K only with the L2 normalizer and the SoftMax twin
     assert call(normalizer=3, dtype=0) == -4
     assert call(normalizer=1, dtype=3) == -4       # fp16 storage only with the L2 normalizer
     assert call(d=100) == -3

@@ -371,6 +371,27 @@ def test_normalizer_family_parity(pkg, oracle, name, B, H, N, d):
         assert np.abs(got - ref).max() <= 2.0 ** -9 * np.abs(ref).max() + 1e-2 * rms
 
 
+@pytest.mark.parametrize("B,H,N,d", [(1, 2, 300, 64), (1, 1, 1029, 128), (2, 2, 2048, 128)])
+def test_softmax_twin_with_fp8_qk(pkg, oracle, B, H, N, d):
+    """SoftMax on the family's kernel with Q, K in E4M3 (the twin of the fp8-Q/K path).  Inputs
+    of moderate size (N(0, 0.5) cast to E4M3 without the per-tensor scaling of the workloads),
+    so that the SoftMax is not one-hot; tolerance as for the bf16 twin."""
+    print(f"case softmax fp8qk B={B} H={H} N={N} d={d}", flush=True)
+    qf, kf, vf = si.gaussian_qkv(B, H, N, d, seed=860 + N, factor=0.5)
+    q, k, v = qf.to(torch.float8_e4m3fn), kf.to(torch.float8_e4m3fn), vf.to(torch.bfloat16)
+    dev = torch.device("cuda:0")
+    out = pkg.sphattn_normalized_fwd(q.to(dev), k.to(dev), v.to(dev), dtype="fp8qk_bf16v", normalizer="softmax")
+    torch.cuda.synchronize()
+    got = out.cpu().to(torch.float64).numpy()
+    bits, kinds = _kinds(q, k, v)
+    ref = oracle.normalized_attention(*bits, "softmax", kinds=kinds)
+    assert np.all(np.isfinite(got))
+    rms = np.sqrt((ref ** 2).mean())
+    err = np.abs(got - ref).max()
+    print(f"softmax fp8qk max|err|/rms={err / rms:.3e}", flush=True)
+    assert err <= 2.0 ** -9 * np.abs(ref).max() + 1e-2 * rms
+
+
 def test_one_long_head(pkg, oracle):
     """A single long, ragged head (N = 70001, d = 64): 32-bit buffer ranges, many key tiles,
     fewer workgroups than CUs.  Sampled rows against the oracle plus the Gram closed form."""
