@@ -287,6 +287,20 @@ int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O,
                     int B, int H, int N, int d, void* stream);
 
 /*
+ * Comparison twin of sphattn_fp8_fwd: O = softmax(Q K^T / sqrt(d)) V with the same storage, the
+ * same kernel skeleton and the weights entering the second contraction as E4M3, made as cheap
+ * as a SoftMax can be there: row i is shifted by the bound |q_i| max_j |k_j| / sqrt(d) instead
+ * of its running maximum (mathematically the same function), so that only a scale-and-shift and
+ * an exponential per score are added to the spherical kernel's work.  For timing the cost of the
+ * exponential at the fp8 matrix rate (paper, Section 1) on inputs of moderate size: a row whose
+ * largest score lies more than about 12 sqrt(d) below that bound underflows to all-zero
+ * weights and gives 0.  Arguments, workspace and errors as sphattn_fp8_fwd.
+ */
+int sphattn_fp8_softmax_fwd(const void* Q, const void* K, const void* V, void* O,
+                            void* workspace, size_t workspace_bytes,
+                            int B, int H, int N, int d, void* stream);
+
+/*
  * Measurement aid, not part of the method: one launch (256 workgroups of 256 threads, one per
  * CU) of a loop of nothing but matrix instructions, to measure what the matrix pipes
  * sustain on given operand values next to the attention kernels (on random data the part is

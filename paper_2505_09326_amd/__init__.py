@@ -23,7 +23,7 @@ _DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN
 EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_fwd_z", "sphattn_grn_fwd", "sphattn_normalized_fwd",
                     "sphattn_softmax_fwd", "sphattn_cross_fwd", "sphattn_partial_fwd", "sphattn_combine", "sphattn_splitkv_fwd",
                     "sphattn_splitkv_workspace_bytes", "sphattn_splitkv_heuristic", "sphattn_bwd", "sphattn_grn_bwd",
-                    "sphattn_fp8_workspace_bytes", "sphattn_fp8_fwd", "sphattn_mfma_probe",
+                    "sphattn_fp8_workspace_bytes", "sphattn_fp8_fwd", "sphattn_fp8_softmax_fwd", "sphattn_mfma_probe",
                     "sphattn_strerror", "sphattn_version")
 
 NORMALIZERS = {"l2": 0, "softmax": 1, "l1": 2, "sqrelu": 3}
@@ -76,8 +76,10 @@ def load_library() -> ctypes.CDLL:
         lib.sphattn_grn_bwd.argtypes = [vp] * 11 + [ip, ip, ip, ip, ip, ip, vp]
         lib.sphattn_fp8_workspace_bytes.restype = ctypes.c_size_t
         lib.sphattn_fp8_workspace_bytes.argtypes = [ip, ip, ip, ip]
-        lib.sphattn_fp8_fwd.restype = ip
-        lib.sphattn_fp8_fwd.argtypes = [vp, vp, vp, vp, vp, ctypes.c_size_t, ip, ip, ip, ip, vp]
+        for name in ("sphattn_fp8_fwd", "sphattn_fp8_softmax_fwd"):
+            fn = getattr(lib, name)
+            fn.restype = ip
+            fn.argtypes = [vp, vp, vp, vp, vp, ctypes.c_size_t, ip, ip, ip, ip, vp]
         lib.sphattn_mfma_probe.restype = ip
         lib.sphattn_mfma_probe.argtypes = [vp, vp, ip, ip, vp]
         lib.sphattn_strerror.restype = ctypes.c_char_p
@@ -298,7 +300,13 @@ def sphattn_fp8_workspace_bytes(B, H, N, d) -> int:
     return int(load_library().sphattn_fp8_workspace_bytes(B, H, N, d))
 
 
-def sphattn_fp8_fwd(Q, K, V, workspace, O=None, stream=None):
+def sphattn_fp8_softmax_fwd(Q, K, V, workspace, O=None, stream=None):
+    """SoftMax comparison twin of sphattn_fp8_fwd (same arguments): for timing, on inputs of
+    moderate size."""
+    return sphattn_fp8_fwd(Q, K, V, workspace, O=O, stream=stream, _entry="sphattn_fp8_softmax_fwd")
+
+
+def sphattn_fp8_fwd(Q, K, V, workspace, O=None, stream=None, _entry="sphattn_fp8_fwd"):
     """Spherical attention with Q, K and V all stored in E4M3 (float8_e4m3fn tensors [B,H,N,128])
     and both contractions on the fp8 matrix instructions; O is bfloat16.  `workspace` is a
     device byte tensor of at least sphattn_fp8_workspace_bytes(...)."""
@@ -308,9 +316,9 @@ def sphattn_fp8_fwd(Q, K, V, workspace, O=None, stream=None):
         O = torch.empty(Q.shape, dtype=torch.bfloat16, device=Q.device)
     _check_device("Q, K, V, O, workspace", Q, K, V, O, workspace)
     B, H, N, d = Q.shape
-    rc = lib.sphattn_fp8_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), workspace.data_ptr(),
-                             workspace.numel() * workspace.element_size(), B, H, N, d,
-                             ctypes.c_void_p(_stream_of(Q, stream)))
+    rc = getattr(lib, _entry)(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), workspace.data_ptr(),
+                              workspace.numel() * workspace.element_size(), B, H, N, d,
+                              ctypes.c_void_p(_stream_of(Q, stream)))
     if rc != 0:
         raise SphattnError(rc, sphattn_strerror(rc))
     return O

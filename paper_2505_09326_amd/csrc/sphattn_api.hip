@@ -500,8 +500,8 @@ size_t sphattn_fp8_workspace_bytes(int B, int H, int N, int d)
     return (size_t)B * H * d * tiles * kFp8Tile + (((size_t)B * H * 4 + 255) & ~(size_t)255);
 }
 
-int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O, void* workspace,
-                    size_t workspace_bytes, int B, int H, int N, int d, void* stream)
+static int fp8_forward(const void* Q, const void* K, const void* V, void* O, void* workspace,
+                       size_t workspace_bytes, int B, int H, int N, int d, void* stream, bool softmax)
 {
     if (d != kFp8D) return SPHATTN_ERR_HEAD_DIM;
     if (!Q || !K || !V || !O) return SPHATTN_ERR_NULL;
@@ -528,9 +528,9 @@ int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O, void* 
     hipLaunchKernelGGL(fp8_prepare_kernel, dim3((unsigned)(heads * n_tiles)), dim3(256), 0, st,
                        (const unsigned char*)K, (const unsigned char*)V, VT, kmax, N, n_tiles);
     constexpr int lds_bytes = 4 * 2 * kFp8Tile * kFp8D;
-    static std::atomic<uint64_t> done{0};
-    auto kern = fwd_fp8_kernel;
-    if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;
+    static std::atomic<uint64_t> done{0}, done_twin{0};
+    auto kern = softmax ? fwd_fp8_kernel<true> : fwd_fp8_kernel<false>;
+    if (!raise_lds_limit(kern, lds_bytes, softmax ? done_twin : done)) return SPHATTN_ERR_LAUNCH;
     const int n_qtiles = (N + 255) / 256;
     const long long n_wg = (long long)heads * n_qtiles;
     if (n_wg > 0x7fffffff) return SPHATTN_ERR_SHAPE;
@@ -538,6 +538,18 @@ int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O, void* 
                        (const unsigned char*)Q, (const unsigned char*)K, (const unsigned char*)VT,
                        (const float*)kmax, (unsigned short*)O, N, n_tiles, n_qtiles, (int)n_wg);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
+}
+
+int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O, void* workspace,
+                    size_t workspace_bytes, int B, int H, int N, int d, void* stream)
+{
+    return fp8_forward(Q, K, V, O, workspace, workspace_bytes, B, H, N, d, stream, false);
+}
+
+int sphattn_fp8_softmax_fwd(const void* Q, const void* K, const void* V, void* O, void* workspace,
+                            size_t workspace_bytes, int B, int H, int N, int d, void* stream)
+{
+    return fp8_forward(Q, K, V, O, workspace, workspace_bytes, B, H, N, d, stream, true);
 }
 
 int sphattn_mfma_probe(const void* operands, long long* clocks, int form, int iters, void* stream)

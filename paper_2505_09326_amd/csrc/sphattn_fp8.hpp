@@ -136,6 +136,17 @@ __global__ void fp8_clear_kernel(float* __restrict__ p, int n)
 //
 // One workgroup = 4 wavefronts = 256 query rows of one (b, h); a wavefront owns NQ = 4 blocks
 // of 16 rows.  VT and kmax come from fp8_prepare_kernel (same stream, earlier).
+//
+// SOFTMAX: the comparison twin.  O = softmax(Q K^T / sqrt(d)) V on the same skeleton, made as
+// cheap as a SoftMax can be here: the shift of row i is not a running maximum but the bound
+// |q_i| max_j |k_j| / sqrt(d) >= max_j s_ij / sqrt(d) (any shift that is not below the maximum
+// gives the same result), so there is no cross-lane maximum and no rescaling of the
+// accumulators; what remains per score is one scale-and-shift and one exponential in front of
+// the convert.  The weights p = exp(...) <= 1 enter the second contraction as 256 p in E4M3;
+// the row sums come from the matrix cores as well (an all-ones A fragment against P).  A row
+// whose largest score is more than about 12 sqrt(d) below its bound underflows to zero weights
+// and gives 0: a twin for timing on inputs of moderate size, not a general SoftMax.
+template <bool SOFTMAX>
 __global__ __launch_bounds__(kThreads, 1)
 void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __restrict__ K,
                     const unsigned char* __restrict__ VT, const float* __restrict__ kmax,
@@ -183,6 +194,8 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     typedef __attribute__((ext_vector_type(8))) int frag_t;
     frag_t qf[NQ];
     float qdiv[NQ];                                // 2^e_i: the scores of row i are divided by it on conversion
+    float qshift[NQ];
+    constexpr float kSoftmaxScaleLog2 = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
     const float km = kmax[bh];
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
@@ -204,7 +217,8 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
         int e = 0;
         (void)__builtin_frexpf(bound * (1.0f / 440.f), &e);   // bound / 440 = m 2^e, m in [0.5, 1)
         e = bound > 0.f ? min(max(e, -126), 127) : 0;
-        qdiv[qb] = __builtin_ldexpf(1.0f, e);
+        qdiv[qb] = SOFTMAX ? 1.0f / 256.f : __builtin_ldexpf(1.0f, e);
+        qshift[qb] = bound * kSoftmaxScaleLog2;    // SOFTMAX: exponent of 2 subtracted from every score's
     }
 
     f32x4 oacc[SLOTS][NQ];
@@ -254,13 +268,30 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     // (nearest even) into one half of a register.  lo starts a register (no initial value
     // needed: hi writes the other half), hi completes it.
     typedef __attribute__((ext_vector_type(2))) short s16x2;
-    auto stage_b_lo = [&](f32x4 sc, float div) -> s16x2 {
+    // `left` = how many of the lane's four keys of this block exist (keys past the end of the
+    // head have zero rows, which the spherical weights turn into zeros by themselves; the
+    // SoftMax twin has to leave them out explicitly)
+    auto weight = [&](float sc, float shift, bool exists) -> float {
+        if constexpr (SOFTMAX) return exists ? __builtin_amdgcn_exp2f(__builtin_fmaf(sc, kSoftmaxScaleLog2, -shift)) : 0.f;
+        else return sc;
+    };
+    auto stage_b_lo = [&](f32x4 sc, float div, float shift, int left) -> s16x2 {
         s16x2 w;
         asm volatile("" : "=v"(w));
-        return __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, sc[0], sc[1], div, false);
+        return __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, weight(sc[0], shift, left > 0), weight(sc[1], shift, left > 1), div, false);
     };
-    auto stage_b_hi = [&](s16x2 w, f32x4 sc, float div) -> int {
-        return __builtin_bit_cast(int, __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, sc[2], sc[3], div, true));
+    auto stage_b_hi = [&](s16x2 w, f32x4 sc, float div, float shift, int left) -> int {
+        return __builtin_bit_cast(int, __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, weight(sc[2], shift, left > 2), weight(sc[3], shift, left > 3), div, true));
+    };
+    // keys of the lane in block row kb of tile t: 128 t + 64 (kb / 4) + 16 g + 4 (kb % 4) + 0..3
+    auto keys_left = [&](int t, int kb) -> int {
+        if (!SOFTMAX) return 4;
+        return t < 0 ? 0 : N - (128 * t + 64 * (kb >> 2) + 16 * g + 4 * (kb & 3));   // t = -1: before the first tile
+    };
+    // SOFTMAX: row sums of P as all-ones rows times P
+    const frag_t ones = {0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838};
+    auto row_aggregate = [&](frag_t pq, f32x4 acc) -> f32x4 {
+        return SOFTMAX ? mfma8(ones, pq, acc) : mfma8(pq, pq, acc);
     };
     f32x4 zz[NQ];
 #pragma unroll
@@ -347,13 +378,14 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
                     oacc[(i + 7) % 8][m - NQ] = mfma8(vfr, Pr[m - NQ], oacc[(i + 7) % 8][m - NQ]);
                 }
                 const int qb = m / 2;
-                if (m % 2 == 0) wlo = stage_b_lo(Sc[qb], qdiv[qb]);
-                else Pw[qb][(i + 7) % 8] = stage_b_hi(wlo, Sc[qb], qdiv[qb]);
+                const int left = keys_left(i == 0 ? tile - 1 : tile, (i + 7) % 8);   // the block row in Sc
+                if (m % 2 == 0) wlo = stage_b_lo(Sc[qb], qdiv[qb], qshift[qb], left);
+                else Pw[qb][(i + 7) % 8] = stage_b_hi(wlo, Sc[qb], qdiv[qb], qshift[qb], left);
                 __builtin_amdgcn_sched_barrier(0);
             }
             // z of the previous tile as the diagonal of P^T P (P serves as A and as B operand:
             // lane (n16, g) holds the k-slots 32g.. of row, or column, n16 either way)
-            if (i >= 1 && i <= NQ) zz[i - 1] = mfma8(Pr[i - 1], Pr[i - 1], zz[i - 1]);
+            if (i >= 1 && i <= NQ) zz[i - 1] = row_aggregate(Pr[i - 1], zz[i - 1]);
             // copies, two per slot: those of tile T+2 start behind the barrier and carry on in the
             // first slots of the next tile (where the same tile is T+1)
             if (i >= SLOTS - PD) {
@@ -382,10 +414,11 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
         }
 #pragma unroll
         for (int qb = 0; qb < NQ; ++qb)
-            P1[qb][7] = stage_b_hi(stage_b_lo(SB[qb], qdiv[qb]), SB[qb], qdiv[qb]);
+            P1[qb][7] = stage_b_hi(stage_b_lo(SB[qb], qdiv[qb], qshift[qb], keys_left(2 * n_pairs - 1, 7)), SB[qb],
+                                   qdiv[qb], qshift[qb], keys_left(2 * n_pairs - 1, 7));
         // the last tile's Gram product (the loop adds a tile's in the next tile's slots)
 #pragma unroll
-        for (int qb = 0; qb < NQ; ++qb) zz[qb] = mfma8(P1[qb], P1[qb], zz[qb]);
+        for (int qb = 0; qb < NQ; ++qb) zz[qb] = row_aggregate(P1[qb], zz[qb]);
 #pragma unroll
         for (int db = 0; db < SLOTS; ++db) {
             const frag_t vfr = read_frag(bprv + KTILE + db * 2048);
@@ -401,9 +434,13 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
         // z_i: the diagonal element of query n16 (row 4g + t = n16) is held by lane group n16 / 4
         // in register n16 % 4; the other three lanes of the query get it through the sum
         const float dsel = (n16 & 3) == 0 ? zz[qb][0] : (n16 & 3) == 1 ? zz[qb][1] : (n16 & 3) == 2 ? zz[qb][2] : zz[qb][3];
-        const float z = sum_across_groups(g == (n16 >> 2) ? dsel : 0.f);
+        float z = sum_across_groups(g == (n16 >> 2) ? dsel : 0.f);
         // o and z were both accumulated from the scores divided by 2^e_i: the factor cancels
-        const float inv = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
+        float inv = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
+        if constexpr (SOFTMAX) {                   // every row of the product is the row sum of query n16
+            z = zz[qb][0];
+            inv = z > 0.f ? 1.0f / z : 0.f;
+        }
         const int row = q0 + qb * 16 + n16;
         if (row < N) {
             unsigned short* dst = Oh + (size_t)row * D + 4 * g;

@@ -242,6 +242,10 @@ def test_fp8_argument_errors_and_workspace_size(lib):
     assert call(ws=0) == -9 and call(ws=0x40000004) == -9 and call(size=need - 1) == -9
     assert call(ws=0x2000000) == -7                        # workspace is K
     assert call(ws=0x4000000 + 4096) == -7                 # workspace inside O
+    # the SoftMax twin shares the checks
+    twin = lib.sphattn_fp8_softmax_fwd
+    assert twin(P(0x1000000), P(0x2000000), P(0x3000000), P(0x4000000), P(0x40000000), need - 1, 1, 2, 1000, 128, None) == -9
+    assert twin(P(0x1000000), P(0x2000000), P(0x3000000), P(0x4000000), P(0x40000000), need, 1, 2, 1000, 64, None) == -3
 
 
 def test_mfma_probe_argument_errors(lib):

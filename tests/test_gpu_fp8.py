@@ -190,3 +190,25 @@ def test_fp8_all_argument_errors_on_device(pkg):
     with pytest.raises(pkg.SphattnError) as e:
         pkg.sphattn_fp8_fwd(q64, k64, v64, ws)
     assert e.value.code == -3
+
+
+@pytest.mark.parametrize("B,H,N", [(1, 1, 77), (1, 2, 128), (2, 1, 300), (1, 1, 1000), (1, 2, 2049)])
+def test_fp8_all_softmax_twin(pkg, oracle, B, H, N):
+    """The all-E4M3 SoftMax twin against the oracle's SoftMax, on inputs of moderate size (N(0, 0.5)
+    cast to E4M3).  Its weights are rounded to E4M3 like the spherical variant's scores, so the same
+    statistical bounds apply: rms(err) <= 0.04 rms(O), max <= 0.25 rms(O).  Ragged N checks that
+    keys past the end get no weight (a zero key row would get exp(-shift) > 0)."""
+    print(f"case fp8-all softmax twin B={B} H={H} N={N}", flush=True)
+    qf, kf, vf = si.gaussian_qkv(B, H, N, 128, seed=950 + N, factor=0.5)
+    q, k, v = (t.to(torch.float8_e4m3fn) for t in (qf, kf, vf))
+    ws = torch.empty(pkg.sphattn_fp8_workspace_bytes(B, H, N, 128), dtype=torch.uint8, device=DEV)
+    out = pkg.sphattn_fp8_softmax_fwd(q.to(DEV), k.to(DEV), v.to(DEV), ws)
+    torch.cuda.synchronize()
+    got = out.cpu().to(torch.float64).numpy()
+    ref = oracle.softmax_attention(*_bits(q, k, v), kinds=("e4m3fn",) * 3)
+    assert np.all(np.isfinite(got))
+    rms = np.sqrt((ref ** 2).mean())
+    err = got - ref
+    err_rms, err_max = np.sqrt((err ** 2).mean()) / rms, np.abs(err).max() / rms
+    print(f"softmax twin vs oracle: rms {err_rms:.3e} max {err_max:.3e}", flush=True)
+    assert err_rms <= TOL_EXACT_RMS and err_max <= TOL_EXACT_MAX
