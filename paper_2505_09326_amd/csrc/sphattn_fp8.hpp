@@ -158,7 +158,7 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     constexpr int BUF_BYTES = 2 * KTILE;
     constexpr int NBUF = 4;
     constexpr int SLOTS = 8;                       // per tile: block rows kb = V^T fragments db
-    constexpr int PD = 2;                          // LDS prefetch distance in slots
+    constexpr int PD = 2;                          // LDS prefetch distance in slots (measured best of 1, 2, 3)
     constexpr int RING = 4;
     constexpr int NCOPY = 8;                       // 1 KB copies per wave per tile: 4 of K, 4 of V^T
     static_assert((2 * SLOTS) % RING == 0 && PD < RING, "ring indices must repeat");
