@@ -74,6 +74,10 @@ typedef enum {
  * Returns SPHATTN_OK or a negative SPHATTN_ERR_* code; on error nothing is
  * enqueued and O is untouched.  Never throws or aborts.
  *
+ * Range: scores and the row aggregates are fp32 on the device, so sum_j s_ij^2 must stay below
+ * the fp32 maximum (3.4e38); beyond that a row comes out as zeros or NaN.  Inputs are expected
+ * to be finite.
+ *
  * 16-bit launches use workgroups of 256 query rows, or of 128 when 256-row tiles would
  * leave CUs without work.  The environment variable SPHATTN_TILE_ROWS=128 or =256, read at
  * every call, overrides that choice (for tests and measurements); the result is the same
