@@ -274,21 +274,23 @@ int sphattn_grn_bwd(const void* Q, const void* K, const void* V, const float* mu
  * the quotient).  The result carries the relative error of a 3-bit mantissa on every term
  * of the sum: about 2.7 % of rms(O) in the root mean square and up to about 15 % of rms(O) on
  * single elements, not the 2^-9 of the 16-bit paths.
- *   Q, K, V  : device, [B,H,N,d] contiguous, one byte per element (E4M3, finite values),
+ *   Q        : device, [B,H,N,d] contiguous, one byte per element (E4M3, finite values),
  *              16-byte aligned.  d must be 128 (anything else: SPHATTN_ERR_HEAD_DIM).
+ *   K, V     : the same with H_kv heads, [B,H_kv,N,d]; H_kv divides H, and query head h reads
+ *              K/V head h / (H / H_kv) (Appendix A.2); H_kv == H: no sharing.
  *   O        : device, [B,H,N,d] bfloat16, written by the call, must not overlap the inputs.
  *   workspace: device scratch owned by the caller, 16-byte aligned, at least
- *              sphattn_fp8_workspace_bytes(B, H, N, d) bytes (a transposed copy of V padded to
- *              whole 128-key tiles, and the largest key norm of every head); overwritten by the
+ *              sphattn_fp8_workspace_bytes(B, H_kv, N, d) bytes (a transposed copy of V padded
+ *              to whole 128-key tiles, and the largest key norm of every K/V head); overwritten by the
  *              call, must not overlap Q, K, V or O.  A NULL, misaligned or short workspace
  *              returns SPHATTN_ERR_WORKSPACE.  Calls that share a workspace must be ordered.
  * Three launches on `stream` (clear, prepare, attention); no allocation, no synchronisation.
  * Other errors as sphattn_fwd.  sphattn_fp8_workspace_bytes returns 0 for an invalid shape.
  */
-size_t sphattn_fp8_workspace_bytes(int B, int H, int N, int d);
+size_t sphattn_fp8_workspace_bytes(int B, int H_kv, int N, int d);
 int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O,
                     void* workspace, size_t workspace_bytes,
-                    int B, int H, int N, int d, void* stream);
+                    int B, int H, int H_kv, int N, int d, void* stream);
 
 /*
  * Comparison twin of sphattn_fp8_fwd: O = softmax(Q K^T / sqrt(d)) V with the same storage, the
@@ -302,7 +304,7 @@ int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O,
  */
 int sphattn_fp8_softmax_fwd(const void* Q, const void* K, const void* V, void* O,
                             void* workspace, size_t workspace_bytes,
-                            int B, int H, int N, int d, void* stream);
+                            int B, int H, int H_kv, int N, int d, void* stream);
 
 /*
  * Measurement aid, not part of the method: one launch (256 workgroups of 256 threads, one per

@@ -79,7 +79,7 @@ def load_library() -> ctypes.CDLL:
         for name in ("sphattn_fp8_fwd", "sphattn_fp8_softmax_fwd"):
             fn = getattr(lib, name)
             fn.restype = ip
-            fn.argtypes = [vp, vp, vp, vp, vp, ctypes.c_size_t, ip, ip, ip, ip, vp]
+            fn.argtypes = [vp, vp, vp, vp, vp, ctypes.c_size_t, ip, ip, ip, ip, ip, vp]
         lib.sphattn_mfma_probe.restype = ip
         lib.sphattn_mfma_probe.argtypes = [vp, vp, ip, ip, vp]
         lib.sphattn_strerror.restype = ctypes.c_char_p
@@ -296,8 +296,9 @@ def sphattn_splitkv_fwd(Q, K, V, workspace, mult=None, O=None, Z=None, n_splits=
     return O
 
 
-def sphattn_fp8_workspace_bytes(B, H, N, d) -> int:
-    return int(load_library().sphattn_fp8_workspace_bytes(B, H, N, d))
+def sphattn_fp8_workspace_bytes(B, H_kv, N, d) -> int:
+    """Workspace of sphattn_fp8_fwd for K, V of shape [B,H_kv,N,d]."""
+    return int(load_library().sphattn_fp8_workspace_bytes(B, H_kv, N, d))
 
 
 def sphattn_fp8_softmax_fwd(Q, K, V, workspace, O=None, stream=None):
@@ -307,9 +308,9 @@ def sphattn_fp8_softmax_fwd(Q, K, V, workspace, O=None, stream=None):
 
 
 def sphattn_fp8_fwd(Q, K, V, workspace, O=None, stream=None, _entry="sphattn_fp8_fwd"):
-    """Spherical attention with Q, K and V all stored in E4M3 (float8_e4m3fn tensors [B,H,N,128])
-    and both contractions on the fp8 matrix instructions; O is bfloat16.  `workspace` is a
-    device byte tensor of at least sphattn_fp8_workspace_bytes(...)."""
+    """Spherical attention with Q [B,H,N,128], K and V [B,H_kv,N,128] all stored in E4M3
+    (float8_e4m3fn tensors) and both contractions on the fp8 matrix instructions; O is bfloat16.
+    `workspace` is a device byte tensor of at least sphattn_fp8_workspace_bytes(B, H_kv, N, 128)."""
     import torch
     lib = load_library()
     if O is None:
@@ -317,7 +318,7 @@ def sphattn_fp8_fwd(Q, K, V, workspace, O=None, stream=None, _entry="sphattn_fp8
     _check_device("Q, K, V, O, workspace", Q, K, V, O, workspace)
     B, H, N, d = Q.shape
     rc = getattr(lib, _entry)(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), workspace.data_ptr(),
-                              workspace.numel() * workspace.element_size(), B, H, N, d,
+                              workspace.numel() * workspace.element_size(), B, H, K.shape[1], N, d,
                               ctypes.c_void_p(_stream_of(Q, stream)))
     if rc != 0:
         raise SphattnError(rc, sphattn_strerror(rc))

@@ -493,31 +493,31 @@ int sphattn_bwd(const void* Q, const void* K, const void* V, const void* O, cons
     return sphattn_grn_bwd(Q, K, V, nullptr, O, dO, Z, dQ, dK, dV, delta, B, H, H, N, d, dtype, stream);
 }
 
-size_t sphattn_fp8_workspace_bytes(int B, int H, int N, int d)
+size_t sphattn_fp8_workspace_bytes(int B, int H_kv, int N, int d)
 {
-    if (B <= 0 || H <= 0 || N <= 0 || d != kFp8D) return 0;
+    if (B <= 0 || H_kv <= 0 || N <= 0 || d != kFp8D) return 0;
     const size_t tiles = ((size_t)N + kFp8Tile - 1) / kFp8Tile;
-    return (size_t)B * H * d * tiles * kFp8Tile + (((size_t)B * H * 4 + 255) & ~(size_t)255);
+    return (size_t)B * H_kv * d * tiles * kFp8Tile + (((size_t)B * H_kv * 4 + 255) & ~(size_t)255);
 }
 
 static int fp8_forward(const void* Q, const void* K, const void* V, void* O, void* workspace,
-                       size_t workspace_bytes, int B, int H, int N, int d, void* stream, bool softmax)
+                       size_t workspace_bytes, int B, int H, int H_kv, int N, int d, void* stream, bool softmax)
 {
     if (d != kFp8D) return SPHATTN_ERR_HEAD_DIM;
     if (!Q || !K || !V || !O) return SPHATTN_ERR_NULL;
-    const int rc = check_shape(B, H, H, N, N, d, SPHATTN_FP8QK_BF16V);
+    const int rc = check_shape(B, H, H_kv, N, N, d, SPHATTN_FP8QK_BF16V);
     if (rc != SPHATTN_OK) return rc;
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return SPHATTN_ERR_ALIGN;
-    const size_t in_bytes = (size_t)B * H * N * d;
-    if (overlaps(O, in_bytes * 2, Q, in_bytes) || overlaps(O, in_bytes * 2, K, in_bytes) ||
-        overlaps(O, in_bytes * 2, V, in_bytes))
+    const size_t in_bytes = (size_t)B * H * N * d, kv_bytes = (size_t)B * H_kv * N * d;
+    if (overlaps(O, in_bytes * 2, Q, in_bytes) || overlaps(O, in_bytes * 2, K, kv_bytes) ||
+        overlaps(O, in_bytes * 2, V, kv_bytes))
         return SPHATTN_ERR_ALIAS;
-    const size_t need = sphattn_fp8_workspace_bytes(B, H, N, d);
+    const size_t need = sphattn_fp8_workspace_bytes(B, H_kv, N, d);
     if (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < need) return SPHATTN_ERR_WORKSPACE;
-    if (overlaps(workspace, need, Q, in_bytes) || overlaps(workspace, need, K, in_bytes) ||
-        overlaps(workspace, need, V, in_bytes) || overlaps(workspace, need, O, in_bytes * 2))
+    if (overlaps(workspace, need, Q, in_bytes) || overlaps(workspace, need, K, kv_bytes) ||
+        overlaps(workspace, need, V, kv_bytes) || overlaps(workspace, need, O, in_bytes * 2))
         return SPHATTN_ERR_ALIAS;
-    const int heads = B * H;
+    const int heads = B * H_kv;                    // K/V heads: what the preparation pass covers
     const int n_tiles = (N + kFp8Tile - 1) / kFp8Tile;
     const size_t kmax_bytes = ((size_t)heads * 4 + 255) & ~(size_t)255;
     float* kmax = (float*)workspace;
@@ -532,24 +532,24 @@ static int fp8_forward(const void* Q, const void* K, const void* V, void* O, voi
     auto kern = softmax ? fwd_fp8_kernel<true> : fwd_fp8_kernel<false>;
     if (!raise_lds_limit(kern, lds_bytes, softmax ? done_twin : done)) return SPHATTN_ERR_LAUNCH;
     const int n_qtiles = (N + 255) / 256;
-    const long long n_wg = (long long)heads * n_qtiles;
+    const long long n_wg = (long long)B * H * n_qtiles;
     if (n_wg > 0x7fffffff) return SPHATTN_ERR_SHAPE;
     hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, st,
                        (const unsigned char*)Q, (const unsigned char*)K, (const unsigned char*)VT,
-                       (const float*)kmax, (unsigned short*)O, N, n_tiles, n_qtiles, (int)n_wg);
+                       (const float*)kmax, (unsigned short*)O, N, H, H / H_kv, n_tiles, n_qtiles, (int)n_wg);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
 int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O, void* workspace,
-                    size_t workspace_bytes, int B, int H, int N, int d, void* stream)
+                    size_t workspace_bytes, int B, int H, int H_kv, int N, int d, void* stream)
 {
-    return fp8_forward(Q, K, V, O, workspace, workspace_bytes, B, H, N, d, stream, false);
+    return fp8_forward(Q, K, V, O, workspace, workspace_bytes, B, H, H_kv, N, d, stream, false);
 }
 
 int sphattn_fp8_softmax_fwd(const void* Q, const void* K, const void* V, void* O, void* workspace,
-                            size_t workspace_bytes, int B, int H, int N, int d, void* stream)
+                            size_t workspace_bytes, int B, int H, int H_kv, int N, int d, void* stream)
 {
-    return fp8_forward(Q, K, V, O, workspace, workspace_bytes, B, H, N, d, stream, true);
+    return fp8_forward(Q, K, V, O, workspace, workspace_bytes, B, H, H_kv, N, d, stream, true);
 }
 
 int sphattn_mfma_probe(const void* operands, long long* clocks, int form, int iters, void* stream)

@@ -150,7 +150,7 @@ template <bool SOFTMAX>
 __global__ __launch_bounds__(kThreads, 1)
 void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __restrict__ K,
                     const unsigned char* __restrict__ VT, const float* __restrict__ kmax,
-                    unsigned short* __restrict__ O, int N, int n_tiles, int n_qtiles, int n_wg)
+                    unsigned short* __restrict__ O, int N, int H, int kv_group, int n_tiles, int n_qtiles, int n_wg)
 {
     constexpr int D = kFp8D, BC = kFp8Tile, NQ = 4;
     constexpr int BR = kWaves * 16 * NQ;
@@ -172,6 +172,9 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
 
     const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
     const int qt = lid % n_qtiles, bh = lid / n_qtiles;
+    // kv_group query heads share one K/V head (and its V^T copy and key-norm maximum); the heads
+    // of a group are adjacent in the workgroup order, so they meet in one L2
+    const int kvh = (bh / H) * (H / kv_group) + (bh % H) / kv_group;
     const size_t Np = (size_t)n_tiles * BC;
     const unsigned char* Qh = Q + (size_t)bh * N * D;
     const int q0 = qt * BR + wave * 16 * NQ;
@@ -196,7 +199,7 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     float qdiv[NQ];                                // 2^e_i: the scores of row i are divided by it on conversion
     float qshift[NQ];
     constexpr float kSoftmaxScaleLog2 = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
-    const float km = kmax[bh];
+    const float km = kmax[kvh];
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
         int row = q0 + qb * 16 + n16;
@@ -227,8 +230,8 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
 #pragma unroll
         for (int qb = 0; qb < NQ; ++qb) oacc[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const i32x4 krw = rsrc_words(K + (size_t)bh * N * D, (uint32_t)N * D);
-    const i32x4 vrw = rsrc_words(VT + (size_t)bh * D * Np, (uint32_t)(D * Np));
+    const i32x4 krw = rsrc_words(K + (size_t)kvh * N * D, (uint32_t)N * D);
+    const i32x4 vrw = rsrc_words(VT + (size_t)kvh * D * Np, (uint32_t)(D * Np));
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     // copy c of this wave's share of tile `tile` into buffer `buf`: c < 4 K, else V^T.  K rows
     // past the end of the head are out of the descriptor's range and arrive as zeros.

@@ -231,10 +231,12 @@ def test_fp8_argument_errors_and_workspace_size(lib):
     assert wsb(1, 1, 128, 64) == 0 and wsb(0, 1, 128, 128) == 0 and wsb(1, 1, 0, 128) == 0
     need = wsb(1, 2, 1000, 128)
 
-    def call(Q=0x1000000, K=0x2000000, V=0x3000000, O=0x4000000, ws=0x40000000, size=need, B=1, H=2, N=1000, d=128):
-        return lib.sphattn_fp8_fwd(P(Q), P(K), P(V), P(O), P(ws), size, B, H, N, d, None)
+    def call(Q=0x1000000, K=0x2000000, V=0x3000000, O=0x4000000, ws=0x40000000, size=need, B=1, H=2, H_kv=2,
+             N=1000, d=128):
+        return lib.sphattn_fp8_fwd(P(Q), P(K), P(V), P(O), P(ws), size, B, H, H_kv, N, d, None)
     assert call(Q=0) == -1 and call(K=0) == -1 and call(V=0) == -1 and call(O=0) == -1
-    assert call(N=0) == -2 and call(H=0) == -2
+    assert call(N=0) == -2 and call(H=0) == -2 and call(H=3, H_kv=2) == -2
+    assert call(H=4, H_kv=2, size=wsb(1, 2, 1000, 128) - 1) == -9   # the workspace is sized by H_kv
     assert call(d=64) == -3 and call(d=96) == -3           # d = 128 only
     assert call(V=0x3000008) == -5
     assert call(O=0x1000000) == -7                         # O is Q
@@ -244,8 +246,8 @@ def test_fp8_argument_errors_and_workspace_size(lib):
     assert call(ws=0x4000000 + 4096) == -7                 # workspace inside O
     # the SoftMax twin shares the checks
     twin = lib.sphattn_fp8_softmax_fwd
-    assert twin(P(0x1000000), P(0x2000000), P(0x3000000), P(0x4000000), P(0x40000000), need - 1, 1, 2, 1000, 128, None) == -9
-    assert twin(P(0x1000000), P(0x2000000), P(0x3000000), P(0x4000000), P(0x40000000), need, 1, 2, 1000, 64, None) == -3
+    assert twin(P(0x1000000), P(0x2000000), P(0x3000000), P(0x4000000), P(0x40000000), need - 1, 1, 2, 2, 1000, 128, None) == -9
+    assert twin(P(0x1000000), P(0x2000000), P(0x3000000), P(0x4000000), P(0x40000000), need, 1, 2, 2, 1000, 64, None) == -3
 
 
 def test_mfma_probe_argument_errors(lib):

@@ -45,7 +45,7 @@ def oracle():
 
 def _run(pkg, q, k, v, slack=0):
     B, H, N, d = q.shape
-    ws = torch.empty(pkg.sphattn_fp8_workspace_bytes(B, H, N, d) + slack, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(pkg.sphattn_fp8_workspace_bytes(B, k.shape[1], N, d) + slack, dtype=torch.uint8, device=DEV)
     out = pkg.sphattn_fp8_fwd(q.to(DEV), k.to(DEV), v.to(DEV), ws)
     torch.cuda.synchronize()
     return out.cpu().to(torch.float64).numpy()
@@ -113,6 +113,19 @@ def test_fp8_all_rows_of_very_different_norm(pkg, oracle):
     k[:, :, 17] *= 12.0
     q, k, v = si.cast_storage(q, k, v, "fp8")
     _check(oracle, _run(pkg, q, k, v), q, k, v)
+
+
+@pytest.mark.parametrize("B,H,H_kv,N", [(1, 4, 2, 300), (2, 6, 1, 129), (1, 8, 4, 1000)])
+def test_fp8_all_shared_kv_heads(pkg, oracle, B, H, H_kv, N):
+    """Query head h reads K/V head h / (H / H_kv): against the oracle on K, V repeated per group."""
+    print(f"case fp8-all shared heads B={B} H={H} H_kv={H_kv} N={N}", flush=True)
+    q, _, _ = si.make_qkv(B, H, N, 128, "fp8", seed=970 + N)
+    _, k, v = si.make_qkv(B, H_kv, N, 128, "fp8", seed=980 + N)
+    got = _run(pkg, q, k, v)
+    rep = H // H_kv
+    k_full = k.view(torch.uint8).repeat_interleave(rep, dim=1).view(torch.float8_e4m3fn)
+    v_full = v.view(torch.uint8).repeat_interleave(rep, dim=1).view(torch.float8_e4m3fn)
+    _check(oracle, got, q, k_full, v_full)
 
 
 def test_fp8_all_degenerate_rows(pkg, oracle):
