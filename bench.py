@@ -46,6 +46,27 @@ def time_launches(fn, steps, warmup):
     return wall_ms / steps, per
 
 
+def load_mfma_probe():
+    """bench_mfma_probe of libbench_mfma_probe.so (built by __graft_entry__.build()): loops of
+    matrix instructions only, the benchmark's own measurement aid."""
+    import ctypes
+    path = os.path.join(ROOT, "libbench_mfma_probe.so")
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+    fn = ctypes.CDLL(path).bench_mfma_probe
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+
+    def probe(operands, clocks, form, iters):
+        import torch
+        rc = fn(operands.data_ptr(), clocks.data_ptr(), int(form), int(iters),
+                ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if rc != 0:
+            raise RuntimeError(f"bench_mfma_probe returned {rc}")
+        return 256.0 * 4 * iters * 16 * 32768.0    # flop of the launch
+    return probe
+
+
 def cpu_baseline(w, q, k, v, budget_s=12.0):
     """The fp64 oracle, as it stands, on a bounded sample: whole heads of the workload, one
     after the other, until about `budget_s` seconds of CPU time have been spent."""
@@ -226,6 +247,7 @@ def main() -> int:
         ops = torch.randn(32768, generator=g, dtype=torch.float32).to(torch.bfloat16).to(dev)
         clk = torch.zeros(3, dtype=torch.int64, device=dev)
         ceil = {}
+        mfma_probe = load_mfma_probe()
         ops8 = si.to_e4m3fn(torch.randn(65536, generator=g, dtype=torch.float32)).view(torch.uint8).to(dev)
         for form, name in ((0, "32x32x16_bf16"), (1, "16x16x32_bf16"), (2, "16x16x128_e4m3"),
                            (3, "16x16x128_e4m3_with_l2_stage_b_mix"), (4, "16x16x128_e4m3_with_softmax_stage_b_mix")):
@@ -235,11 +257,11 @@ def main() -> int:
                     continue
                 ops = ops8
             for _ in range(2):
-                flop = pkg.sphattn_mfma_probe(ops, clk, form, iters)
+                flop = mfma_probe(ops, clk, form, iters)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            flop = pkg.sphattn_mfma_probe(ops, clk, form, iters)
+            flop = mfma_probe(ops, clk, form, iters)
             e1.record()
             torch.cuda.synchronize()
             c = clk.cpu().tolist()

@@ -79,9 +79,7 @@ typedef enum {
  * to be finite.
  *
  * 16-bit launches use workgroups of 256 query rows, or of 128 when 256-row tiles would
- * leave CUs without work.  The environment variable SPHATTN_TILE_ROWS=128 or =256, read at
- * every call, overrides that choice (for tests and measurements); the result is the same
- * function of the inputs either way.
+ * leave compute units without work (sphattn_fwd_tile_rows forces either shape).
  */
 int sphattn_fwd(const void* Q, const void* K, const void* V, void* O,
                 int B, int H, int N, int d, int dtype, void* stream);
@@ -96,6 +94,17 @@ int sphattn_fwd(const void* Q, const void* K, const void* V, void* O,
  */
 int sphattn_fwd_z(const void* Q, const void* K, const void* V, void* O, float* Z,
                   int B, int H, int N, int d, int dtype, void* stream);
+
+/*
+ * sphattn_fwd_z with the workgroup shape of the 16-bit kernels forced, for tests and
+ * measurements of both shapes on one problem (same definition as sphattn_fwd; the two shapes
+ * add the same terms in different order):
+ *   tile_rows : 0 = the library's choice (then this is sphattn_fwd_z), 128 or 256 query rows
+ *               per workgroup; anything else returns SPHATTN_ERR_SHAPE.  Ignored where only
+ *               one shape exists (fp32, fp16 and fp8-Q/K storage).
+ */
+int sphattn_fwd_tile_rows(const void* Q, const void* K, const void* V, void* O, float* Z,
+                          int B, int H, int N, int d, int dtype, int tile_rows, void* stream);
 
 /*
  * Gene-regulatory-network variant (paper, Section 3.1 and Appendix A.2).  Tokens are genes;
@@ -199,7 +208,8 @@ int sphattn_combine(const float* o_parts, const float* z_parts, int n_parts, voi
  * B * H * N / 256 is below the number of compute units, i.e. few heads of moderate length.
  *
  *   n_splits       : slices asked for; 0 lets sphattn_splitkv_heuristic choose.  Slices are
- *                    whole 64-key tiles of equal size, so fewer than asked may be used.
+ *                    whole 64-key tiles of equal size, so fewer than asked may be used (any
+ *                    count above the number of tiles means one tile per slice).
  *   workspace      : device scratch, 16-byte aligned, at least
  *                    sphattn_splitkv_workspace_bytes(B,H,N,d,n_splits) bytes (n_splits as passed
  *                    here, or the heuristic's value when 0); contents undefined afterwards.
@@ -218,8 +228,8 @@ int sphattn_splitkv_fwd(const void* Q, const void* K, const void* V, const float
 size_t sphattn_splitkv_workspace_bytes(int B, int H, int N, int d, int n_splits);
 
 /* Number of slices sphattn_splitkv_fwd uses when asked for 0: 1 when whole-key-axis workgroups
- * already cover the compute units, otherwise enough to cover them with slices of at least
- * 8 tiles.  Host-only arithmetic. */
+ * already cover the compute units of the current device (256 when no device can be asked),
+ * otherwise enough to cover them with slices of at least 8 tiles.  Launches nothing. */
 int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype);
 
 /*
@@ -305,29 +315,6 @@ int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O,
 int sphattn_fp8_softmax_fwd(const void* Q, const void* K, const void* V, void* O,
                             void* workspace, size_t workspace_bytes,
                             int B, int H, int H_kv, int N, int d, void* stream);
-
-/*
- * Measurement aid, not part of the method: one launch (256 workgroups of 256 threads, one per
- * CU) of a loop of nothing but matrix instructions, to measure what the matrix pipes
- * sustain on given operand values next to the attention kernels (on random data the part is
- * power-bound well below its nominal peak).
- *   operands : 64 KB of device memory, 16-byte aligned, read as operand values (bfloat16 for
- *              forms 0 and 1, E4M3 bytes for forms 2 to 4).
- *   clocks   : 3 int64 on the device, 8-byte aligned; receives {shader clocks, 100 MHz reference
- *              ticks} spent in the loop by workgroup 0 (the third is scratch).
- *   form     : 0 = v_mfma_f32_32x32x16_bf16 (16 per iteration), 1 = v_mfma_f32_16x16x32_bf16 (32 per
- *              iteration), 2 = v_mfma_f32_16x16x128_f8f6f4 on E4M3 (8 per iteration); in every
- *              form 256 * 4 waves * iters * 16 * 32768 flop per launch.  Forms 3 and 4 are form 2
- *              with, pinned behind every matrix instruction, the other instructions that one wave
- *              of an all-E4M3 attention kernel issues per matrix instruction: a 16-byte LDS read
- *              and, 3: one scaled convert and two register moves (L2 normaliser); 4: scale-and-
- *              shift, exponential, running max and sum for two scores and one convert (SoftMax,
- *              without its cross-lane maximum and rescaling).  Their ratio is what the
- *              exponential costs at the fp8 matrix rate (paper, Section 1).
- *   iters    : 1 .. 2^24.
- * Errors: SPHATTN_ERR_NULL, SPHATTN_ERR_SHAPE (form, iters), SPHATTN_ERR_ALIGN, SPHATTN_ERR_LAUNCH.
- */
-int sphattn_mfma_probe(const void* operands, long long* clocks, int form, int iters, void* stream);
 
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* sphattn_strerror(int code);

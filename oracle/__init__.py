@@ -294,51 +294,6 @@ def spherical_tail(o_parts, z_parts) -> np.ndarray:
     return out
 
 
-def round_to_e4m3(x: np.ndarray) -> np.ndarray:
-    """Nearest OCP E4M3 value (ties to even) of every element of the fp64 array x, |x| <= 448:
-    three mantissa bits, least normal exponent -6, subnormals in steps of 2^-9."""
-    x = np.asarray(x, dtype=np.float64)
-    ax = np.abs(x)
-    if ax.size and ax.max() > 448.0:
-        raise ValueError("outside the E4M3 range")
-    _, ex = np.frexp(ax)                       # ax = m 2^ex with m in [0.5, 1): leading bit is 2^(ex-1)
-    lead = np.maximum(ex - 1, -6)              # subnormals share the exponent of the least normal
-    step = np.ldexp(1.0, lead - 3)
-    return np.copysign(np.rint(ax / step) * step, x)
-
-
-def e4m3_row_exponents(Q, K) -> np.ndarray:
-    """The power of two by which the all-E4M3 variant divides the scores of row i before it
-    rounds them: e_i with |q_i| max_j |k_j| / 440 = m 2^e_i, m in [0.5, 1) (e_i = 0 for a zero
-    bound).  By Cauchy-Schwarz every score of the row, divided by 2^e_i, is within +-440.
-    Q, K fp64 [B,H,N,d]; returns (e [B,H,N] int, m [B,H,N])."""
-    qn = np.sqrt((Q * Q).sum(-1))
-    kmax = np.sqrt((K * K).sum(-1)).max(-1)
-    bound = qn * kmax[..., None]
-    m, e = np.frexp(bound / 440.0)
-    e = np.where(bound > 0.0, e, 0)
-    return e, m
-
-
-def spherical_attention_e4m3_scores(Q, K, V, kinds=None) -> np.ndarray:
-    """Model of the all-E4M3 variant of spherical attention (not in the paper; the variant
-    follows from the paper's remark, Section 1 and Section 3.1, that nothing but matrix products
-    is left): the scores of row i are divided by 2^e_i (e4m3_row_exponents) and rounded to
-    E4M3, and O_i = (sum_j p_ij v_j) / sqrt(sum_j p_ij^2) is formed from the ROUNDED scores
-    p_ij in fp64.  The row factor cancels in the quotient."""
-    kq, kk, kv = kinds if kinds is not None else (None, None, None)
-    Q, K, V = widen(Q, kq), widen(K, kk), widen(V, kv)
-    e, _ = e4m3_row_exponents(Q, K)
-    S = np.matmul(Q, np.swapaxes(K, -1, -2))
-    P = round_to_e4m3(S * np.ldexp(1.0, -e)[..., None])
-    o = np.matmul(P, V)
-    z = (P * P).sum(-1)
-    out = np.zeros_like(o)
-    nz = z > 0.0
-    out[nz] = o[nz] / np.sqrt(z[nz])[:, None]
-    return out
-
-
 def spherical_attention_bwd(Q, K, V, dO, kinds=None):
     """Gradients (dQ, dK, dV), fp64 [B,H,N,d], of sum(O * dO) for spherical attention O(Q, K, V);
     kinds = (q, k, v, dO) stored formats."""

@@ -20,6 +20,9 @@ class _SphericalAttention(torch.autograd.Function):
     def forward(ctx, Q, K, V, mult):
         if Q.dtype not in _DTYPES or K.dtype != Q.dtype or V.dtype != Q.dtype:
             raise TypeError("spherical_attention differentiates bf16 or fp16 tensors of one dtype")
+        if Q.dim() != 4 or K.dim() != 4 or K.shape[2] != Q.shape[2]:
+            # the backward kernels are self-attention only; catch it before anything is launched
+            raise ValueError(f"spherical_attention needs K, V with Q's N: Q {tuple(Q.shape)}, K {tuple(K.shape)}")
         dtype = _DTYPES[Q.dtype]
         Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
         plain = mult is None and K.shape[1] == Q.shape[1]

@@ -9,7 +9,6 @@
 #include "../../include/sphattn.h"
 
 #include <stdint.h>
-#include <stdlib.h>
 
 #include <atomic>
 
@@ -19,10 +18,18 @@ using namespace sphattn;
 
 constexpr int kVersion = 500;   // 0.5.0
 
+// [a, a+an) and [b, b+bn) share a byte.  Written with differences, so that a range reaching the
+// top of the address space cannot wrap the comparison.
 bool overlaps(const void* a, size_t an, const void* b, size_t bn)
 {
-    uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
-    return a0 < b0 + bn && b0 < a0 + an;
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 <= b0 ? b0 - a0 < an : a0 - b0 < bn;
+}
+
+// a buffer of `bytes` bytes at p would run past the end of the address space
+bool wraps(const void* p, size_t bytes)
+{
+    return (uintptr_t)p + bytes < (uintptr_t)p;
 }
 
 int check_shape(int B, int H, int H_kv, int Nq, int Nk, int d, int dtype)
@@ -55,6 +62,9 @@ int check_args(const void* Q, const void* K, const void* V, const void* out, siz
     const size_t qk = dtype == SPHATTN_F32 ? 4 : dtype == SPHATTN_FP8QK_BF16V ? 1 : 2;
     const size_t vo = dtype == SPHATTN_F32 ? 4 : 2;
     const size_t zb = (size_t)B * H * Nq * 4;
+    if (wraps(out, out_bytes) || wraps(Q, nq * qk) || wraps(K, nkv * qk) || wraps(V, nkv * vo) ||
+        (Z && wraps(Z, zb)) || (mult && wraps(mult, (size_t)B * Nk * 4)))
+        return SPHATTN_ERR_SHAPE;
     if (overlaps(out, out_bytes, Q, nq * qk) || overlaps(out, out_bytes, K, nkv * qk) ||
         overlaps(out, out_bytes, V, nkv * vo) ||
         (mult && overlaps(out, out_bytes, mult, (size_t)B * Nk * 4)))
@@ -99,6 +109,7 @@ struct Problem {
     int B, H, H_kv, Nq, Nk;
     hipStream_t stream;
     int n_splits = 1, keys_per_split = 0;
+    int tile_rows = 0;          // query rows per workgroup: 0 = the library's choice, else 128 or 256
 };
 
 // Key slices are whole 64-key tiles.  Asking for more slices than there are tiles, or for a
@@ -107,9 +118,31 @@ struct Problem {
 struct SplitPlan { int n_splits, keys_per_split; };
 SplitPlan plan_splits(int Nk, int requested)
 {
-    const int tiles = (Nk + kBC - 1) / kBC;
-    const int per = (tiles + requested - 1) / requested;
+    const int tiles = (int)(((long long)Nk + kBC - 1) / kBC);   // >= 1: every caller has checked Nk >= 1
+    requested = requested < 1 ? 1 : requested > tiles ? tiles : requested;
+    const int per = (tiles + requested - 1) / requested;   // >= 1, and no overflow: requested <= tiles
     return SplitPlan{(tiles + per - 1) / per, per * kBC};
+}
+
+// Compute units of the current device, asked once per device; 256 (MI355X) when there is no
+// device to ask.
+long long cu_count()
+{
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n <= 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            return 256;
+        }
+        cached[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
 }
 
 template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
@@ -174,12 +207,8 @@ int launch_softmax32(const Problem& p)
 // not justify it, because the part is power-bound and idle CUs give their share to the rest.
 bool narrow_tiles_pay(const Problem& p)
 {
-    if (const char* e = getenv("SPHATTN_TILE_ROWS")) {
-        if (e[0] == '1' && e[1] == '2' && e[2] == '8' && !e[3]) return true;
-        if (e[0] == '2' && e[1] == '5' && e[2] == '6' && !e[3]) return false;
-    }
-    constexpr long long kCus = 256;
-    return (long long)p.B * p.H * ((p.Nq + 255) / 256) < kCus;
+    if (p.tile_rows != 0) return p.tile_rows == 128;
+    return (long long)p.B * p.H * ((p.Nq + 255) / 256) < cu_count();
 }
 
 template <Norm NORM, bool MULT>
@@ -314,9 +343,17 @@ int sphattn_fwd(const void* Q, const void* K, const void* V, void* O,
 int sphattn_fwd_z(const void* Q, const void* K, const void* V, void* O, float* Z,
                   int B, int H, int N, int d, int dtype, void* stream)
 {
+    return sphattn_fwd_tile_rows(Q, K, V, O, Z, B, H, N, d, dtype, 0, stream);
+}
+
+int sphattn_fwd_tile_rows(const void* Q, const void* K, const void* V, void* O, float* Z,
+                          int B, int H, int N, int d, int dtype, int tile_rows, void* stream)
+{
     const int rc = check_args(Q, K, V, O, out_bytes_of(B, H, N, d, dtype), nullptr, Z, B, H, H, N, N, d, dtype);
     if (rc != SPHATTN_OK) return rc;
-    const Problem p{Q, K, V, O, nullptr, Z, B, H, H, N, N, (hipStream_t)stream};
+    if (tile_rows != 0 && tile_rows != 128 && tile_rows != 256) return SPHATTN_ERR_SHAPE;
+    Problem p{Q, K, V, O, nullptr, Z, B, H, H, N, N, (hipStream_t)stream};
+    p.tile_rows = tile_rows;
     return dispatch<Norm::Spherical, false>(p, d, dtype);
 }
 
@@ -411,9 +448,9 @@ size_t sphattn_splitkv_workspace_bytes(int B, int H, int N, int d, int n_splits)
 int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype)
 {
     if (B <= 0 || H <= 0 || N <= 0 || (d != 64 && d != 128)) return 1;
-    constexpr long long kCus = 256;
+    const long long kCus = cu_count();
     const int rows_per_wg = dtype == SPHATTN_F32 ? 32 : 256;
-    const long long wg = (long long)B * H * ((N + rows_per_wg - 1) / rows_per_wg);
+    const long long wg = (long long)B * H * (((long long)N + rows_per_wg - 1) / rows_per_wg);
     if (wg >= kCus) return 1;
     // Half-filled launches run on 128-row workgroups instead (twice as many, 15-25 % slower per
     // row); two slices of 256-row workgroups beat that only when the combine step is small
@@ -421,7 +458,7 @@ int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype)
     if (dtype != SPHATTN_F32 && 2 * wg >= kCus && N < 16384) return 1;
     // enough slices to give every CU a workgroup, but no slice shorter than 8 tiles
     const long long want = (kCus + wg - 1) / wg;
-    const long long most = ((N + kBC - 1) / kBC + 7) / 8;
+    const long long most = (((long long)N + kBC - 1) / kBC + 7) / 8;
     const long long s = want < most ? want : most;
     return plan_splits(N, (int)(s < 1 ? 1 : s)).n_splits;
 }
@@ -524,16 +561,19 @@ static int fp8_forward(const void* Q, const void* K, const void* V, void* O, voi
     unsigned char* VT = (unsigned char*)workspace + kmax_bytes;
     hipStream_t st = (hipStream_t)stream;
     if ((long long)heads * n_tiles > 0x7fffffff) return SPHATTN_ERR_SHAPE;
-    hipLaunchKernelGGL(fp8_clear_kernel, dim3((heads + 255) / 256), dim3(256), 0, st, kmax, heads);
-    hipLaunchKernelGGL(fp8_prepare_kernel, dim3((unsigned)(heads * n_tiles)), dim3(256), 0, st,
-                       (const unsigned char*)K, (const unsigned char*)V, VT, kmax, N, n_tiles);
+    const int n_qtiles = (N + 255) / 256;
+    const long long n_wg = (long long)B * H * n_qtiles;
+    if (n_wg > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    // everything that can fail without a launch comes before the first launch
     constexpr int lds_bytes = 4 * 2 * kFp8Tile * kFp8D;
     static std::atomic<uint64_t> done{0}, done_twin{0};
     auto kern = softmax ? fwd_fp8_kernel<true> : fwd_fp8_kernel<false>;
     if (!raise_lds_limit(kern, lds_bytes, softmax ? done_twin : done)) return SPHATTN_ERR_LAUNCH;
-    const int n_qtiles = (N + 255) / 256;
-    const long long n_wg = (long long)B * H * n_qtiles;
-    if (n_wg > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    hipLaunchKernelGGL(fp8_clear_kernel, dim3((heads + 255) / 256), dim3(256), 0, st, kmax, heads);
+    if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
+    hipLaunchKernelGGL(fp8_prepare_kernel, dim3((unsigned)(heads * n_tiles)), dim3(256), 0, st,
+                       (const unsigned char*)K, (const unsigned char*)V, VT, kmax, N, n_tiles);
+    if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, st,
                        (const unsigned char*)Q, (const unsigned char*)K, (const unsigned char*)VT,
                        (const float*)kmax, (unsigned short*)O, N, H, H / H_kv, n_tiles, n_qtiles, (int)n_wg);
@@ -550,29 +590,6 @@ int sphattn_fp8_softmax_fwd(const void* Q, const void* K, const void* V, void* O
                             size_t workspace_bytes, int B, int H, int H_kv, int N, int d, void* stream)
 {
     return fp8_forward(Q, K, V, O, workspace, workspace_bytes, B, H, H_kv, N, d, stream, true);
-}
-
-int sphattn_mfma_probe(const void* operands, long long* clocks, int form, int iters, void* stream)
-{
-    if (!operands || !clocks) return SPHATTN_ERR_NULL;
-    if (iters <= 0 || iters > (1 << 24) || form < 0 || form > 4) return SPHATTN_ERR_SHAPE;
-    if (((uintptr_t)operands & 15) || ((uintptr_t)clocks & 7)) return SPHATTN_ERR_ALIGN;
-    if (form == 0)
-        hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(256), dim3(256), 0, (hipStream_t)stream,
-                           (const i32x4*)operands, clocks, iters);
-    else if (form == 1)
-        hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(256), dim3(256), 0, (hipStream_t)stream,
-                           (const i32x4*)operands, clocks, iters);
-    else if (form == 2)
-        hipLaunchKernelGGL(mfma_probe_kernel<2>, dim3(256), dim3(256), 0, (hipStream_t)stream,
-                           (const i32x4*)operands, clocks, iters);
-    else if (form == 3)
-        hipLaunchKernelGGL(mfma_probe_kernel<3>, dim3(256), dim3(256), 0, (hipStream_t)stream,
-                           (const i32x4*)operands, clocks, iters);
-    else
-        hipLaunchKernelGGL(mfma_probe_kernel<4>, dim3(256), dim3(256), 0, (hipStream_t)stream,
-                           (const i32x4*)operands, clocks, iters);
-    return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
 const char* sphattn_strerror(int code)

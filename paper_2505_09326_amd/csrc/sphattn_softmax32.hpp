@@ -1,9 +1,13 @@
 // SoftMax attention on the 32x32x16 matrix instructions: the comparison twin in the form that
 // is fastest for SoftMax on gfx950 (bf16 storage only).
 //
-// Same tiles, LDS layout, three-stage pipeline, four rotating LDS buffers and one barrier per
-// 64-key tile as fwd_pipelined_kernel (sphattn_pipelined.hpp).  The difference is the matrix
-// instruction: a wavefront owns 64 query rows as two blocks of 32, scores are produced
+// Same tile sizes, three-stage pipeline, four rotating LDS buffers and one barrier per 64-key
+// tile as fwd_pipelined_kernel (sphattn_pipelined.hpp), but its own data path: tiles are
+// staged through registers (global load, ds_write) into row-major LDS rows padded against bank
+// conflicts, where the spherical kernel copies global -> LDS directly into unpadded fragment
+// blocks.  A timing ratio against the spherical kernel therefore contains that data-path
+// difference as well as the exponential; the like-for-like twin is the Norm::Softmax
+// instantiation of fwd_pipelined_kernel.  The matrix instruction differs too: a wavefront owns 64 query rows as two blocks of 32, scores are produced
 // transposed with v_mfma_f32_32x32x16_bf16 (lane l owns query column l & 31 and, in register
 // 4g+t, key row 8g + 4(l>>5) + t), and eight consecutive accumulator registers are one B
 // operand of O^T += V^T P^T.  The exponential is a quarter-rate instruction (16 cycles per

@@ -250,14 +250,50 @@ def test_fp8_argument_errors_and_workspace_size(lib):
     assert twin(P(0x1000000), P(0x2000000), P(0x3000000), P(0x4000000), P(0x40000000), need, 1, 2, 2, 1000, 64, None) == -3
 
 
-def test_mfma_probe_argument_errors(lib):
+def test_bench_probe_library_argument_errors():
+    """The matrix-instruction probe is the benchmark's own library, not part of the ABI."""
+    path = os.path.join(ROOT, "libbench_mfma_probe.so")
+    if not os.path.exists(path):
+        import __graft_entry__ as g
+        g.build_bench_probe()
+    probe = ctypes.CDLL(path).bench_mfma_probe
+    probe.restype = ctypes.c_int
+    probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     P = ctypes.c_void_p
-    assert lib.sphattn_mfma_probe(P(0), P(0x2000), 0, 10, None) == -1
-    assert lib.sphattn_mfma_probe(P(0x1000), P(0), 0, 10, None) == -1
-    assert lib.sphattn_mfma_probe(P(0x1000), P(0x2000), 5, 10, None) == -2
-    assert lib.sphattn_mfma_probe(P(0x1000), P(0x2000), 0, 0, None) == -2
-    assert lib.sphattn_mfma_probe(P(0x1008), P(0x2000), 0, 10, None) == -5
-    assert lib.sphattn_mfma_probe(P(0x1000), P(0x2004), 0, 10, None) == -5
+    assert probe(P(0), P(0x2000), 0, 10, None) == -1
+    assert probe(P(0x1000), P(0), 0, 10, None) == -1
+    assert probe(P(0x1000), P(0x2000), 5, 10, None) == -2
+    assert probe(P(0x1000), P(0x2000), 0, 0, None) == -2
+    assert probe(P(0x1008), P(0x2000), 0, 10, None) == -5
+    assert probe(P(0x1000), P(0x2004), 0, 10, None) == -5
+
+
+def test_no_measurement_probe_in_the_attention_library(lib):
+    assert not hasattr(lib, "sphattn_mfma_probe")
+
+
+def test_tile_rows_argument(lib):
+    P = ctypes.c_void_p
+
+    def call(tile_rows, Z=0):
+        return lib.sphattn_fwd_tile_rows(P(0x1000), P(0x2000000), P(0x4000000), P(0x6000000), P(Z),
+                                         1, 1, 128, 128, 1, tile_rows, None)
+    for bad in (-1, 1, 64, 129, 512):
+        assert call(bad) == -2
+    assert call(128, Z=0x6000000) == -7        # checks of sphattn_fwd_z apply: Z is O
+
+
+def test_splitkv_slice_counts_never_divide_by_zero(lib):
+    """Any n_splits >= 0 is accepted: more slices than 64-key tiles means one tile per slice.
+    (INT_MAX used to overflow the ceiling division and end the process with SIGFPE.)"""
+    P = ctypes.c_void_p
+    wsb = lib.sphattn_splitkv_workspace_bytes
+    N, d = 1024, 128                            # 16 tiles
+    for n_splits in (17, 1000, 2 ** 31 - 1):
+        rc = lib.sphattn_splitkv_fwd(P(0x1000), P(0x2000000), P(0x4000000), P(0), P(0x6000000), P(0),
+                                     1, 1, 1, N, d, 1, n_splits, P(0x10000000), wsb(1, 1, N, d, 16) - 1, None)
+        assert rc == -9                          # 16 slices planned: one byte short of their workspace
+    assert lib.sphattn_splitkv_heuristic(1, 1, 2 ** 31 - 1, 128, 1) >= 1
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -193,14 +193,13 @@ def test_splitkv_parity(pkg, oracle, B, H, H_kv, N, d, dtype, with_mult, n_split
     np.testing.assert_allclose(Z.cpu().double().numpy(), ref_z, rtol=Z_RTOL)
 
 
-def test_splitkv_single_slice_equals_unsplit_call(pkg, monkeypatch):
+def test_splitkv_single_slice_equals_unsplit_call(pkg):
     """One slice runs the same arithmetic in the same order as the unsplit 256-row kernel."""
-    monkeypatch.setenv("SPHATTN_TILE_ROWS", "256")
     B, H, N, d = 1, 3, 900, 128
     q, k, v = (t.to(DEV) for t in si.make_qkv(B, H, N, d, "bf16", seed=1300))
     ws, _ = _workspace(pkg, B, H, N, d, 1)
     a = pkg.sphattn_splitkv_fwd(q, k, v, ws, n_splits=1, dtype="bf16")
-    b = pkg.sphattn_fwd(q, k, v, dtype="bf16")
+    b, _ = pkg.sphattn_fwd_tile_rows(q, k, v, dtype="bf16", tile_rows=256)
     torch.cuda.synchronize()
     assert torch.equal(a, b)
 

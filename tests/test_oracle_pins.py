@@ -530,100 +530,3 @@ def test_grn_backward_against_central_differences_and_autograd(oracle):
     np.testing.assert_allclose(dQ, Qt.grad.numpy(), rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(dK, Kt.grad.numpy(), rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(dV, Vt.grad.numpy(), rtol=1e-10, atol=1e-12)
-
-
-# ---------------------------------------------------------------------------
-# Model of the all-E4M3 variant (scores rounded to E4M3 before the second contraction)
-# ---------------------------------------------------------------------------
-import torch  # noqa: E402  (library casts serve as the independent reference here)
-
-import synthetic_inputs as si  # noqa: E402
-
-def _e4m3_values():
-    """All finite E4M3 values, ascending, decoded by the library cast (not by the oracle)."""
-    codes = torch.arange(256, dtype=torch.uint8)
-    vals = codes.view(torch.float8_e4m3fn).to(torch.float64)
-    return np.unique(vals[torch.isfinite(vals)].numpy())
-
-
-def test_e4m3_rounding_fixed_points_midpoints_and_library_cast(oracle):
-    vals = _e4m3_values()
-    assert len(vals) == 253 and vals.max() == 448.0          # 2 * 126 non-zero magnitudes + zero
-    # every representable value is a fixed point
-    assert np.array_equal(oracle.round_to_e4m3(vals), vals)
-    # a midpoint goes to the neighbour whose code is even (ties to even); just off it, to the nearer
-    lo, hi = vals[:-1], vals[1:]
-    mid = 0.5 * (lo + hi)
-    codes = {float(v): int(c) for c, v in zip(range(256), torch.arange(256, dtype=torch.uint8)
-                                              .view(torch.float8_e4m3fn).to(torch.float64).tolist()) if v == v}
-    want = np.array([a if codes[float(a)] % 2 == 0 else b for a, b in zip(lo, hi)])
-    nonzero = (lo != 0) | (hi != 0)
-    assert np.array_equal(np.abs(oracle.round_to_e4m3(mid))[nonzero], np.abs(want)[nonzero])
-    eps = 1e-9 * (hi - lo)
-    assert np.array_equal(oracle.round_to_e4m3(mid - eps), lo)
-    assert np.array_equal(oracle.round_to_e4m3(mid + eps), hi)
-    # random values against the library's own cast
-    g = torch.Generator().manual_seed(11)
-    x = (torch.randn(100000, generator=g, dtype=torch.float64)
-         * torch.logspace(-4, 2.4, 100000, dtype=torch.float64)).clamp(-448, 448)
-    lib = x.to(torch.float32).to(torch.float8_e4m3fn).to(torch.float64).numpy()
-    assert np.array_equal(oracle.round_to_e4m3(x.numpy()), lib)
-    with pytest.raises(ValueError):
-        oracle.round_to_e4m3(np.array([449.0]))
-
-
-def test_e4m3_row_exponents_bound_the_scores(oracle):
-    rng = np.random.default_rng(5)
-    Q = rng.standard_normal((2, 2, 40, 16)) * np.exp(rng.standard_normal((2, 2, 40, 1)) * 3)
-    K = rng.standard_normal((2, 2, 40, 16)) * np.exp(rng.standard_normal((2, 2, 40, 1)))
-    Q[0, 0, 3] = 0.0
-    e, m = oracle.e4m3_row_exponents(Q, K)
-    S = Q @ np.swapaxes(K, -1, -2)
-    scaled = np.abs(S) * np.ldexp(1.0, -e)[..., None]
-    assert scaled.max() <= 440.0
-    # the exponent is the smallest that does it for the Cauchy-Schwarz bound
-    bound = np.sqrt((Q * Q).sum(-1)) * np.sqrt((K * K).sum(-1)).max(-1)[..., None]
-    nz = bound > 0
-    assert np.all(bound[nz] * np.ldexp(1.0, -e[nz]) > 220.0)
-    assert e[0, 0, 3] == 0
-
-
-def test_e4m3_model_close_to_exact_and_invariant_to_row_scaling(oracle):
-    q, k, v = si.make_qkv(1, 2, 300, 64, "fp8", seed=21)
-    bits = [si.storage_bits(t)[0] for t in (q, k, v)]
-    kinds = ("e4m3fn",) * 3
-    exact = oracle.spherical_attention(*bits, kinds=kinds)
-    model = oracle.spherical_attention_e4m3_scores(*bits, kinds=kinds)
-    rms = np.sqrt((exact ** 2).mean())
-    err = model - exact
-    # rounding to 3 mantissa bits: relative error uniform in +-2^-4 at the bottom of a binade,
-    # +-2^-5 at the top, about 0.026 rms; independent over the terms of the sum
-    assert 0.015 <= np.sqrt((err ** 2).mean()) / rms <= 0.04
-    assert np.abs(err).max() / rms <= 0.25
-    # scaling a query row by a power of two shifts e_i and changes nothing else
-    qs = oracle.widen(bits[0], "e4m3fn")
-    ks, vs = oracle.widen(bits[1], "e4m3fn"), oracle.widen(bits[2], "e4m3fn")
-    scale = np.ldexp(1.0, np.arange(300) % 7 - 3)[None, None, :, None]
-    a = oracle.spherical_attention_e4m3_scores(qs, ks, vs)
-    b = oracle.spherical_attention_e4m3_scores(qs * scale, ks, vs)
-    assert np.array_equal(a, b)
-    assert np.array_equal(a, model)
-    # scaling all keys by a power of two: the same
-    c = oracle.spherical_attention_e4m3_scores(qs, ks * 0.25, vs)
-    assert np.array_equal(a, c)
-
-
-def test_e4m3_model_brute_force_tiny(oracle):
-    """Two keys, hand-checkable: q = (1, 0), k1 = (3, 0), k2 = (1, 1); v = 1, -1."""
-    Q = np.array([[[[1.0, 0.0]]]])
-    K = np.array([[[[3.0, 0.0], [1.0, 1.0]]]])
-    V = np.array([[[[1.0], [-1.0]]]])
-    # bound = 1 * 3 -> 3 / 440 = 0.8727.. * 2^-7 -> e = -7; scores 3, 1 -> 384, 128: both representable
-    e, _ = oracle.e4m3_row_exponents(Q, K)
-    assert e[0, 0, 0] == -7
-    out = oracle.spherical_attention_e4m3_scores(Q, K, V)
-    assert np.isclose(out[0, 0, 0, 0], (3.0 - 1.0) / np.sqrt(10.0), rtol=1e-15)
-    # a score that is not representable: s = (1, 2.2) / bound 2.2 -> e = -7: 128, 281.6 -> 288
-    K2 = np.array([[[[2.2, 0.0], [1.0, 0.0]]]])
-    out2 = oracle.spherical_attention_e4m3_scores(Q, K2, V)
-    assert np.isclose(out2[0, 0, 0, 0], (288.0 - 128.0) / np.sqrt(288.0 ** 2 + 128.0 ** 2), rtol=1e-15)
