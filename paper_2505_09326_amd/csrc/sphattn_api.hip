@@ -330,6 +330,25 @@ size_t workspace_bytes(int B, int H, int N, int d, int n_splits)
     return ((size_t)n_splits * rows * (d + 1) * 4 + 255) & ~(size_t)255;
 }
 
+// The two launches of the split-key forward on checked arguments: partial pairs of every slice
+// into `workspace` (o parts, then z parts), then their sum and the tail.  Every partial the
+// second launch reads is written by the first (every planned slice holds at least one tile),
+// so the workspace needs no clearing.
+int run_splitkv(const void* Q, const void* K, const void* V, const float* mult, void* O, float* Z,
+                int B, int H, int H_kv, int N, int d, int dtype, SplitPlan plan, void* workspace, hipStream_t stream)
+{
+    const size_t rows = (size_t)B * H * N;
+    float* o_parts = (float*)workspace;
+    float* z_parts = o_parts + (size_t)plan.n_splits * rows * d;
+    Problem p{Q, K, V, o_parts, mult, z_parts, B, H, H_kv, N, N, stream};
+    p.n_splits = plan.n_splits;
+    p.keys_per_split = plan.keys_per_split;
+    const int r1 = mult ? dispatch_partial<true>(p, d, dtype) : dispatch_partial<false>(p, d, dtype);
+    if (r1 != SPHATTN_OK) return r1;
+    return d == 128 ? launch_combine<128>(o_parts, z_parts, plan.n_splits, O, Z, rows, dtype, stream)
+                    : launch_combine<64>(o_parts, z_parts, plan.n_splits, O, Z, rows, dtype, stream);
+}
+
 }  // namespace
 
 extern "C" {
@@ -478,21 +497,13 @@ int sphattn_splitkv_fwd(const void* Q, const void* K, const void* V, const float
     const size_t nq = (size_t)B * H * N * d, nkv = (size_t)B * H_kv * N * d;
     const size_t qk = dtype == SPHATTN_F32 ? 4 : dtype == SPHATTN_FP8QK_BF16V ? 1 : 2;
     const size_t vo = dtype == SPHATTN_F32 ? 4 : 2;
+    if (wraps(workspace, need)) return SPHATTN_ERR_WORKSPACE;
     if (overlaps(workspace, need, Q, nq * qk) || overlaps(workspace, need, K, nkv * qk) ||
         overlaps(workspace, need, V, nkv * vo) || overlaps(workspace, need, O, ob) ||
         (mult && overlaps(workspace, need, mult, (size_t)B * N * 4)) ||
         (Z && overlaps(workspace, need, Z, (size_t)B * H * N * 4)))
         return SPHATTN_ERR_ALIAS;
-    const size_t rows = (size_t)B * H * N;
-    float* o_parts = (float*)workspace;
-    float* z_parts = o_parts + (size_t)plan.n_splits * rows * d;
-    Problem p{Q, K, V, o_parts, mult, z_parts, B, H, H_kv, N, N, (hipStream_t)stream};
-    p.n_splits = plan.n_splits;
-    p.keys_per_split = plan.keys_per_split;
-    const int r1 = mult ? dispatch_partial<true>(p, d, dtype) : dispatch_partial<false>(p, d, dtype);
-    if (r1 != SPHATTN_OK) return r1;
-    return d == 128 ? launch_combine<128>(o_parts, z_parts, plan.n_splits, O, Z, rows, dtype, (hipStream_t)stream)
-                    : launch_combine<64>(o_parts, z_parts, plan.n_splits, O, Z, rows, dtype, (hipStream_t)stream);
+    return run_splitkv(Q, K, V, mult, O, Z, B, H, H_kv, N, d, dtype, plan, workspace, (hipStream_t)stream);
 }
 
 int sphattn_grn_bwd(const void* Q, const void* K, const void* V, const float* mult,
