@@ -49,7 +49,8 @@ enum {
     SPHATTN_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch */
     SPHATTN_ERR_ALIAS = -7,       /* O overlaps Q, K or V (or mult) */
     SPHATTN_ERR_NORMALIZER = -8,  /* normalizer is not a sphattn_normalizer value */
-    SPHATTN_ERR_WORKSPACE = -9    /* workspace NULL, not 16-byte aligned, or too small */
+    SPHATTN_ERR_WORKSPACE = -9,   /* workspace NULL, not 16-byte aligned, or too small */
+    SPHATTN_ERR_SCRATCH = -10     /* sphattn_splitkv_fwd_noalloc: needs more than SPHATTN_NOALLOC_SCRATCH_BYTES */
 };
 
 /* Normalizers N(x)_i = a1(x_i) / b(sum_j a2(x_j)) (paper, Appendix A.1, Definition 2). */
@@ -222,6 +223,25 @@ int sphattn_combine(const float* o_parts, const float* z_parts, int n_parts, voi
 int sphattn_splitkv_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O, float* Z,
                         int B, int H, int H_kv, int N, int d, int dtype, int n_splits,
                         void* workspace, size_t workspace_size, void* stream);
+
+/*
+ * sphattn_splitkv_fwd for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (without the workspace), same kernels, same result bit for bit; the partial pairs
+ * live in an array of SPHATTN_NOALLOC_SCRATCH_BYTES bytes that is part of the library itself
+ * (one per GPU the library runs on, held until the process ends).  The call allocates and
+ * frees nothing.
+ *   - A problem whose slices need more, sphattn_splitkv_workspace_bytes(B,H,N,d,n_splits) >
+ *     SPHATTN_NOALLOC_SCRATCH_BYTES (n_splits as used: the heuristic's value when 0 is passed,
+ *     never more than the number of 64-key tiles), returns SPHATTN_ERR_SCRATCH; nothing is enqueued.
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU
+ *     (different streams, different threads) race on it and must be ordered by the caller.
+ *     Nothing in the array has to start at zero: each call writes every partial it reads.
+ * Other arguments and errors as sphattn_splitkv_fwd.
+ */
+#define SPHATTN_NOALLOC_SCRATCH_BYTES (64u << 20)
+int sphattn_splitkv_fwd_noalloc(const void* Q, const void* K, const void* V, const float* mult, void* O, float* Z,
+                                int B, int H, int H_kv, int N, int d, int dtype, int n_splits, void* stream);
 
 /* Bytes of workspace sphattn_splitkv_fwd needs for n_splits >= 1 slices: n_splits * B*H*N * (d+1)
  * fp32 values, rounded up to 256.  Returns 0 for arguments sphattn_splitkv_fwd would reject. */

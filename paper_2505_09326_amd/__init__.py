@@ -28,7 +28,7 @@ _DTYPE_NAMES = {"f32": SPHATTN_F32, "bf16": SPHATTN_BF16, "fp8qk_bf16v": SPHATTN
 EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_fwd_z", "sphattn_fwd_tile_rows", "sphattn_grn_fwd",
                     "sphattn_normalized_fwd", "sphattn_softmax_fwd", "sphattn_cross_fwd", "sphattn_partial_fwd",
                     "sphattn_combine", "sphattn_splitkv_fwd", "sphattn_splitkv_workspace_bytes",
-                    "sphattn_splitkv_heuristic",
+                    "sphattn_splitkv_heuristic", "sphattn_splitkv_fwd_noalloc",
                     "sphattn_bwd", "sphattn_grn_bwd",
                     "sphattn_fp8_workspace_bytes", "sphattn_fp8_fwd", "sphattn_fp8_softmax_fwd",
                     "sphattn_strerror", "sphattn_version")
@@ -74,6 +74,8 @@ def load_library() -> ctypes.CDLL:
         lib.sphattn_combine.argtypes = [vp, vp, ip, vp, vp, ip, ip, ip, ip, ip, vp]
         lib.sphattn_splitkv_fwd.restype = ip
         lib.sphattn_splitkv_fwd.argtypes = [vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, ip, vp, sz, vp]
+        lib.sphattn_splitkv_fwd_noalloc.restype = ip
+        lib.sphattn_splitkv_fwd_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, ip, vp]
         lib.sphattn_splitkv_workspace_bytes.restype = sz
         lib.sphattn_splitkv_workspace_bytes.argtypes = [ip, ip, ip, ip, ip]
         lib.sphattn_splitkv_heuristic.restype = ip
@@ -364,6 +366,19 @@ def sphattn_splitkv_fwd(Q, K, V, workspace, mult=None, O=None, Z=None, n_splits=
     _raise_on(lib.sphattn_splitkv_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(mult), O.data_ptr(), _ptr(Z),
                                       B, H, H_kv, N, d, code, int(n_splits),
                                       workspace.data_ptr(), ws_bytes, _stream_of(Q, stream)))
+    return O
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20   # SPHATTN_NOALLOC_SCRATCH_BYTES of include/sphattn.h
+
+
+def sphattn_splitkv_fwd_noalloc(Q, K, V, O, mult=None, Z=None, n_splits=0, dtype="bf16", stream=None):
+    """sphattn_splitkv_fwd on the library's own scratch array (NOALLOC_SCRATCH_BYTES): no
+    workspace argument and no allocation anywhere in the call, so O must be given."""
+    lib, code = load_library(), _dtype_code(dtype)
+    B, H, N, d, H_kv, _ = _check_forward(Q, K, V, O, mult, Z, code)
+    _raise_on(lib.sphattn_splitkv_fwd_noalloc(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(mult), O.data_ptr(),
+                                              _ptr(Z), B, H, H_kv, N, d, code, int(n_splits), _stream_of(Q, stream)))
     return O
 
 

@@ -349,6 +349,31 @@ int run_splitkv(const void* Q, const void* K, const void* V, const float* mult, 
                     : launch_combine<64>(o_parts, z_parts, plan.n_splits, O, Z, rows, dtype, stream);
 }
 
+// Scratch memory of sphattn_splitkv_fwd_noalloc: one array per GPU, part of the library's code
+// object, alive until the process ends.  Host code never uses the array's name as an address:
+// its device address is asked for once per device (scratch_address) and kept.
+static __device__ __align__(256) unsigned char scratch[SPHATTN_NOALLOC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device, or nullptr if the runtime cannot give it.
+void* scratch_address()
+{
+    static std::atomic<void*> known[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    void* p = known[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        known[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
+
 }  // namespace
 
 extern "C" {
@@ -506,6 +531,22 @@ int sphattn_splitkv_fwd(const void* Q, const void* K, const void* V, const float
     return run_splitkv(Q, K, V, mult, O, Z, B, H, H_kv, N, d, dtype, plan, workspace, (hipStream_t)stream);
 }
 
+int sphattn_splitkv_fwd_noalloc(const void* Q, const void* K, const void* V, const float* mult, void* O, float* Z,
+                                int B, int H, int H_kv, int N, int d, int dtype, int n_splits, void* stream)
+{
+    const int rc = check_args(Q, K, V, O, out_bytes_of(B, H, N, d, dtype), mult, Z, B, H, H_kv, N, N, d, dtype);
+    if (rc != SPHATTN_OK) return rc;
+    if (n_splits < 0) return SPHATTN_ERR_SHAPE;
+    if (n_splits == 0) n_splits = sphattn_splitkv_heuristic(B, H, N, d, dtype);
+    const SplitPlan plan = plan_splits(N, n_splits);
+    const size_t need = sphattn_splitkv_workspace_bytes(B, H, N, d, plan.n_splits);
+    if (need == 0 || need > (size_t)SPHATTN_NOALLOC_SCRATCH_BYTES) return SPHATTN_ERR_SCRATCH;
+    void* ws = scratch_address();
+    if (ws == nullptr) return SPHATTN_ERR_LAUNCH;
+    // the caller's buffers are allocations of their own and cannot overlap the library's array
+    return run_splitkv(Q, K, V, mult, O, Z, B, H, H_kv, N, d, dtype, plan, ws, (hipStream_t)stream);
+}
+
 int sphattn_grn_bwd(const void* Q, const void* K, const void* V, const float* mult,
                     const void* O, const void* dO, const float* Z,
                     void* dQ, void* dK, void* dV, float* delta,
@@ -616,6 +657,7 @@ const char* sphattn_strerror(int code)
     case SPHATTN_ERR_ALIAS: return "O must not overlap Q, K or V";
     case SPHATTN_ERR_NORMALIZER: return "normalizer is not a sphattn_normalizer value";
     case SPHATTN_ERR_WORKSPACE: return "workspace is NULL, misaligned or smaller than the entry point's *_workspace_bytes";
+    case SPHATTN_ERR_SCRATCH: return "the problem needs more scratch than the library's own array holds (SPHATTN_NOALLOC_SCRATCH_BYTES)";
     default: return "unknown sphattn error code";
     }
 }

@@ -41,7 +41,7 @@ def test_header_symbols_are_exported(lib):
 def test_version_and_strerror(lib):
     assert lib.sphattn_version() >= 100
     assert lib.sphattn_strerror(0) == b"success"
-    for code in range(-9, 0):
+    for code in range(-10, 0):
         assert b"unknown" not in lib.sphattn_strerror(code)
     assert b"unknown" in lib.sphattn_strerror(-99)
 
@@ -294,6 +294,20 @@ def test_splitkv_slice_counts_never_divide_by_zero(lib):
                                      1, 1, 1, N, d, 1, n_splits, P(0x10000000), wsb(1, 1, N, d, 16) - 1, None)
         assert rc == -9                          # 16 slices planned: one byte short of their workspace
     assert lib.sphattn_splitkv_heuristic(1, 1, 2 ** 31 - 1, 128, 1) >= 1
+
+
+def test_noalloc_entry_point_checks_before_it_needs_a_device(lib):
+    P = ctypes.c_void_p
+
+    def call(Q=0x1000000, O=0x4000000, B=1, H=1, N=1024, d=128, dtype=1, n_splits=4, H_kv=1):
+        return lib.sphattn_splitkv_fwd_noalloc(P(Q), P(0x2000000), P(0x3000000), P(0), P(O), P(0),
+                                               B, H, H_kv, N, d, dtype, n_splits, None)
+    assert call(Q=0) == -1 and call(N=0) == -2 and call(d=100) == -3 and call(dtype=8) == -4
+    assert call(O=0x4000008) == -5 and call(O=0x1000000) == -7 and call(n_splits=-1) == -2
+    # 8 heads of 32768 rows in 2 slices: 270 MB of partial pairs, more than the library's array
+    assert lib.sphattn_splitkv_workspace_bytes(1, 8, 32768, 128, 2) > (64 << 20)
+    assert call(H=8, H_kv=8, N=32768, n_splits=2, O=0x40000000) == -10
+    assert b"scratch" in lib.sphattn_strerror(-10)
 
 
 def test_bench_refuses_more_than_one_gpu():
