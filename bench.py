@@ -22,8 +22,14 @@ if ROOT not in sys.path:
 # and half at the bf16 rate (2500): harmonic mean
 PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "fp8qk_bf16v": 1.0 / (0.5 / 5000.0 + 0.5 / 2500.0), "f32": 157.3}
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by the reading of a
-# 256 MiB device copy in the same run (see profiles/); workloads not profiled report null
-MEASURED_HBM_BYTES = {"C3": 268.6e6, "C5": 1208.0e6}
+# 256 MiB device copy in the same run.  These are stored readings of the profile named beside
+# them, not measured by this process (counters need the profiler): `traffic` carries one only for
+# the workload and kernel that profile covers, `traffic_source` says where it came from, and
+# every other workload reports null.
+MEASURED_HBM_BYTES = {
+    "C3": (268.6e6, "profiles/fwd_pipelined_bf16_d128_C3.md"),
+    "C5": (1208.0e6, "profiles/fwd_pipelined_fp8qk_d128_C5.md"),
+}
 HBM_PEAK_GBS = 8000.0
 
 
@@ -67,6 +73,35 @@ def load_mfma_probe():
     return probe
 
 
+def measure_mfma_ceiling(args, si, dev):
+    """Loops of nothing but matrix instructions on Gaussian operands: TFLOP/s and shader clock
+    per instruction form (the fp8 forms only with --fp8-all)."""
+    import torch
+    g = torch.Generator(device="cpu").manual_seed(7)
+    ops16 = torch.randn(32768, generator=g, dtype=torch.float32).to(torch.bfloat16).to(dev)
+    ops8 = si.to_e4m3fn(torch.randn(65536, generator=g, dtype=torch.float32)).view(torch.uint8).to(dev)
+    clk = torch.zeros(3, dtype=torch.int64, device=dev)
+    mfma_probe = load_mfma_probe()
+    ceil = {}
+    for form, name in ((0, "32x32x16_bf16"), (1, "16x16x32_bf16"), (2, "16x16x128_e4m3"),
+                       (3, "16x16x128_e4m3_with_l2_stage_b_mix"), (4, "16x16x128_e4m3_with_softmax_stage_b_mix")):
+        iters = 100000
+        if form >= 2 and not args.fp8_all:
+            continue
+        ops = ops8 if form >= 2 else ops16
+        for _ in range(2):
+            flop = mfma_probe(ops, clk, form, iters)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = mfma_probe(ops, clk, form, iters)
+        e1.record()
+        torch.cuda.synchronize()
+        c = clk.cpu().tolist()
+        ceil[name] = {"tflops": flop / (e0.elapsed_time(e1) * 1e-3) / 1e12, "shader_ghz": 0.1 * c[0] / max(c[1], 1)}
+    return ceil
+
+
 def cpu_baseline(w, q, k, v, budget_s=12.0):
     """The fp64 oracle, as it stands, on a bounded sample: whole heads of the workload, one
     after the other, until about `budget_s` seconds of CPU time have been spent."""
@@ -101,6 +136,7 @@ def main() -> int:
                          "default C3: the configuration the target is quoted on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-twin", action="store_true")
+    ap.add_argument("--no-after-idle", action="store_true", help="skip the second timing taken after 1 s of idle")
     ap.add_argument("--grn", type=int, default=0, metavar="H_KV",
                     help="also time the gene-regulatory-network entry point on the same shape with "
                          "H_KV shared K/V heads and Poisson(1.5) multiplicities")
@@ -139,6 +175,18 @@ def main() -> int:
     def step():
         pkg.sphattn_fwd(qd, kd, vd, out, dtype=w.dtype)
 
+    # What the matrix pipes sustain on Gaussian operands, matrix instructions only.  It runs
+    # BEFORE the timed steps on purpose: after any idle period the part's power management goes
+    # through a transient of about 30 launches (boost, overshoot down to -25 %, recovery), and a
+    # short timed region right after start-up would sit in the middle of it.  With ~0.2 s of matrix
+    # work in front, the warm-up and timed steps measure the settled state; `after_idle` below is
+    # the same measurement taken from idle, for comparison.
+    # (One call first, so that loading the library's code object and raising the kernel's LDS
+    # limit, which take milliseconds of idle GPU, do not fall between the probe and the steps.)
+    step()
+    torch.cuda.synchronize()
+    ceil = measure_mfma_ceiling(args, si, dev) if not args.no_mfma_ceiling else None
+
     ms_wall, per = time_launches(step, args.steps, args.warmup)
     ms_kernel = sum(per) / len(per)
     tflops = w.flops / (ms_wall * 1e-3) / 1e12
@@ -158,10 +206,26 @@ def main() -> int:
         "config": {"workload": w.describe(), "B": w.B, "H": w.H, "N": w.N, "d": w.d,
                    "flop_per_step": w.flops, "min_hbm_bytes_per_step": algo_bytes},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": peak, "unit": "TFLOP/s",
-                     "frac": kern_tflops / peak, "traffic": MEASURED_HBM_BYTES.get(w.name),
+                     "frac": kern_tflops / peak,
+                     "traffic": MEASURED_HBM_BYTES[w.name][0] if w.name in MEASURED_HBM_BYTES else None,
+                     "traffic_source": (f"stored reading of {MEASURED_HBM_BYTES[w.name][1]} (rocprofv3 FETCH_SIZE + WRITE_SIZE, "
+                                        "scaled by a 256 MiB copy), not measured by this run"
+                                        if w.name in MEASURED_HBM_BYTES else None),
                      "kernel_ms_avg": ms_kernel, "kernel_ms_median": per[len(per) // 2],
                      "kernel_ms_min": per[0]},
     }
+
+    # the same K steps after W warm-up steps, taken from idle (1 s of sleep): what a short timed
+    # region sees when nothing ran before it
+    if w.flops >= 1e11 and not args.no_after_idle:
+        torch.cuda.synchronize()
+        time.sleep(1.0)
+        _, per_idle = time_launches(step, args.steps, args.warmup)
+        result["roofline"]["timing_state"] = ("settled: the matrix-only probe ran first" if ceil is not None
+                                              else "whatever preceded the warm-up steps")
+        result["roofline"]["after_idle"] = {
+            "kernel_ms_avg": sum(per_idle) / len(per_idle), "frac": w.flops / (sum(per_idle) / len(per_idle) * 1e-3) / 1e12 / peak,
+            "note": "same steps and warm-up after 1 s of idle: inside the power-management transient"}
 
     # short problems are bound by launch latency and occupancy, not by the matrix pipes: also
     # state what the launch achieves against the HBM roofline (algorithmic bytes / time)
@@ -191,7 +255,9 @@ def main() -> int:
         ms_t = sum(per_t) / len(per_t)
         result["softmax_twin"] = {"kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12,
                                   "spherical_speedup": ms_t / ms_kernel,
-                                  "form": "32x32x16 MFMA, the fastest SoftMax form here"}
+                                  "form": "32x32x16 MFMA, the fastest SoftMax form here", "shares_the_spherical_kernels_data_path": False,
+                                  "note": "own data path (register-staged, padded LDS rows): the ratio mixes that "
+                                          "difference into the exponential's cost; softmax_twin_same_instructions is like for like"}
 
         def twin16():
             pkg.sphattn_normalized_fwd(qd, kd, vd, out, dtype=w.dtype, normalizer="softmax")
@@ -199,7 +265,8 @@ def main() -> int:
         ms_t = sum(per_t) / len(per_t)
         result["softmax_twin_same_instructions"] = {
             "kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12, "spherical_speedup": ms_t / ms_kernel,
-            "form": "16x16x32 MFMA, the spherical kernel with exp/max/rescale in stage B"}
+            "form": "16x16x32 MFMA, the spherical kernel with exp/max/rescale in stage B",
+            "shares_the_spherical_kernels_data_path": True}
 
     if not args.no_twin and w.dtype == "fp8qk_bf16v":
         def twin8():
@@ -208,7 +275,8 @@ def main() -> int:
         ms_t = sum(per_t) / len(per_t)
         result["softmax_twin_same_instructions"] = {
             "kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12, "spherical_speedup": ms_t / ms_kernel,
-            "form": "the spherical kernel (fp8 16x16x128 scores, bf16 16x16x32 output) with exp/max/rescale in stage B"}
+            "form": "the spherical kernel (fp8 16x16x128 scores, bf16 16x16x32 output) with exp/max/rescale in stage B",
+            "shares_the_spherical_kernels_data_path": True}
 
     if args.grn:
         g = torch.Generator(device="cpu").manual_seed(w.seed + 1000)
@@ -241,31 +309,7 @@ def main() -> int:
             "split_speedup": ms_u / ms_s,
         }
 
-    if not args.no_mfma_ceiling:
-        # what the matrix pipes sustain on Gaussian operands, matrix instructions only
-        g = torch.Generator(device="cpu").manual_seed(7)
-        ops = torch.randn(32768, generator=g, dtype=torch.float32).to(torch.bfloat16).to(dev)
-        clk = torch.zeros(3, dtype=torch.int64, device=dev)
-        ceil = {}
-        mfma_probe = load_mfma_probe()
-        ops8 = si.to_e4m3fn(torch.randn(65536, generator=g, dtype=torch.float32)).view(torch.uint8).to(dev)
-        for form, name in ((0, "32x32x16_bf16"), (1, "16x16x32_bf16"), (2, "16x16x128_e4m3"),
-                           (3, "16x16x128_e4m3_with_l2_stage_b_mix"), (4, "16x16x128_e4m3_with_softmax_stage_b_mix")):
-            iters = 100000
-            if form >= 2:
-                if not args.fp8_all:
-                    continue
-                ops = ops8
-            for _ in range(2):
-                flop = mfma_probe(ops, clk, form, iters)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            flop = mfma_probe(ops, clk, form, iters)
-            e1.record()
-            torch.cuda.synchronize()
-            c = clk.cpu().tolist()
-            ceil[name] = {"tflops": flop / (e0.elapsed_time(e1) * 1e-3) / 1e12, "shader_ghz": 0.1 * c[0] / max(c[1], 1)}
+    if ceil is not None:
         result["mfma_only_ceiling_gaussian_operands"] = ceil
         result["roofline"]["frac_of_mfma_only_ceiling"] = kern_tflops / ceil["16x16x32_bf16"]["tflops"]
 
