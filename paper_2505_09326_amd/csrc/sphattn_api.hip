@@ -82,6 +82,33 @@ size_t out_bytes_of(int B, int H, int N, int d, int dtype)
 
 // Kernels that use more than 64 KB of LDS need their limit raised once per device; `done` is
 // that kernel's bit mask of devices already configured (the only state the library keeps).
+long long cu_count();
+
+// How many consecutive workgroups of one XCD's range run at the same time: that XCD's share of
+// the compute units times the workgroups of this kernel that fit one unit.  Feeds the kernels'
+// key-stream direction (see fwd_pipelined_kernel); asked once per kernel and device.
+template <typename Kern>
+int stream_period(Kern kern, int lds_bytes, std::atomic<int> (&cached)[64])
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    int p = cached[dev].load(std::memory_order_relaxed);
+    if (p == 0) {
+        int per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kern, kThreads, (size_t)lds_bytes) != hipSuccess ||
+            per_cu <= 0) {
+            (void)hipGetLastError();
+            return 0;                              // 0: never reverse
+        }
+        p = (int)(cu_count() / kXcds) * per_cu;
+        cached[dev].store(p, std::memory_order_relaxed);
+    }
+    return p;
+}
+
 template <typename Kern>
 bool raise_lds_limit(Kern kern, int lds_bytes, std::atomic<uint64_t>& done)
 {
@@ -153,6 +180,7 @@ int launch_pipelined(const Problem& p)
     constexpr int lds_bytes = kNBuf * kBC * (D * EQ + D * 2 + (MULT ? 4 : 0));
     auto kern = fwd_pipelined_kernel<D, NQ, QKT, NORM, MULT, PARTIAL>;
     static std::atomic<uint64_t> done{0};
+    static std::atomic<int> period[64];
     if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;
     const int n_qtiles = (p.Nq + BR - 1) / BR;
     const long long n_wg = (long long)p.B * p.H * n_qtiles * p.n_splits;
@@ -161,7 +189,7 @@ int launch_pipelined(const Problem& p)
     hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, p.stream,
                        p.Q, p.K, p.V, p.O, p.mult, p.Z,
                        p.Nq, p.Nk, p.H, p.H / p.H_kv, n_qtiles, (int)n_wg,
-                       p.n_splits, p.keys_per_split, scale_log2);
+                       p.n_splits, p.keys_per_split, scale_log2, stream_period(kern, lds_bytes, period));
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
@@ -619,8 +647,10 @@ static int fp8_forward(const void* Q, const void* K, const void* V, void* O, voi
     // everything that can fail without a launch comes before the first launch
     constexpr int lds_bytes = 4 * 2 * kFp8Tile * kFp8D;
     static std::atomic<uint64_t> done{0}, done_twin{0};
+    static std::atomic<int> period[64], period_twin[64];
     auto kern = softmax ? fwd_fp8_kernel<true> : fwd_fp8_kernel<false>;
     if (!raise_lds_limit(kern, lds_bytes, softmax ? done_twin : done)) return SPHATTN_ERR_LAUNCH;
+    const int sp = stream_period(kern, lds_bytes, softmax ? period_twin : period);
     hipLaunchKernelGGL(fp8_clear_kernel, dim3((heads + 255) / 256), dim3(256), 0, st, kmax, heads);
     if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
     hipLaunchKernelGGL(fp8_prepare_kernel, dim3((unsigned)(heads * n_tiles)), dim3(256), 0, st,
@@ -628,7 +658,7 @@ static int fp8_forward(const void* Q, const void* K, const void* V, void* O, voi
     if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, st,
                        (const unsigned char*)Q, (const unsigned char*)K, (const unsigned char*)VT,
-                       (const float*)kmax, (unsigned short*)O, N, H, H / H_kv, n_tiles, n_qtiles, (int)n_wg);
+                       (const float*)kmax, (unsigned short*)O, N, H, H / H_kv, n_tiles, n_qtiles, (int)n_wg, sp);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 

@@ -150,7 +150,8 @@ template <bool SOFTMAX>
 __global__ __launch_bounds__(kThreads, 1)
 void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __restrict__ K,
                     const unsigned char* __restrict__ VT, const float* __restrict__ kmax,
-                    unsigned short* __restrict__ O, int N, int H, int kv_group, int n_tiles, int n_qtiles, int n_wg)
+                    unsigned short* __restrict__ O, int N, int H, int kv_group, int n_tiles, int n_qtiles, int n_wg,
+                    int stream_period)
 {
     constexpr int D = kFp8D, BC = kFp8Tile, NQ = 4;
     constexpr int BR = kWaves * 16 * NQ;
@@ -235,8 +236,12 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     // copy c of this wave's share of tile `tile` into buffer `buf`: c < 4 K, else V^T.  K rows
     // past the end of the head are out of the descriptor's range and arrive as zeros.
-    auto copy_chunk = [&](int c, int tile, SPH_LDS unsigned char* buf) {
+    // every other batch of workgroups of an XCD streams the keys backwards (see fwd_pipelined_kernel)
+    const bool backwards = stream_period > 0 && (((int)blockIdx.x / kXcds) / stream_period) % 2 == 1;
+    auto src_tile = [&](int t) { return t >= n_tiles ? n_tiles : backwards ? n_tiles - 1 - t : t; };
+    auto copy_chunk = [&](int c, int t, SPH_LDS unsigned char* buf) {
         const uint32_t base = (uint32_t)(uintptr_t)buf;
+        const int tile = src_tile(t);
         if (c < 4)
             copy_to_lds(krw, base + (wave_u * 4 + c) * 1024, kld_lane, tile * KTILE + (c >> 1) * 4 * D + (c & 1) * 64);
         else
@@ -289,7 +294,7 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     // keys of the lane in block row kb of tile t: 128 t + 64 (kb / 4) + 16 g + 4 (kb % 4) + 0..3
     auto keys_left = [&](int t, int kb) -> int {
         if (!SOFTMAX) return 4;
-        return t < 0 ? 0 : N - (128 * t + 64 * (kb >> 2) + 16 * g + 4 * (kb & 3));   // t = -1: before the first tile
+        return t < 0 ? 0 : N - (128 * src_tile(t) + 64 * (kb >> 2) + 16 * g + 4 * (kb & 3));   // t = -1: before the first tile
     };
     // SOFTMAX: row sums of P as all-ones rows times P
     const frag_t ones = {0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838};

@@ -120,7 +120,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                           const void* __restrict__ Vv, void* __restrict__ Ov,
                           const float* __restrict__ mult, float* __restrict__ Zv,
                           int Nq, int Nk, int H, int kv_group, int n_qtiles, int n_wg,
-                          int n_splits, int keys_per_split, float scale_log2)
+                          int n_splits, int keys_per_split, float scale_log2, int stream_period)
 {
     constexpr bool FP8 = QKT == QKType::Fp8;
     constexpr bool HALF = QKT == QKType::F16;      // 16-bit type of V, O and P
@@ -205,6 +205,10 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     const int kld_lane = (16 * wave + (lane >> 2)) * KROWB + (lane & 3) * 16;
     const int vld_lane = (16 * wave + ((lane & 31) >> 1)) * VROWB + (lane >> 5) * 32 + (lane & 1) * 16;
 
+    // Q is read once and O written once by this workgroup and by no other: both go past the L2's
+    // retention (non-temporal), so that what stays in the XCD's L2 between batches of workgroups
+    // is the K/V stream (measured: with ordinary loads and stores the 2 MB of O and 2 MB of Q that
+    // 32 workgroups move at a batch boundary flush a 4 MB L2 completely).
     // ---- Q fragments (B operands of S^T = K Q^T), held for the whole kernel: lane holds
     // Q[q0 + 16qb + n16][k-slots of group g].  fp8 with d = 64 fills half of the k = 128 of
     // the instruction: groups 2 and 3 hold zeros on both sides.
@@ -223,12 +227,12 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             if constexpr (FP8) {
                 i32x4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
                 if (k_live) {
-                    lo = *reinterpret_cast<const i32x4*>(src);
-                    hi = *reinterpret_cast<const i32x4*>(src + 16);
+                    lo = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(src));
+                    hi = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(src + 16));
                 }
                 qf[qb][kk] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             } else {
-                qf[qb][kk] = *reinterpret_cast<const i32x4*>(src + kk * 64);
+                qf[qb][kk] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(src + kk * 64));
             }
         }
     }
@@ -259,6 +263,17 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             mreg[par][kb] = __builtin_bit_cast(f32x4, lds_read_b128(buf + MLDS + (32 * sub + 16 * kb + 4 * g) * 4));
     };
 
+    const int n_tiles = (N + BC - 1) / BC;
+    // Direction of the key stream.  The workgroups that an XCD runs at the same time (stream_period
+    // consecutive ones of its contiguous range) stream one head's K/V together through that XCD's
+    // L2.  When a head has more query tiles than that, the next batch streams the same K/V again;
+    // if the head's K/V is larger than the L2, what the first batch left there is the END of the
+    // stream, so every other batch walks the keys backwards and starts on what is still resident
+    // (a sum over keys: any order gives the same accumulator up to fp32 rounding).  Tiles past
+    // the end (the pipeline runs two ahead) map past the end in either direction.
+    const bool backwards = stream_period > 0 && (((int)blockIdx.x / kXcds) / stream_period) % 2 == 1;
+    auto src_tile = [&](int t) { return t >= n_tiles ? n_tiles : backwards ? n_tiles - 1 - t : t; };
+
     // copy c (K: c < LDK, V: the rest) of this wave's share of tile `tile` into buffer `buf`.
     // Rows past the end of the head are out of the descriptor's range and arrive as zeros.
     const i32x4 krw = rsrc_words((const unsigned char*)Kv + kv_off * EQ, (uint32_t)N * KROWB);
@@ -266,8 +281,9 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     // multiplicities of this cell's keys; those past the last key arrive as 0 (their keys are zero anyway)
     const i32x4 mrw = rsrc_words(MULT ? mult + (size_t)bidx * Nk + k0 : nullptr, MULT ? (uint32_t)N * 4 : 0);
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
-    auto copy_chunk = [&](int c, int tile, SPH_LDS unsigned char* buf) {
+    auto copy_chunk = [&](int c, int t, SPH_LDS unsigned char* buf) {
         const uint32_t base = (uint32_t)(uintptr_t)buf;
+        const int tile = src_tile(t);
         if (c < LDK)
             copy_to_lds(krw, base + (wave_u * KBLK + c) * 1024, kld_lane, tile * KTILE + c * 64);
         else if (c < LDK + LDV)
@@ -275,8 +291,6 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         else if (wave == 0 && lane < BC / 4)       // 16 lanes x 4 multiplicities
             copy_to_lds(mrw, base + MLDS, lane * 16, tile * BC * 4);
     };
-
-    const int n_tiles = (N + BC - 1) / BC;
 
     // ---- prologue: buffer 3 plays "tile -1" (zeros) for the first stage C; tiles 0 and 1 go
     // to buffers 0 and 1
@@ -446,7 +460,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             if constexpr (NORM == Norm::Softmax) {
                 if (i == 0) {
                     // keys past N (ragged last tile only) must not take part in the SoftMax
-                    const int key0 = (2 * j + hf) * 32;      // first key of the current sub-step
+                    const int key0 = (2 * src_tile(j) + hf) * 32;      // first key of the current sub-step
                     if (key0 + 32 > N) {
 #pragma unroll
                         for (int kb = 0; kb < 2; ++kb)
@@ -566,7 +580,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                 if (g == 0) Zp[row] = z;
                 float* dst = Op + (size_t)row * D + 4 * g;
 #pragma unroll
-                for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(dst + db * 16) = oacc[db][qb];
+                for (int db = 0; db < DB; ++db) __builtin_nontemporal_store(oacc[db][qb], reinterpret_cast<f32x4*>(dst + db * 16));
             }
         }
         return;
@@ -595,7 +609,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             for (int db = 0; db < DB; ++db) {
                 const i32x2 o4 = {pack2<HALF>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
                                   pack2<HALF>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
-                *reinterpret_cast<i32x2*>(dst + db * 16) = o4;
+                __builtin_nontemporal_store(o4, reinterpret_cast<i32x2*>(dst + db * 16));
             }
         }
     }

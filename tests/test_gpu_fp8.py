@@ -266,3 +266,25 @@ def test_fp8_all_softmax_twin(pkg, oracle, B, H, N):
     err_rms, err_max = np.sqrt((err ** 2).mean()) / rms, np.abs(err).max() / rms
     print(f"softmax twin vs oracle: rms {err_rms:.3e} max {err_max:.3e}", flush=True)
     assert err_rms <= TWIN_RMS and err_max <= TWIN_MAX
+
+
+def test_fp8_all_backward_key_stream_with_ragged_tail(pkg, oracle):
+    """More workgroups than run at once (330 at one per compute unit): every other batch of an XCD
+    streams the keys from the last tile to the first, the ragged tile first.  Sampled rows of every
+    head against the oracle-derived bounds."""
+    B, H, N, d = 2, 5, 8237, 128
+    print(f"case fp8-all key-stream direction B={B} H={H} N={N}", flush=True)
+    q, k, v = si.make_qkv(B, H, N, d, "fp8", seed=4242)
+    got = _run(pkg, q, k, v)
+    assert np.all(np.isfinite(got))
+    qb, kb, vb = _bits(q, k, v)
+    rng = np.random.default_rng(6)
+    for bh in range(B * H):
+        b, h = divmod(bh, H)
+        # one row of every 256-row query tile (each is one workgroup), first and last included
+        rows = sorted({0, N - 1} | {int(t * 256 + rng.integers(min(256, N - t * 256))) for t in range((N + 255) // 256)})
+        Q, K, V = (oracle.widen(x[b, h], "e4m3fn") for x in (qb, kb, vb))
+        exact = oracle.spherical_attention_rows(qb, kb, vb, bh, rows, kinds=("e4m3fn",) * 3)
+        S = Q[rows] @ K.T
+        cap = np.sqrt((Q[rows] ** 2).sum(-1)) * np.sqrt((K * K).sum(-1)).max()
+        _assert_within_oracle_bounds(got[b, h][rows], exact, S, V, cap, d, f"bh={bh}")

@@ -432,3 +432,28 @@ def test_very_long_head(pkg, oracle):
     print(f"very long head sampled rows max|err|/rms={err:.3e}", flush=True)
     assert err <= TOL["bf16"]
     assert _rel_err(got, _gram_reference(q, k, v)) <= TOL["bf16"]
+
+
+# ---------------------------------------------------------------- key-stream direction
+@pytest.mark.parametrize("B,H,N,d,dtype,normalizer", [
+    (2, 5, 8237, 128, "bf16", "l2"),          # 330 workgroups at one per compute unit: 74 walk the keys backwards
+    (1, 16, 8237, 64, "bf16", "l2"),          # 528 workgroups at two per compute unit
+    (2, 5, 8237, 128, "fp8qk_bf16v", "l2"),
+    (1, 9, 8237, 128, "bf16", "softmax"),     # the ragged last tile is masked wherever it comes in the stream
+])
+def test_backward_key_stream_with_ragged_tail(pkg, oracle, B, H, N, d, dtype, normalizer):
+    """Launches with more workgroups than run at once: every other batch of an XCD streams the
+    keys from the last tile to the first (so that a head's K/V still in that XCD's L2 is reused),
+    and the ragged last tile is then the first one read.  Whole tensor against the oracle."""
+    print(f"case key-stream direction B={B} H={H} N={N} d={d} {dtype} {normalizer}", flush=True)
+    q, k, v = si.make_qkv(B, H, N, d, dtype, seed=4100 + d + H)
+    dev = torch.device("cuda:0")
+    out = pkg.sphattn_normalized_fwd(q.to(dev), k.to(dev), v.to(dev), dtype=dtype, normalizer=normalizer)
+    torch.cuda.synchronize()
+    got = out.cpu().to(torch.float64).numpy()
+    bits, kinds = _kinds(q, k, v)
+    ref = oracle.normalized_attention(*bits, normalizer, kinds=kinds)
+    assert np.all(np.isfinite(got))
+    err = _rel_err(got, ref)
+    print(f"max|err|/rms={err:.3e}", flush=True)
+    assert err <= TOL[dtype]
