@@ -43,7 +43,7 @@ enum {
     SPHATTN_OK = 0,
     SPHATTN_ERR_NULL = -1,        /* a required pointer is NULL */
     SPHATTN_ERR_SHAPE = -2,       /* B, H, N (or H_kv) not positive, H_kv not dividing H, or sizes overflow */
-    SPHATTN_ERR_HEAD_DIM = -3,    /* d is not 64 or 128 (sphattn_fp8_fwd: not 128) */
+    SPHATTN_ERR_HEAD_DIM = -3,    /* d is not 64 or 128 */
     SPHATTN_ERR_DTYPE = -4,       /* dtype is not a sphattn_dtype value */
     SPHATTN_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned */
     SPHATTN_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch */
@@ -305,7 +305,8 @@ int sphattn_grn_bwd(const void* Q, const void* K, const void* V, const float* mu
  * of the sum: about 2.7 % of rms(O) in the root mean square and up to about 15 % of rms(O) on
  * single elements, not the 2^-9 of the 16-bit paths.
  *   Q        : device, [B,H,N,d] contiguous, one byte per element (E4M3, finite values),
- *              16-byte aligned.  d must be 128 (anything else: SPHATTN_ERR_HEAD_DIM).
+ *              16-byte aligned.  d is 64 or 128 (anything else: SPHATTN_ERR_HEAD_DIM); d = 64 runs
+ *              the first contraction on the same k = 128 instruction with half of its slots zero.
  *   K, V     : the same with H_kv heads, [B,H_kv,N,d]; H_kv divides H, and query head h reads
  *              K/V head h / (H / H_kv) (Appendix A.2); H_kv == H: no sharing.
  *   O        : device, [B,H,N,d] bfloat16, written by the call, must not overlap the inputs.
@@ -321,6 +322,18 @@ size_t sphattn_fp8_workspace_bytes(int B, int H_kv, int N, int d);
 int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O,
                     void* workspace, size_t workspace_bytes,
                     int B, int H, int H_kv, int N, int d, void* stream);
+
+/*
+ * sphattn_fp8_fwd with the gene multiplicities of sphattn_grn_fwd (paper, Section 3.1):
+ * s_ij = mult[b,j] (q_i . k_j), multiplied in fp32 before the score is scaled and rounded to
+ * E4M3; the row factor 2^e_i then comes from |q_i| max_j |mult[b,j]| |k_j|.
+ *   mult : [B,N] fp32 device pointer (4-byte aligned), finite values; NULL means all ones
+ *          (then this is sphattn_fp8_fwd).  Must not overlap O or the workspace.
+ * Everything else as sphattn_fp8_fwd.
+ */
+int sphattn_fp8_grn_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O,
+                        void* workspace, size_t workspace_bytes,
+                        int B, int H, int H_kv, int N, int d, void* stream);
 
 /*
  * Comparison twin of sphattn_fp8_fwd: O = softmax(Q K^T / sqrt(d)) V with the same storage, the

@@ -30,7 +30,7 @@ EXPORTED_SYMBOLS = ("sphattn_fwd", "sphattn_fwd_z", "sphattn_fwd_tile_rows", "sp
                     "sphattn_combine", "sphattn_splitkv_fwd", "sphattn_splitkv_workspace_bytes",
                     "sphattn_splitkv_heuristic", "sphattn_splitkv_fwd_noalloc",
                     "sphattn_bwd", "sphattn_grn_bwd",
-                    "sphattn_fp8_workspace_bytes", "sphattn_fp8_fwd", "sphattn_fp8_softmax_fwd",
+                    "sphattn_fp8_workspace_bytes", "sphattn_fp8_fwd", "sphattn_fp8_grn_fwd", "sphattn_fp8_softmax_fwd",
                     "sphattn_strerror", "sphattn_version")
 
 NORMALIZERS = {"l2": 0, "softmax": 1, "l1": 2, "sqrelu": 3}
@@ -90,6 +90,8 @@ def load_library() -> ctypes.CDLL:
             fn = getattr(lib, name)
             fn.restype = ip
             fn.argtypes = [vp, vp, vp, vp, vp, sz, ip, ip, ip, ip, ip, vp]
+        lib.sphattn_fp8_grn_fwd.restype = ip
+        lib.sphattn_fp8_grn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, sz, ip, ip, ip, ip, ip, vp]
         lib.sphattn_strerror.restype = ctypes.c_char_p
         lib.sphattn_strerror.argtypes = [ip]
         lib.sphattn_version.restype = ip
@@ -419,6 +421,20 @@ def sphattn_fp8_softmax_fwd(Q, K, V, workspace, O=None, stream=None):
     """SoftMax comparison twin of sphattn_fp8_fwd (same arguments): for timing, on inputs of
     moderate size."""
     return sphattn_fp8_fwd(Q, K, V, workspace, O=O, stream=stream, _entry="sphattn_fp8_softmax_fwd")
+
+
+def sphattn_fp8_grn_fwd(Q, K, V, mult, workspace, O=None, stream=None):
+    """sphattn_fp8_fwd with per-gene multiplicities mult [B,N] (fp32, or None) on the scores."""
+    import torch
+    lib = load_library()
+    if O is None:
+        O = torch.empty(Q.shape, dtype=torch.bfloat16, device=Q.device)
+    ws_bytes = _need_workspace(workspace)
+    B, H, N, d, H_kv = _check_fp8(Q, K, V, O, mult)
+    _on_device(Q=Q, workspace=workspace)
+    _raise_on(lib.sphattn_fp8_grn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(mult), O.data_ptr(),
+                                      workspace.data_ptr(), ws_bytes, B, H, H_kv, N, d, _stream_of(Q, stream)))
+    return O
 
 
 def _check_backward(Q, K, V, mult, O, dO, Z, dQ, dK, dV, delta, code):

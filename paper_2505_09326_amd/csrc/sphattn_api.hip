@@ -377,6 +377,77 @@ int run_splitkv(const void* Q, const void* K, const void* V, const float* mult, 
                     : launch_combine<64>(o_parts, z_parts, plan.n_splits, O, Z, rows, dtype, stream);
 }
 
+template <int D, bool SOFTMAX, bool MULT>
+int launch_fp8(const void* Q, const void* K, const unsigned char* VT, const float* kmax, const float* mult,
+                      void* O, int B, int H, int H_kv, int N, int n_tiles, hipStream_t st)
+{
+    constexpr int lds_bytes = 4 * (2 * kFp8Tile * D + (MULT ? kFp8Tile * 4 : 0));
+    static std::atomic<uint64_t> done{0};
+    static std::atomic<int> period[64];
+    auto kern = fwd_fp8_kernel<D, SOFTMAX, MULT>;
+    if (!raise_lds_limit(kern, lds_bytes, done)) return SPHATTN_ERR_LAUNCH;
+    const int n_qtiles = (N + 255) / 256;
+    const long long n_wg = (long long)B * H * n_qtiles;
+    hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, st,
+                       (const unsigned char*)Q, (const unsigned char*)K, VT, kmax, mult, (unsigned short*)O,
+                       N, H, H / H_kv, n_tiles, n_qtiles, (int)n_wg, stream_period(kern, lds_bytes, period));
+    return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
+}
+
+int fp8_forward(const void* Q, const void* K, const void* V, const float* mult, void* O, void* workspace,
+                       size_t workspace_bytes, int B, int H, int H_kv, int N, int d, void* stream, bool softmax)
+{
+    if (d != 64 && d != 128) return SPHATTN_ERR_HEAD_DIM;
+    if (!Q || !K || !V || !O) return SPHATTN_ERR_NULL;
+    const int rc = check_shape(B, H, H_kv, N, N, d, SPHATTN_FP8QK_BF16V);
+    if (rc != SPHATTN_OK) return rc;
+    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return SPHATTN_ERR_ALIGN;
+    if ((uintptr_t)mult & 3) return SPHATTN_ERR_ALIGN;
+    const size_t in_bytes = (size_t)B * H * N * d, kv_bytes = (size_t)B * H_kv * N * d, m_bytes = (size_t)B * N * 4;
+    if (wraps(O, in_bytes * 2) || wraps(Q, in_bytes) || wraps(K, kv_bytes) || wraps(V, kv_bytes) ||
+        (mult && wraps(mult, m_bytes)))
+        return SPHATTN_ERR_SHAPE;
+    if (overlaps(O, in_bytes * 2, Q, in_bytes) || overlaps(O, in_bytes * 2, K, kv_bytes) ||
+        overlaps(O, in_bytes * 2, V, kv_bytes) || (mult && overlaps(O, in_bytes * 2, mult, m_bytes)))
+        return SPHATTN_ERR_ALIAS;
+    const size_t need = sphattn_fp8_workspace_bytes(B, H_kv, N, d);
+    if (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < need || wraps(workspace, need))
+        return SPHATTN_ERR_WORKSPACE;
+    if (overlaps(workspace, need, Q, in_bytes) || overlaps(workspace, need, K, kv_bytes) ||
+        overlaps(workspace, need, V, kv_bytes) || overlaps(workspace, need, O, in_bytes * 2) ||
+        (mult && overlaps(workspace, need, mult, m_bytes)))
+        return SPHATTN_ERR_ALIAS;
+    const int heads = B * H_kv;                    // K/V heads: what the preparation pass covers
+    const int n_tiles = (N + kFp8Tile - 1) / kFp8Tile;
+    const size_t kmax_bytes = ((size_t)heads * 4 + 255) & ~(size_t)255;
+    float* kmax = (float*)workspace;
+    unsigned char* VT = (unsigned char*)workspace + kmax_bytes;
+    hipStream_t st = (hipStream_t)stream;
+    if ((long long)heads * n_tiles > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    if ((long long)B * H * ((N + 255) / 256) > 0x7fffffff) return SPHATTN_ERR_SHAPE;
+    if ((unsigned __int128)d * n_tiles * kFp8Tile > 0x7fffffff) return SPHATTN_ERR_SHAPE;   // one head of V^T: a 32-bit range
+    // three launches; the attention kernel's attribute (the one thing that can fail without a
+    // launch) is set by its launcher before it enqueues anything, so a refusal there leaves the
+    // workspace written and nothing else
+    hipLaunchKernelGGL(fp8_clear_kernel, dim3((heads + 255) / 256), dim3(256), 0, st, kmax, heads);
+    if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
+    if (d == 128)
+        hipLaunchKernelGGL(fp8_prepare_kernel<128>, dim3((unsigned)(heads * n_tiles)), dim3(256), 0, st,
+                           (const unsigned char*)K, (const unsigned char*)V, mult, VT, kmax, N, n_tiles, H_kv);
+    else
+        hipLaunchKernelGGL(fp8_prepare_kernel<64>, dim3((unsigned)(heads * n_tiles)), dim3(256), 0, st,
+                           (const unsigned char*)K, (const unsigned char*)V, mult, VT, kmax, N, n_tiles, H_kv);
+    if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
+    if (d == 128) {
+        if (softmax) return launch_fp8<128, true, false>(Q, K, VT, kmax, nullptr, O, B, H, H_kv, N, n_tiles, st);
+        return mult ? launch_fp8<128, false, true>(Q, K, VT, kmax, mult, O, B, H, H_kv, N, n_tiles, st)
+                    : launch_fp8<128, false, false>(Q, K, VT, kmax, nullptr, O, B, H, H_kv, N, n_tiles, st);
+    }
+    if (softmax) return launch_fp8<64, true, false>(Q, K, VT, kmax, nullptr, O, B, H, H_kv, N, n_tiles, st);
+    return mult ? launch_fp8<64, false, true>(Q, K, VT, kmax, mult, O, B, H, H_kv, N, n_tiles, st)
+                : launch_fp8<64, false, false>(Q, K, VT, kmax, nullptr, O, B, H, H_kv, N, n_tiles, st);
+}
+
 // Scratch memory of sphattn_splitkv_fwd_noalloc: one array per GPU, part of the library's code
 // object, alive until the process ends.  Host code never uses the array's name as an address:
 // its device address is asked for once per device (scratch_address) and kept.
@@ -612,66 +683,27 @@ int sphattn_bwd(const void* Q, const void* K, const void* V, const void* O, cons
 
 size_t sphattn_fp8_workspace_bytes(int B, int H_kv, int N, int d)
 {
-    if (B <= 0 || H_kv <= 0 || N <= 0 || d != kFp8D) return 0;
+    if (B <= 0 || H_kv <= 0 || N <= 0 || (d != 64 && d != 128)) return 0;
     const size_t tiles = ((size_t)N + kFp8Tile - 1) / kFp8Tile;
     return (size_t)B * H_kv * d * tiles * kFp8Tile + (((size_t)B * H_kv * 4 + 255) & ~(size_t)255);
-}
-
-static int fp8_forward(const void* Q, const void* K, const void* V, void* O, void* workspace,
-                       size_t workspace_bytes, int B, int H, int H_kv, int N, int d, void* stream, bool softmax)
-{
-    if (d != kFp8D) return SPHATTN_ERR_HEAD_DIM;
-    if (!Q || !K || !V || !O) return SPHATTN_ERR_NULL;
-    const int rc = check_shape(B, H, H_kv, N, N, d, SPHATTN_FP8QK_BF16V);
-    if (rc != SPHATTN_OK) return rc;
-    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return SPHATTN_ERR_ALIGN;
-    const size_t in_bytes = (size_t)B * H * N * d, kv_bytes = (size_t)B * H_kv * N * d;
-    if (overlaps(O, in_bytes * 2, Q, in_bytes) || overlaps(O, in_bytes * 2, K, kv_bytes) ||
-        overlaps(O, in_bytes * 2, V, kv_bytes))
-        return SPHATTN_ERR_ALIAS;
-    const size_t need = sphattn_fp8_workspace_bytes(B, H_kv, N, d);
-    if (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < need) return SPHATTN_ERR_WORKSPACE;
-    if (overlaps(workspace, need, Q, in_bytes) || overlaps(workspace, need, K, kv_bytes) ||
-        overlaps(workspace, need, V, kv_bytes) || overlaps(workspace, need, O, in_bytes * 2))
-        return SPHATTN_ERR_ALIAS;
-    const int heads = B * H_kv;                    // K/V heads: what the preparation pass covers
-    const int n_tiles = (N + kFp8Tile - 1) / kFp8Tile;
-    const size_t kmax_bytes = ((size_t)heads * 4 + 255) & ~(size_t)255;
-    float* kmax = (float*)workspace;
-    unsigned char* VT = (unsigned char*)workspace + kmax_bytes;
-    hipStream_t st = (hipStream_t)stream;
-    if ((long long)heads * n_tiles > 0x7fffffff) return SPHATTN_ERR_SHAPE;
-    const int n_qtiles = (N + 255) / 256;
-    const long long n_wg = (long long)B * H * n_qtiles;
-    if (n_wg > 0x7fffffff) return SPHATTN_ERR_SHAPE;
-    // everything that can fail without a launch comes before the first launch
-    constexpr int lds_bytes = 4 * 2 * kFp8Tile * kFp8D;
-    static std::atomic<uint64_t> done{0}, done_twin{0};
-    static std::atomic<int> period[64], period_twin[64];
-    auto kern = softmax ? fwd_fp8_kernel<true> : fwd_fp8_kernel<false>;
-    if (!raise_lds_limit(kern, lds_bytes, softmax ? done_twin : done)) return SPHATTN_ERR_LAUNCH;
-    const int sp = stream_period(kern, lds_bytes, softmax ? period_twin : period);
-    hipLaunchKernelGGL(fp8_clear_kernel, dim3((heads + 255) / 256), dim3(256), 0, st, kmax, heads);
-    if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
-    hipLaunchKernelGGL(fp8_prepare_kernel, dim3((unsigned)(heads * n_tiles)), dim3(256), 0, st,
-                       (const unsigned char*)K, (const unsigned char*)V, VT, kmax, N, n_tiles);
-    if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, st,
-                       (const unsigned char*)Q, (const unsigned char*)K, (const unsigned char*)VT,
-                       (const float*)kmax, (unsigned short*)O, N, H, H / H_kv, n_tiles, n_qtiles, (int)n_wg, sp);
-    return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 
 int sphattn_fp8_fwd(const void* Q, const void* K, const void* V, void* O, void* workspace,
                     size_t workspace_bytes, int B, int H, int H_kv, int N, int d, void* stream)
 {
-    return fp8_forward(Q, K, V, O, workspace, workspace_bytes, B, H, H_kv, N, d, stream, false);
+    return fp8_forward(Q, K, V, nullptr, O, workspace, workspace_bytes, B, H, H_kv, N, d, stream, false);
+}
+
+int sphattn_fp8_grn_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O, void* workspace,
+                        size_t workspace_bytes, int B, int H, int H_kv, int N, int d, void* stream)
+{
+    return fp8_forward(Q, K, V, mult, O, workspace, workspace_bytes, B, H, H_kv, N, d, stream, false);
 }
 
 int sphattn_fp8_softmax_fwd(const void* Q, const void* K, const void* V, void* O, void* workspace,
                             size_t workspace_bytes, int B, int H, int H_kv, int N, int d, void* stream)
 {
-    return fp8_forward(Q, K, V, O, workspace, workspace_bytes, B, H, H_kv, N, d, stream, true);
+    return fp8_forward(Q, K, V, nullptr, O, workspace, workspace_bytes, B, H, H_kv, N, d, stream, true);
 }
 
 const char* sphattn_strerror(int code)
@@ -680,7 +712,7 @@ const char* sphattn_strerror(int code)
     case SPHATTN_OK: return "success";
     case SPHATTN_ERR_NULL: return "a required pointer is NULL";
     case SPHATTN_ERR_SHAPE: return "B, H, N must be positive, H_kv must divide H, and sizes must not overflow";
-    case SPHATTN_ERR_HEAD_DIM: return "head dimension d must be 64 or 128 (128 for the all-E4M3 forward)";
+    case SPHATTN_ERR_HEAD_DIM: return "head dimension d must be 64 or 128";
     case SPHATTN_ERR_DTYPE: return "unsupported dtype for this entry point";
     case SPHATTN_ERR_ALIGN: return "Q, K, V and O must be 16-byte aligned";
     case SPHATTN_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";

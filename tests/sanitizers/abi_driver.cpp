@@ -81,6 +81,9 @@ int main()
     EXPECT(sphattn_fp8_fwd(Q, K, V, O, W, need - 1, 1, 2, 2, 1000, 128, nullptr), SPHATTN_ERR_WORKSPACE);
     EXPECT(sphattn_fp8_fwd(Q, K, V, O, K, need, 1, 2, 2, 1000, 128, nullptr), SPHATTN_ERR_ALIAS);
     EXPECT(sphattn_fp8_fwd(Q, K, V, O, W, need, 1, 2, 2, 1000, 96, nullptr), SPHATTN_ERR_HEAD_DIM);
+    EXPECT(sphattn_fp8_workspace_bytes(1, 1, 130, 64), (size_t)64 * 256 + 256);
+    EXPECT(sphattn_fp8_grn_fwd(Q, K, V, (const float*)O, O, W, need, 1, 2, 2, 1000, 128, nullptr), SPHATTN_ERR_ALIAS);
+    EXPECT(sphattn_fp8_grn_fwd(Q, K, V, (const float*)P(0x5000001), O, W, need, 1, 2, 2, 1000, 128, nullptr), SPHATTN_ERR_ALIGN);
     EXPECT(sphattn_fp8_softmax_fwd(Q, K, V, O, W, need, 1, 3, 2, 1000, 128, nullptr), SPHATTN_ERR_SHAPE);
 
     for (int code = -12; code <= 1; ++code)

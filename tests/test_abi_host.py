@@ -228,7 +228,8 @@ def test_fp8_argument_errors_and_workspace_size(lib):
     # V^T padded to whole 128-key tiles (one byte per element) + one float per head, rounded up
     assert wsb(2, 3, 300, 128) == 2 * 3 * 128 * 384 + 256
     assert wsb(1, 1, 128, 128) == 128 * 128 + 256
-    assert wsb(1, 1, 128, 64) == 0 and wsb(0, 1, 128, 128) == 0 and wsb(1, 1, 0, 128) == 0
+    assert wsb(1, 1, 130, 64) == 64 * 256 + 256
+    assert wsb(1, 1, 128, 96) == 0 and wsb(0, 1, 128, 128) == 0 and wsb(1, 1, 0, 128) == 0
     need = wsb(1, 2, 1000, 128)
 
     def call(Q=0x1000000, K=0x2000000, V=0x3000000, O=0x4000000, ws=0x40000000, size=need, B=1, H=2, H_kv=2,
@@ -237,7 +238,8 @@ def test_fp8_argument_errors_and_workspace_size(lib):
     assert call(Q=0) == -1 and call(K=0) == -1 and call(V=0) == -1 and call(O=0) == -1
     assert call(N=0) == -2 and call(H=0) == -2 and call(H=3, H_kv=2) == -2
     assert call(H=4, H_kv=2, size=wsb(1, 2, 1000, 128) - 1) == -9   # the workspace is sized by H_kv
-    assert call(d=64) == -3 and call(d=96) == -3           # d = 128 only
+    assert call(d=96) == -3 and call(d=32) == -3           # d = 64 or 128
+    assert call(d=64, size=wsb(1, 2, 1000, 64) - 1) == -9
     assert call(V=0x3000008) == -5
     assert call(O=0x1000000) == -7                         # O is Q
     assert call(O=0x3000000 - 256) == -7                   # O runs into V
@@ -247,7 +249,13 @@ def test_fp8_argument_errors_and_workspace_size(lib):
     # the SoftMax twin shares the checks
     twin = lib.sphattn_fp8_softmax_fwd
     assert twin(P(0x1000000), P(0x2000000), P(0x3000000), P(0x4000000), P(0x40000000), need - 1, 1, 2, 2, 1000, 128, None) == -9
-    assert twin(P(0x1000000), P(0x2000000), P(0x3000000), P(0x4000000), P(0x40000000), need, 1, 2, 2, 1000, 64, None) == -3
+    assert twin(P(0x1000000), P(0x2000000), P(0x3000000), P(0x4000000), P(0x40000000), need, 1, 2, 2, 1000, 96, None) == -3
+    # multiplicities: alignment and overlap with what the call writes
+    grn = lib.sphattn_fp8_grn_fwd
+
+    def g(mult, O=0x4000000, ws=0x40000000):
+        return grn(P(0x1000000), P(0x2000000), P(0x3000000), P(mult), P(O), P(ws), need, 1, 2, 2, 1000, 128, None)
+    assert g(0x5000002) == -5 and g(0x4000000 + 64) == -7 and g(0x40000000 + 1024) == -7
 
 
 def test_bench_probe_library_argument_errors():

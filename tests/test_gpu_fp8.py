@@ -51,10 +51,13 @@ def oracle():
     return o
 
 
-def _run(pkg, q, k, v, slack=0):
+def _run(pkg, q, k, v, slack=0, mult=None):
     B, H, N, d = q.shape
     ws = torch.empty(pkg.sphattn_fp8_workspace_bytes(B, k.shape[1], N, d) + slack, dtype=torch.uint8, device=DEV)
-    out = pkg.sphattn_fp8_fwd(q.to(DEV), k.to(DEV), v.to(DEV), ws)
+    if mult is None:
+        out = pkg.sphattn_fp8_fwd(q.to(DEV), k.to(DEV), v.to(DEV), ws)
+    else:
+        out = pkg.sphattn_fp8_grn_fwd(q.to(DEV), k.to(DEV), v.to(DEV), mult.to(DEV), ws)
     torch.cuda.synchronize()
     return out.cpu().to(torch.float64).numpy()
 
@@ -128,6 +131,65 @@ def test_fp8_all_small_full_compare(pkg, oracle, B, H, N):
     print(f"case fp8-all B={B} H={H} N={N}", flush=True)
     q, k, v = si.make_qkv(B, H, N, 128, "fp8", seed=900 + N)
     _check(oracle, _run(pkg, q, k, v), q, k, v)
+
+
+@pytest.mark.parametrize("B,H,N", [(1, 1, 1), (1, 2, 33), (2, 2, 77), (1, 1, 128), (1, 3, 129), (1, 2, 256), (1, 1, 257),
+                                   (1, 2, 300), (1, 1, 1000), (2, 2, 513), (1, 1, 2176)])
+def test_fp8_all_d64_small_full_compare(pkg, oracle, B, H, N):
+    """Head dimension 64: the first contraction runs with half of its k-slots zero, the output
+    has four column blocks."""
+    print(f"case fp8-all d=64 B={B} H={H} N={N}", flush=True)
+    q, k, v = si.make_qkv(B, H, N, 64, "fp8", seed=1900 + N)
+    _check(oracle, _run(pkg, q, k, v), q, k, v)
+
+
+def _counts(B, N, seed):
+    """Gene counts of a cell: mostly small integers, some zeros (genes that are absent)."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return torch.poisson(torch.full((B, N), 1.5), generator=g).to(torch.float32)
+
+
+@pytest.mark.parametrize("B,H,H_kv,N,d", [(1, 1, 1, 1, 128), (1, 2, 2, 33, 128), (2, 2, 1, 77, 64), (1, 3, 3, 129, 128),
+                                          (1, 2, 2, 256, 64), (1, 4, 2, 300, 128), (1, 1, 1, 1000, 64),
+                                          (2, 2, 2, 513, 128), (1, 2, 1, 2176, 128)])
+def test_fp8_all_multiplicities(pkg, oracle, B, H, H_kv, N, d):
+    """s_ij = mult_j (q_i . k_j) (paper, Section 3.1), with shared K/V heads, both head dimensions,
+    ragged N: against the oracle's gene-regulatory-network variant on K, V repeated per group."""
+    print(f"case fp8-all multiplicities B={B} H={H} H_kv={H_kv} N={N} d={d}", flush=True)
+    q, _, _ = si.make_qkv(B, H, N, d, "fp8", seed=2970 + N)
+    _, k, v = si.make_qkv(B, H_kv, N, d, "fp8", seed=2980 + N)
+    mult = _counts(B, N, 31 + N)
+    if N == 1:
+        mult[:] = 3.0
+    got = _run(pkg, q, k, v, mult=mult)
+    rep = H // H_kv
+    k_full = k.view(torch.uint8).repeat_interleave(rep, dim=1).view(torch.float8_e4m3fn)
+    v_full = v.view(torch.uint8).repeat_interleave(rep, dim=1).view(torch.float8_e4m3fn)
+    _check(oracle, got, q, k_full, v_full, mult=mult.numpy().astype(np.float64))
+
+
+def test_fp8_all_multiplicities_that_differ_by_orders_of_magnitude(pkg, oracle):
+    """One gene counted 500 times among genes counted once: it sets the row bound for every row."""
+    print("case fp8-all large multiplicity", flush=True)
+    q, k, v = si.make_qkv(1, 2, 400, 128, "fp8", seed=61)
+    mult = torch.ones((1, 400), dtype=torch.float32)
+    mult[0, 123] = 500.0
+    mult[0, 7] = 0.0
+    got = _run(pkg, q, k, v, mult=mult)
+    _check(oracle, got, q, k, v, mult=mult.numpy().astype(np.float64))
+
+
+def test_fp8_all_without_multiplicities_equals_plain_call(pkg):
+    q, k, v = (t.to(DEV) for t in si.make_qkv(1, 2, 700, 64, "fp8", seed=62))
+    ws = torch.empty(pkg.sphattn_fp8_workspace_bytes(1, 2, 700, 64), dtype=torch.uint8, device=DEV)
+    a = pkg.sphattn_fp8_fwd(q, k, v, ws).clone()
+    b = pkg.sphattn_fp8_grn_fwd(q, k, v, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    ones = torch.ones((1, 700), dtype=torch.float32, device=DEV)
+    c = pkg.sphattn_fp8_grn_fwd(q, k, v, ones, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), c.view(torch.int16))
 
 
 @pytest.mark.parametrize("factor", [2.0 ** -6, 30.0])
@@ -235,10 +297,10 @@ def test_fp8_all_argument_errors_on_device(pkg):
     with pytest.raises(pkg.SphattnError) as e:
         pkg.sphattn_fp8_fwd(q, k, v, small)
     assert e.value.code == -9
-    q64, k64, v64 = (t.to(DEV) for t in si.make_qkv(1, 1, 64, 64, "fp8", seed=1))
+    q96 = torch.zeros((1, 1, 64, 96), dtype=torch.float8_e4m3fn, device=DEV)
     ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
     with pytest.raises(pkg.SphattnError) as e:
-        pkg.sphattn_fp8_fwd(q64, k64, v64, ws)
+        pkg.sphattn_fp8_fwd(q96, q96, q96, ws)
     assert e.value.code == -3
 
 
@@ -246,16 +308,17 @@ def test_fp8_all_argument_errors_on_device(pkg):
 TWIN_RMS, TWIN_MAX = 0.04, 0.25
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("B,H,N", [(1, 1, 77), (1, 2, 128), (2, 1, 300), (1, 1, 1000), (1, 2, 2049)])
-def test_fp8_all_softmax_twin(pkg, oracle, B, H, N):
+def test_fp8_all_softmax_twin(pkg, oracle, B, H, N, d):
     """The all-E4M3 SoftMax twin against the oracle's SoftMax, on inputs of moderate size (N(0, 0.5)
     cast to E4M3).  Its weights are rounded to E4M3 like the spherical variant's scores, so the same
     statistical bounds apply: rms(err) <= 0.04 rms(O), max <= 0.25 rms(O).  Ragged N checks that
     keys past the end get no weight (a zero key row would get exp(-shift) > 0)."""
-    print(f"case fp8-all softmax twin B={B} H={H} N={N}", flush=True)
-    qf, kf, vf = si.gaussian_qkv(B, H, N, 128, seed=950 + N, factor=0.5)
+    print(f"case fp8-all softmax twin B={B} H={H} N={N} d={d}", flush=True)
+    qf, kf, vf = si.gaussian_qkv(B, H, N, d, seed=950 + N, factor=0.5)
     q, k, v = (t.to(torch.float8_e4m3fn) for t in (qf, kf, vf))
-    ws = torch.empty(pkg.sphattn_fp8_workspace_bytes(B, H, N, 128), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(pkg.sphattn_fp8_workspace_bytes(B, H, N, d), dtype=torch.uint8, device=DEV)
     out = pkg.sphattn_fp8_softmax_fwd(q.to(DEV), k.to(DEV), v.to(DEV), ws)
     torch.cuda.synchronize()
     got = out.cpu().to(torch.float64).numpy()
