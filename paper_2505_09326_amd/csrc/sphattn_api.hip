@@ -322,16 +322,16 @@ struct BwdProblem {
     hipStream_t stream;
 };
 
-template <int D, bool HALF, bool MULT>
+template <int D, bool HALF, bool MULT, int NK>
 int launch_bwd(const BwdProblem& p)
 {
     constexpr int tile = kBC * D * 2;
     constexpr int lds_dq = 2 * (2 * tile + (MULT ? kBC * 4 : 0)), lds_dkv = 2 * (2 * tile + 2 * kBC * 4);
     auto kq = bwd_dq_kernel<D, HALF, MULT>;
-    auto kkv = bwd_dkv_kernel<D, HALF, MULT>;
+    auto kkv = bwd_dkv_kernel<D, HALF, MULT, NK>;
     static std::atomic<uint64_t> done_q{0}, done_kv{0};
     if (!raise_lds_limit(kq, lds_dq, done_q) || !raise_lds_limit(kkv, lds_dkv, done_kv)) return SPHATTN_ERR_LAUNCH;
-    const int n_qtiles = (p.N + 255) / 256, n_ktiles = (p.N + 127) / 128;
+    const int n_qtiles = (p.N + 255) / 256, n_ktiles = (p.N + 64 * NK - 1) / (64 * NK);
     const long long wg_q = (long long)p.B * p.H * n_qtiles, wg_kv = (long long)p.B * p.H_kv * n_ktiles;
     if (wg_q > 0x7fffffff || wg_kv > 0x7fffffff) return SPHATTN_ERR_SHAPE;
     const int kv_group = p.H / p.H_kv;
@@ -348,8 +348,8 @@ int launch_bwd(const BwdProblem& p)
 template <bool MULT>
 int dispatch_bwd(const BwdProblem& p, int d, int dtype)
 {
-    if (dtype == SPHATTN_F16) return d == 128 ? launch_bwd<128, true, MULT>(p) : launch_bwd<64, true, MULT>(p);
-    return d == 128 ? launch_bwd<128, false, MULT>(p) : launch_bwd<64, false, MULT>(p);
+    if (dtype == SPHATTN_F16) return d == 128 ? launch_bwd<128, true, MULT, 2>(p) : launch_bwd<64, true, MULT, 2>(p);
+    return d == 128 ? launch_bwd<128, false, MULT, 2>(p) : launch_bwd<64, false, MULT, 2>(p);
 }
 
 size_t workspace_bytes(int B, int H, int N, int d, int n_splits)

@@ -228,18 +228,23 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
 // dK and dV.  Workgroup = 4 waves x 32 keys (two blocks of 16).  Streams Q/dO tiles of 64
 // queries together with their z and delta.
 // ---------------------------------------------------------------------------
-// Two workgroups per CU (two waves per SIMD): a fragment feeds only two matrix instructions
-// here, so a second wave fills the gaps that the LDS reads leave (one wave per SIMD with the
-// same step sequence measured slower at d = 128).
-template <int D, bool HALF, bool MULT>
-__global__ __launch_bounds__(kThreads, 2)
+// NK = key blocks of 16 per wave.  Every LDS fragment feeds NK matrix instructions of each
+// product, so NK sets the LDS instructions per matrix instruction (0.75 at NK = 2; 0.5 at 3;
+// 0.375 at 4, the forward's ratio).  The accumulators (2 NK D / 4 registers) bound it: NK = 2
+// leaves room for two workgroups per CU (two waves per SIMD), NK = 3 (d = 128) and NK = 4
+// (d = 64) fill the register file with one.  Measured with this step sequence (C3 / C4
+// shapes): NK = 2 1.85 / 1.98 ms, NK = 3 2.29 / 2.05 ms, NK = 4 (d = 64) 2.14 ms: with one
+// wave per SIMD the second wave's latency hiding is worth more than the saved LDS reads, so
+// the library launches NK = 2.
+template <int D, bool HALF, bool MULT, int NK>
+__global__ __launch_bounds__(kThreads, NK == 2 ? 2 : 1)
 void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, const void* __restrict__ Vv,
                     const float* __restrict__ mult,
                     const void* __restrict__ dOv, const float* __restrict__ Z, const float* __restrict__ delta,
                     void* __restrict__ dKv, void* __restrict__ dVv,
                     int N, int H, int kv_group, int n_ktiles, int n_wg)
 {
-    constexpr int BC = kBC, NK = 2, BKEYS = kWaves * 16 * NK;
+    constexpr int BC = kBC, BKEYS = kWaves * 16 * NK;
     constexpr int ROWB = D * 2, TILE = BC * ROWB;
     constexpr int KK = D / 32, DB = D / 16, KBLK = ROWB / 64;
     constexpr int GLDS = TILE, ZLDS = 2 * TILE, DLDS = 2 * TILE + BC * 4;   // Q tile, dO tile, z, delta

@@ -492,7 +492,9 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
         }
     }
 
-    // ---- tail: O_i = o_i / sqrt(z_i); the row factor cancels
+    // ---- tail: O_i = o_i / sqrt(z_i); the row factor cancels.  Non-temporal stores only when
+    // later batches of workgroups follow (see fwd_pipelined_kernel).
+    const bool stream_out = stream_period > 0 && n_wg > kXcds * stream_period;
     unsigned short* Oh = O + (size_t)bh * N * D;
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
@@ -513,7 +515,8 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
             for (int db = 0; db < DB; ++db) {
                 const i32x2 o4 = {pack2<false>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
                                   pack2<false>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
-                __builtin_nontemporal_store(o4, reinterpret_cast<i32x2*>(dst + db * 16));
+                if (stream_out) __builtin_nontemporal_store(o4, reinterpret_cast<i32x2*>(dst + db * 16));
+                else *reinterpret_cast<i32x2*>(dst + db * 16) = o4;
             }
         }
     }

@@ -587,6 +587,10 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     }
 
     // ---- tail t(o, z) = o / b(z): spherical b = sqrt, the others b = id
+    // O goes past the L2's retention only when later batches of workgroups will want the K/V
+    // stream from it; a launch that fits the chip in one batch gains nothing from that, and its
+    // last stores would complete later (measured on 256 workgroups of 32 tiles: 30.9 against 28.9 us).
+    const bool stream_out = stream_period > 0 && n_wg > kXcds * stream_period;
     unsigned short* Oh = (unsigned short*)Ov + head_off;
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
@@ -609,7 +613,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
             for (int db = 0; db < DB; ++db) {
                 const i32x2 o4 = {pack2<HALF>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
                                   pack2<HALF>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
-                __builtin_nontemporal_store(o4, reinterpret_cast<i32x2*>(dst + db * 16));
+                if (stream_out) __builtin_nontemporal_store(o4, reinterpret_cast<i32x2*>(dst + db * 16));
+                else *reinterpret_cast<i32x2*>(dst + db * 16) = o4;
             }
         }
     }
