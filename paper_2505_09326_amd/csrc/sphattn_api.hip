@@ -186,10 +186,14 @@ int launch_pipelined(const Problem& p)
     const long long n_wg = (long long)p.B * p.H * n_qtiles * p.n_splits;
     if (n_wg > 0x7fffffff) return SPHATTN_ERR_SHAPE;
     const float scale_log2 = 1.4426950408889634f / __builtin_sqrtf((float)D);
-    hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(kThreads), lds_bytes, p.stream,
+    // persistent workgroups: as many as the chip runs at once (a multiple of the XCD count), or
+    // one per item if that is fewer
+    const long long resident = (long long)kXcds * stream_period(kern, lds_bytes, period);
+    const long long grid = resident > 0 && resident < n_wg ? resident : n_wg;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds_bytes, p.stream,
                        p.Q, p.K, p.V, p.O, p.mult, p.Z,
                        p.Nq, p.Nk, p.H, p.H / p.H_kv, n_qtiles, (int)n_wg,
-                       p.n_splits, p.keys_per_split, scale_log2, stream_period(kern, lds_bytes, period));
+                       p.n_splits, p.keys_per_split, scale_log2);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 

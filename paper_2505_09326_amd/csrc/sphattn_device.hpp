@@ -15,6 +15,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 
@@ -61,7 +62,6 @@ __device__ __forceinline__ i32x4 lds_read_b128(const SPH_LDS unsigned char* p)
     return *reinterpret_cast<const SPH_LDS i32x4*>(p);
 }
 
-typedef __attribute__((ext_vector_type(2))) int i32x2;
 
 // ds_read_b64_tr_b16: each lane supplies the address of 4 consecutive 16-bit elements; within
 // every block of 16 lanes the 16 x 4 elements are transposed, so lane i receives element (i & 3)
@@ -120,6 +120,16 @@ __device__ __forceinline__ float sum_across_halves(float x)
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+
+// 8-byte store at byte `offset` of the buffer, ordinary or non-temporal (past the L2's retention).
+// The policy is an immediate of the instruction; written as two buffer stores rather than as a
+// pointer store with and without the non-temporal hint, which the compiler merges into one
+// ordinary store when both sit in the arms of a branch.
+__device__ __forceinline__ void store_b64(__amdgpu_buffer_rsrc_t rsrc, int offset, i32x2 v, bool non_temporal)
+{
+    if (non_temporal) __builtin_amdgcn_raw_buffer_store_b64(v, rsrc, offset, 0, 2);   // aux 2: nt
+    else __builtin_amdgcn_raw_buffer_store_b64(v, rsrc, offset, 0, 0);
 }
 
 // ---------------------------------------------------------------------------

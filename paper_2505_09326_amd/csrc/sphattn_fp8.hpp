@@ -495,7 +495,7 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     // ---- tail: O_i = o_i / sqrt(z_i); the row factor cancels.  Non-temporal stores only when
     // later batches of workgroups follow (see fwd_pipelined_kernel).
     const bool stream_out = stream_period > 0 && n_wg > kXcds * stream_period;
-    unsigned short* Oh = O + (size_t)bh * N * D;
+    const __amdgpu_buffer_rsrc_t orw = make_rsrc(O + (size_t)bh * N * D, (uint32_t)N * D * 2);
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
         // z_i: the diagonal element of query n16 (row 4g + t = n16) is held by lane group n16 / 4
@@ -510,13 +510,12 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
         }
         const int row = q0 + qb * 16 + n16;
         if (row < N) {
-            unsigned short* dst = Oh + (size_t)row * D + 4 * g;
+            const int dst = (row * D + 4 * g) * 2;             // byte offset in the head's O
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
                 const i32x2 o4 = {pack2<false>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
                                   pack2<false>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
-                if (stream_out) __builtin_nontemporal_store(o4, reinterpret_cast<i32x2*>(dst + db * 16));
-                else *reinterpret_cast<i32x2*>(dst + db * 16) = o4;
+                store_b64(orw, dst + db * 32, o4, stream_out);
             }
         }
     }

@@ -114,13 +114,16 @@ __device__ __forceinline__ void copy_to_lds(i32x4 rsrc, uint32_t lds, int voff, 
                  :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
 
-template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
-__global__ __launch_bounds__(kThreads, 1)
-void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv,
-                          const void* __restrict__ Vv, void* __restrict__ Ov,
-                          const float* __restrict__ mult, float* __restrict__ Zv,
-                          int Nq, int Nk, int H, int kv_group, int n_qtiles, int n_wg,
-                          int n_splits, int keys_per_split, float scale_log2, int stream_period)
+// One work item: the query tile (and key slice) number `item` of the launch's n_items, streamed
+// forwards or backwards over its keys.  Called by every thread of the workgroup.
+template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL>
+__device__ __forceinline__
+void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv,
+                        const void* __restrict__ Vv, void* __restrict__ Ov,
+                        const float* __restrict__ mult, float* __restrict__ Zv,
+                        int Nq, int Nk, int H, int kv_group, int n_qtiles, int n_items,
+                        int n_splits, int keys_per_split, float scale_log2,
+                        int item, bool backwards, bool stream_out)
 {
     constexpr bool FP8 = QKT == QKType::Fp8;
     constexpr bool HALF = QKT == QKType::F16;      // 16-bit type of V, O and P
@@ -174,7 +177,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     const int lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, g = lane >> 4;
 
-    const int lid = xcd_contiguous_id(blockIdx.x, n_wg);
+    const int lid = xcd_contiguous_id(item, n_items);
     // consecutive ids: the query tiles of one (head, key slice), which stream the same K/V
     const int qt = lid % n_qtiles;
     const int split = PARTIAL ? (lid / n_qtiles) % n_splits : 0;
@@ -264,14 +267,8 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     };
 
     const int n_tiles = (N + BC - 1) / BC;
-    // Direction of the key stream.  The workgroups that an XCD runs at the same time (stream_period
-    // consecutive ones of its contiguous range) stream one head's K/V together through that XCD's
-    // L2.  When a head has more query tiles than that, the next batch streams the same K/V again;
-    // if the head's K/V is larger than the L2, what the first batch left there is the END of the
-    // stream, so every other batch walks the keys backwards and starts on what is still resident
-    // (a sum over keys: any order gives the same accumulator up to fp32 rounding).  Tiles past
-    // the end (the pipeline runs two ahead) map past the end in either direction.
-    const bool backwards = stream_period > 0 && (((int)blockIdx.x / kXcds) / stream_period) % 2 == 1;
+    // Direction of the key stream: see fwd_pipelined_kernel.  Tiles past the end (the pipeline
+    // runs two ahead) map past the end in either direction.
     auto src_tile = [&](int t) { return t >= n_tiles ? n_tiles : backwards ? n_tiles - 1 - t : t; };
 
     // copy c (K: c < LDK, V: the rest) of this wave's share of tile `tile` into buffer `buf`.
@@ -569,7 +566,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
 
     // ---- partial result: the pair (o, z) as it stands, in fp32
     if constexpr (PARTIAL) {
-        const size_t rows0 = ((size_t)split * (n_wg / (n_qtiles * n_splits)) + bh) * Nq;
+        const size_t rows0 = ((size_t)split * (n_items / (n_qtiles * n_splits)) + bh) * Nq;
         float* Op = (float*)Ov + rows0 * D;
         float* Zp = Zv + rows0;
 #pragma unroll
@@ -587,11 +584,7 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
     }
 
     // ---- tail t(o, z) = o / b(z): spherical b = sqrt, the others b = id
-    // O goes past the L2's retention only when later batches of workgroups will want the K/V
-    // stream from it; a launch that fits the chip in one batch gains nothing from that, and its
-    // last stores would complete later (measured on 256 workgroups of 32 tiles: 30.9 against 28.9 us).
-    const bool stream_out = stream_period > 0 && n_wg > kXcds * stream_period;
-    unsigned short* Oh = (unsigned short*)Ov + head_off;
+    const __amdgpu_buffer_rsrc_t orw = make_rsrc((unsigned short*)Ov + head_off, (uint32_t)Nq * D * 2);
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
         float inv, z;
@@ -608,15 +601,52 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
         const int row = q0 + qb * 16 + n16;
         if (row < Nq) {
             if (Zv != nullptr && g == 0) Zv[(size_t)bh * Nq + row] = z;
-            unsigned short* dst = Oh + (size_t)row * D + 4 * g;
+            const int dst = (row * D + 4 * g) * 2;             // byte offset in the head's O
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
                 const i32x2 o4 = {pack2<HALF>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
                                   pack2<HALF>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
-                if (stream_out) __builtin_nontemporal_store(o4, reinterpret_cast<i32x2*>(dst + db * 16));
-                else *reinterpret_cast<i32x2*>(dst + db * 16) = o4;
+                store_b64(orw, dst + db * 32, o4, stream_out);
             }
         }
+    }
+}
+
+// The kernel: PERSISTENT workgroups.  The launch has n_items work items (query tile x key slice
+// x head) and at most as many workgroups as the chip runs at once; workgroup w takes the items
+// w, w + gridDim, w + 2 gridDim, ...  Letting the hardware start a fresh workgroup per item
+// instead costs the time between the last wave of one workgroup leaving a CU and the first of
+// the next arriving (measured on 4 items per CU of 173 us each: 11 us per change, 4.5 % of the
+// launch), during which the CU's matrix pipes idle.
+//
+// Workgroup ids are dealt round-robin to the XCDs and gridDim is a multiple of the number of
+// XCDs (or the launch is a single batch), so every item of a workgroup falls into that XCD's
+// contiguous range of (head, query tile) pairs, and the workgroups of an XCD work on
+// consecutive tiles of one head at the same time: they stream the same K/V through one L2.
+//
+// Direction of the key stream.  When a head has more query tiles than an XCD runs at once, the
+// next batch streams the same K/V again; if the head's K/V is larger than the L2, what the first
+// batch left there is the END of the stream, so every other batch walks the keys backwards and
+// starts on what is still resident (a sum over keys: any order gives the same accumulator up to
+// fp32 rounding).  O goes past the L2's retention (non-temporal stores) only when later batches
+// follow; a one-batch launch gains nothing from that, and its last stores would complete later
+// (measured on 256 workgroups of 32 tiles: 30.9 against 28.9 us).
+template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
+__global__ __launch_bounds__(kThreads, 1)
+void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv,
+                          const void* __restrict__ Vv, void* __restrict__ Ov,
+                          const float* __restrict__ mult, float* __restrict__ Zv,
+                          int Nq, int Nk, int H, int kv_group, int n_qtiles, int n_items,
+                          int n_splits, int keys_per_split, float scale_log2)
+{
+    const bool several_batches = n_items > (int)gridDim.x;
+    int batch = 0;
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x, ++batch) {
+        // the LDS buffers change hands: every wave must be done with the previous item's tiles
+        if (batch > 0) __syncthreads();
+        fwd_pipelined_item<D, NQ, QKT, NORM, MULT, PARTIAL>(Qv, Kv, Vv, Ov, mult, Zv, Nq, Nk, H, kv_group, n_qtiles, n_items,
+                                                            n_splits, keys_per_split, scale_log2,
+                                                            item, batch % 2 == 1, several_batches);
     }
 }
 
