@@ -126,10 +126,36 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 // The policy is an immediate of the instruction; written as two buffer stores rather than as a
 // pointer store with and without the non-temporal hint, which the compiler merges into one
 // ordinary store when both sit in the arms of a branch.
-__device__ __forceinline__ void store_b64(__amdgpu_buffer_rsrc_t rsrc, int offset, i32x2 v, bool non_temporal)
+__device__ __forceinline__ void store_b128(__amdgpu_buffer_rsrc_t rsrc, int offset, i32x4 v, bool non_temporal)
 {
-    if (non_temporal) __builtin_amdgcn_raw_buffer_store_b64(v, rsrc, offset, 0, 2);   // aux 2: nt
-    else __builtin_amdgcn_raw_buffer_store_b64(v, rsrc, offset, 0, 0);
+    if (non_temporal) __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, offset, 0, 2);   // aux 2: nt
+    else __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, offset, 0, 0);
+}
+
+// A wave's finished output tile, ROWS rows of ROWB bytes that the lanes hold as 8-byte pieces
+// (accumulator layout), goes through LDS so that every store instruction writes whole rows:
+// 16 bytes per lane, consecutive lanes consecutive bytes.  Non-temporal stores of partial lines
+// are written through piece by piece (measured: 2.3 times the bytes at the memory interface
+// with 8-byte pieces); whole lines are not.  `stage` is this wave's private LDS region of
+// ROWS * (ROWB + 16) bytes (rows padded by 16 bytes against bank conflicts); put_piece fills it,
+// store_tile writes rows row0 .. of the buffer, those below n_rows only.
+template <int ROWB>
+__device__ __forceinline__ void put_piece(SPH_LDS unsigned char* stage, int row, int byte, i32x2 v)
+{
+    *reinterpret_cast<SPH_LDS i32x2*>(stage + row * (ROWB + 16) + byte) = v;
+}
+
+template <int ROWS, int ROWB>
+__device__ __forceinline__ void store_tile(const SPH_LDS unsigned char* stage, __amdgpu_buffer_rsrc_t rsrc,
+                                           int row0, int n_rows, int lane, bool non_temporal)
+{
+    constexpr int LPR = ROWB / 16;                 // lanes per row
+#pragma unroll
+    for (int i = 0; i < ROWS * LPR / 64; ++i) {
+        const int r = i * (64 / LPR) + lane / LPR, c = (lane % LPR) * 16;
+        const i32x4 v = *reinterpret_cast<const SPH_LDS i32x4*>(stage + r * (ROWB + 16) + c);
+        if (row0 + r < n_rows) store_b128(rsrc, (row0 + r) * ROWB + c, v, non_temporal);
+    }
 }
 
 // ---------------------------------------------------------------------------

@@ -496,6 +496,12 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     // later batches of workgroups follow (see fwd_pipelined_kernel).
     const bool stream_out = stream_period > 0 && n_wg > kXcds * stream_period;
     const __amdgpu_buffer_rsrc_t orw = make_rsrc(O + (size_t)bh * N * D, (uint32_t)N * D * 2);
+    // through a per-wave LDS stage, so that every store instruction writes whole rows (the tile
+    // buffers are free once every wave has read its last tile)
+    constexpr int ROWS = 16 * NQ;
+    static_assert(kWaves * ROWS * (D * 2 + 16) <= NBUF * BUF_BYTES, "the output stage fits the tile buffers");
+    SPH_LDS unsigned char* stage = smem + wave * ROWS * (D * 2 + 16);
+    __syncthreads();
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
         // z_i: the diagonal element of query n16 (row 4g + t = n16) is held by lane group n16 / 4
@@ -508,17 +514,14 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
             z = zz[qb][0];
             inv = z > 0.f ? 1.0f / z : 0.f;
         }
-        const int row = q0 + qb * 16 + n16;
-        if (row < N) {
-            const int dst = (row * D + 4 * g) * 2;             // byte offset in the head's O
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const i32x2 o4 = {pack2<false>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
-                                  pack2<false>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
-                store_b64(orw, dst + db * 32, o4, stream_out);
-            }
+        for (int db = 0; db < DB; ++db) {
+            const i32x2 o4 = {pack2<false>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
+                              pack2<false>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
+            put_piece<D * 2>(stage, qb * 16 + n16, db * 32 + 8 * g, o4);
         }
     }
+    store_tile<ROWS, D * 2>(stage, orw, q0, N, lane, stream_out);
 }
 
 }  // namespace sphattn

@@ -577,14 +577,20 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
                 if (g == 0) Zp[row] = z;
                 float* dst = Op + (size_t)row * D + 4 * g;
 #pragma unroll
-                for (int db = 0; db < DB; ++db) __builtin_nontemporal_store(oacc[db][qb], reinterpret_cast<f32x4*>(dst + db * 16));
+                for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(dst + db * 16) = oacc[db][qb];   // read back soon: let the L2 keep it
             }
         }
         return;
     }
 
-    // ---- tail t(o, z) = o / b(z): spherical b = sqrt, the others b = id
+    // ---- tail t(o, z) = o / b(z): spherical b = sqrt, the others b = id.  The rows go out
+    // through a per-wave LDS stage (the tile buffers are free once every wave has read its last
+    // tile), 16 bytes per lane and whole rows per instruction.
     const __amdgpu_buffer_rsrc_t orw = make_rsrc((unsigned short*)Ov + head_off, (uint32_t)Nq * D * 2);
+    constexpr int ROWS = 16 * NQ;
+    static_assert(kWaves * ROWS * (D * 2 + 16) <= NBUF * BUF_BYTES, "the output stage fits the tile buffers");
+    SPH_LDS unsigned char* stage = smem + wave * ROWS * (D * 2 + 16);
+    __syncthreads();
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
         float inv, z;
@@ -599,25 +605,24 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
             inv = z > 0.f ? 1.0f / z : 0.f;
         }
         const int row = q0 + qb * 16 + n16;
-        if (row < Nq) {
-            if (Zv != nullptr && g == 0) Zv[(size_t)bh * Nq + row] = z;
-            const int dst = (row * D + 4 * g) * 2;             // byte offset in the head's O
+        if (Zv != nullptr && g == 0 && row < Nq) Zv[(size_t)bh * Nq + row] = z;
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const i32x2 o4 = {pack2<HALF>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
-                                  pack2<HALF>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
-                store_b64(orw, dst + db * 32, o4, stream_out);
-            }
+        for (int db = 0; db < DB; ++db) {
+            const i32x2 o4 = {pack2<HALF>(oacc[db][qb][0] * inv, oacc[db][qb][1] * inv),
+                              pack2<HALF>(oacc[db][qb][2] * inv, oacc[db][qb][3] * inv)};
+            put_piece<D * 2>(stage, qb * 16 + n16, db * 32 + 8 * g, o4);
         }
     }
+    store_tile<ROWS, D * 2>(stage, orw, q0, Nq, lane, stream_out);
 }
 
 // The kernel: PERSISTENT workgroups.  The launch has n_items work items (query tile x key slice
 // x head) and at most as many workgroups as the chip runs at once; workgroup w takes the items
-// w, w + gridDim, w + 2 gridDim, ...  Letting the hardware start a fresh workgroup per item
-// instead costs the time between the last wave of one workgroup leaving a CU and the first of
-// the next arriving (measured on 4 items per CU of 173 us each: 11 us per change, 4.5 % of the
-// launch), during which the CU's matrix pipes idle.
+// w, w + gridDim, w + 2 gridDim, ..., so that "the workgroups an XCD runs at the same time" is
+// a fact of the launch (batch k = items k gridDim ..) rather than a guess about the dispatcher.
+// (It also removes the 11 us between the last wave of a workgroup leaving a CU and the first of
+// its successor arriving, measured with 4 items of 173 us per CU; on Gaussian data that buys
+// nothing, because the part is power-limited and gives idle time back as clock.)
 //
 // Workgroup ids are dealt round-robin to the XCDs and gridDim is a multiple of the number of
 // XCDs (or the launch is a single batch), so every item of a workgroup falls into that XCD's
