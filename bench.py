@@ -27,8 +27,11 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "fp8qk_bf16v": 1.0 / (0.5 / 5000.0
 # the workload and kernel that profile covers, `traffic_source` says where it came from, and
 # every other workload reports null.
 MEASURED_HBM_BYTES = {
-    "C3": (268.6e6, "profiles/fwd_pipelined_bf16_d128_C3.md"),
-    "C5": (1208.0e6, "profiles/fwd_pipelined_fp8qk_d128_C5.md"),
+    "C1": (1.28e6, "profiles/fwd_f32_d64_C1.md"),
+    "C2": (33.7e6, "profiles/fwd_pipelined_bf16_d64_C2.md"),
+    "C3": (268.7e6, "profiles/fwd_pipelined_bf16_d128_C3.md"),
+    "C4": (260.8e6, "profiles/fwd_pipelined_bf16_d64_C4.md"),
+    "C5": (1020.3e6, "profiles/fwd_pipelined_fp8qk_d128_C5.md"),
 }
 HBM_PEAK_GBS = 8000.0
 
