@@ -188,7 +188,12 @@ def main() -> int:
     # limit, which take milliseconds of idle GPU, do not fall between the probe and the steps.)
     step()
     torch.cuda.synchronize()
-    ceil = measure_mfma_ceiling(args, si, dev) if not args.no_mfma_ceiling else None
+    ceil = None
+    if not args.no_mfma_ceiling:
+        try:
+            ceil = measure_mfma_ceiling(args, si, dev)
+        except ImportError as e:               # the probe is a measurement aid: the benchmark runs without it
+            print(f"bench.py: {e}; continuing without the matrix-only ceiling", file=sys.stderr)
 
     ms_wall, per = time_launches(step, args.steps, args.warmup)
     ms_kernel = sum(per) / len(per)
@@ -344,7 +349,7 @@ def main() -> int:
                 "spherical_speedup": ms_b / ms_a,
                 "form": "same kernel; shift by the Cauchy-Schwarz bound instead of a running maximum, no rescaling",
             }
-        if not args.no_mfma_ceiling:
+        if ceil is not None:
             result["fp8_all_variant"]["frac_of_mfma_only_ceiling"] = tf8 / ceil["16x16x128_e4m3"]["tflops"]
             # what the exponential costs at the fp8 matrix rate (paper, Section 1): the same loop
             # of matrix instructions with an L2 kernel's, or a SoftMax kernel's, other per-score
