@@ -267,7 +267,8 @@ int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype);
  *                    anything else returns SPHATTN_ERR_DTYPE); O and Z as sphattn_fwd_z wrote them.
  *   Z              : [B,H,N] fp32, the row aggregates z_i.
  *   dQ, dK, dV     : [B,H,N,d] in the same 16-bit format, written in full.
- *   delta          : [B,H,N] fp32 scratch from the caller; receives delta_i.
+ *   delta          : [B,H,N] fp32 scratch from the caller; the first launch leaves delta_i r_i^2 there
+ *                    for the second.
  * Outputs and scratch must not overlap each other or the inputs.  Two launches on `stream`.
  * Other arguments and errors as sphattn_fwd.
  */

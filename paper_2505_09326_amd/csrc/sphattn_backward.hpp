@@ -11,7 +11,7 @@
 // Nothing N x N is stored: the scores are recomputed tile by tile, as in the forward.  Two
 // kernels, no atomics, so the result does not depend on the launch:
 //   bwd_dq_kernel   a workgroup owns 256 query rows and streams the keys: S^T = K Q^T,
-//                   G^T = V dO^T, dS^T in registers, dQ^T += K^T dS^T.  Also writes delta.
+//                   G^T = V dO^T, dS^T in registers, dQ^T += K^T dS^T.  Also writes delta_i r_i^2.
 //   bwd_dkv_kernel  a workgroup owns 128 keys and streams the queries: S = Q K^T, G = dO V^T,
 //                   W and dS in registers, dV^T += dO^T W, dK^T += Q^T dS.
 // Both use the forward's building blocks: 16x16x32 matrix instructions with the product
@@ -105,7 +105,8 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
         const float r = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
         c1[qb] = r;
         c2[qb] = dsum * r * r;
-        if (live && g == 0) delta[(size_t)bh * N + row] = dsum;
+        // for the dK/dV kernel: delta_i r_i^2, the factor of s_ij in ds_ij, so that it need not form it
+        if (live && g == 0) delta[(size_t)bh * N + row] = c2[qb];
     }
 
     f32x4 dq[DB][NQ];
@@ -355,7 +356,7 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 r[t] = zq[t] > 0.f ? __builtin_amdgcn_rsqf(zq[t]) : 0.f;   // v_rsq_f32, 1 ulp
-                c[t] = dq_[t] * r[t] * r[t];
+                c[t] = dq_[t];                     // delta_i r_i^2, as the dQ kernel left it
             }
 #pragma unroll
             for (int kb = 0; kb < NK; ++kb) {
