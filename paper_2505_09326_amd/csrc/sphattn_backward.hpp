@@ -11,7 +11,8 @@
 // Nothing N x N is stored: the scores are recomputed tile by tile, as in the forward.  Two
 // kernels, no atomics, so the result does not depend on the launch:
 //   bwd_dq_kernel   a workgroup owns 256 query rows and streams the keys: S^T = K Q^T,
-//                   G^T = V dO^T, dS^T in registers, dQ^T += K^T dS^T.  Also writes delta_i r_i^2.
+//                   G^T = V dO^T, dS^T / r_i = G^T - delta_i r_i S^T in registers,
+//                   dQ^T += K^T dS^T / r_i, times r_i at the end.  Also writes delta_i r_i^2.
 //   bwd_dkv_kernel  a workgroup owns 128 keys and streams the queries: S = Q K^T, G = dO V^T,
 //                   W and dS in registers, dV^T += dO^T W, dK^T += Q^T dS.
 // Both use the forward's building blocks: 16x16x32 matrix instructions with the product
@@ -85,7 +86,7 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
     // own rows: Q and dO as B operands (lane: row q0 + 16qb + n16, elements 32kk + 8g .. +7);
     // r and delta of the lane's query of every block
     i32x4 qf[NQ][KK], gf[NQ][KK];
-    float c1[NQ], c2[NQ];                          // r_i and delta_i r_i^2
+    float c1[NQ], c3[NQ];                          // r_i and delta_i r_i
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
         int row = q0 + qb * 16 + n16;
@@ -104,9 +105,9 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
         const float z = Z[(size_t)bh * N + row];
         const float r = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
         c1[qb] = r;
-        c2[qb] = dsum * r * r;
+        c3[qb] = dsum * r;
         // for the dK/dV kernel: delta_i r_i^2, the factor of s_ij in ds_ij, so that it need not form it
-        if (live && g == 0) delta[(size_t)bh * N + row] = c2[qb];
+        if (live && g == 0) delta[(size_t)bh * N + row] = c3[qb] * r;
     }
 
     f32x4 dq[DB][NQ];
@@ -169,8 +170,9 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
             }
         };
         f32x4 sc[2][NQ], gg[2][NQ];                // scores and dO V^T of key block kb
-        i32x4 dsp[NQ];                             // dS^T of 32 keys as B operands
-        // ds of key block kb of sub-step sub: registers 2kb, 2kb+1 of dsp
+        i32x4 dsp[NQ];                             // dS^T / r_i of 32 keys as B operands
+        // ds_ij / r_i = G_ij - delta_i r_i s_ij of key block kb of sub-step sub (registers 2kb,
+        // 2kb+1 of dsp): r_i is the same for a whole row of dQ and is applied once, at the end
         auto finish_block = [&](int sub, int kb) {
             const int rb = 2 * sub + kb;
             f32x4 mk = {1.f, 1.f, 1.f, 1.f};       // multipliers of the lane's keys 16rb + 4g + t
@@ -179,8 +181,8 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
 #pragma unroll
             for (int qb = 0; qb < NQ; ++qb) {
                 f32x4 ds;
-                if constexpr (MULT) ds = (gg[kb][qb] * c1[qb] - (sc[kb][qb] * mk) * c2[qb]) * mk;
-                else ds = gg[kb][qb] * c1[qb] - sc[kb][qb] * c2[qb];
+                if constexpr (MULT) ds = (gg[kb][qb] - (sc[kb][qb] * mk) * c3[qb]) * mk;
+                else ds = gg[kb][qb] - sc[kb][qb] * c3[qb];
                 dsp[qb][2 * kb] = pack2<HALF>(ds[0], ds[1]);
                 dsp[qb][2 * kb + 1] = pack2<HALF>(ds[2], ds[3]);
             }
@@ -218,6 +220,7 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
             unsigned short* dst = dQh + (size_t)row * D + 4 * g;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
+                dq[db][qb] *= c1[qb];
                 const i32x2 o4 = {pack2<HALF>(dq[db][qb][0], dq[db][qb][1]), pack2<HALF>(dq[db][qb][2], dq[db][qb][3])};
                 *reinterpret_cast<i32x2*>(dst + db * 16) = o4;
             }
