@@ -367,7 +367,7 @@ def main() -> int:
         Zf = torch.empty(qd.shape[:3], dtype=torch.float32, device=dev)
         pkg.sphattn_fwd_z(qd, kd, vd, out, Zf, dtype=w.dtype)
         dQ, dK, dV = (torch.empty_like(qd) for _ in range(3))
-        delta = torch.empty_like(Zf)
+        delta = torch.empty((2, *Zf.shape), dtype=torch.float32, device=dev)
         _, per_b = time_launches(lambda: pkg.sphattn_bwd(qd, kd, vd, out, dO, Zf, dQ, dK, dV, delta, dtype=w.dtype),
                                  max(30, args.steps // 2), max(10, args.warmup // 2))
         ms_b = sum(per_b) / len(per_b)

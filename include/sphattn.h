@@ -267,8 +267,8 @@ int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype);
  *                    anything else returns SPHATTN_ERR_DTYPE); O and Z as sphattn_fwd_z wrote them.
  *   Z              : [B,H,N] fp32, the row aggregates z_i.
  *   dQ, dK, dV     : [B,H,N,d] in the same 16-bit format, written in full.
- *   delta          : [B,H,N] fp32 scratch from the caller; the first launch leaves delta_i r_i^2 there
- *                    for the second.
+ *   delta          : [2,B,H,N] fp32 scratch from the caller; the first launch leaves delta_i r_i^2 (first
+ *                    plane) and r_i (second plane) there for the second.
  * Outputs and scratch must not overlap each other or the inputs.  Two launches on `stream`.
  * Other arguments and errors as sphattn_fwd.
  */
@@ -285,7 +285,7 @@ int sphattn_bwd(const void* Q, const void* K, const void* V, const void* O, cons
  *     dV[b,g,j,:] = sum_{h in group g} sum_i r_i s_ij dO[b,h,i,:]
  *
  * with ds_ij, r_i, delta_i as in sphattn_bwd.  The multiplicities are data: no gradient.
- *   Q, O, dO, dQ : [B,H,N,d];  K, V, dK, dV : [B,H_kv,N,d];  Z, delta : [B,H,N] fp32;
+ *   Q, O, dO, dQ : [B,H,N,d];  K, V, dK, dV : [B,H_kv,N,d];  Z : [B,H,N] fp32;  delta : [2,B,H,N] fp32;
  *   mult : [B,N] fp32 or NULL (all ones).
  * Everything else as sphattn_bwd, which is this call with mult == NULL and H_kv == H.
  */

@@ -448,7 +448,7 @@ def _check_backward(Q, K, V, mult, O, dO, Z, dQ, dK, dV, delta, code):
     for name, x in (("K", K), ("V", V), ("dK", dK), ("dV", dV)):
         _need(name, x, (B, H_kv, N, d), t)
     _need("Z", Z, (B, H, N), _f32_types())
-    _need("delta", delta, (B, H, N), _f32_types())
+    _need("delta", delta, (2, B, H, N), _f32_types())
     _need("mult", mult, (B, N), _f32_types(), optional=True)
     _on_device(Q=Q, K=K, V=V, mult=mult, O=O, dO=dO, Z=Z, dQ=dQ, dK=dK, dV=dV, delta=delta)
     return B, H, N, d, H_kv
@@ -463,7 +463,7 @@ def sphattn_grn_bwd(Q, K, V, mult, O, dO, Z, dQ=None, dK=None, dV=None, delta=No
     dK = torch.empty_like(K) if dK is None else dK
     dV = torch.empty_like(V) if dV is None else dV
     if delta is None:
-        delta = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+        delta = torch.empty((2, *Q.shape[:3]), dtype=torch.float32, device=Q.device)
     B, H, N, d, H_kv = _check_backward(Q, K, V, mult, O, dO, Z, dQ, dK, dV, delta, code)
     _raise_on(lib.sphattn_grn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _ptr(mult), O.data_ptr(), dO.data_ptr(),
                                   Z.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), delta.data_ptr(),
@@ -479,7 +479,7 @@ def sphattn_bwd(Q, K, V, O, dO, Z, dQ=None, dK=None, dV=None, delta=None, dtype=
     dK = torch.empty_like(K) if dK is None else dK
     dV = torch.empty_like(V) if dV is None else dV
     if delta is None:
-        delta = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+        delta = torch.empty((2, *Q.shape[:3]), dtype=torch.float32, device=Q.device)
     if Q.dim() == 4 and K.dim() == 4 and K.shape[1] != Q.shape[1]:
         raise ValueError(f"K must have Q's {Q.shape[1]} heads, got {K.shape[1]} (sphattn_grn_bwd takes shared heads)")
     B, H, N, d, H_kv = _check_backward(Q, K, V, None, O, dO, Z, dQ, dK, dV, delta, code)

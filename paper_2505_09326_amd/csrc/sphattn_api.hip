@@ -339,12 +339,14 @@ int launch_bwd(const BwdProblem& p)
     const long long wg_q = (long long)p.B * p.H * n_qtiles, wg_kv = (long long)p.B * p.H_kv * n_ktiles;
     if (wg_q > 0x7fffffff || wg_kv > 0x7fffffff) return SPHATTN_ERR_SHAPE;
     const int kv_group = p.H / p.H_kv;
-    // delta is written by the first kernel and read by the second, in stream order
+    // the two planes of delta (delta_i r_i^2, then r_i) are written by the first kernel and read
+    // by the second, in stream order
+    float* rnorm = p.delta + (size_t)p.B * p.H * p.N;
     hipLaunchKernelGGL(kq, dim3((unsigned)wg_q), dim3(kThreads), lds_dq, p.stream,
-                       p.Q, p.K, p.V, p.mult, p.O, p.dO, p.Z, p.dQ, p.delta, p.N, p.H, kv_group, n_qtiles, (int)wg_q);
+                       p.Q, p.K, p.V, p.mult, p.O, p.dO, p.Z, p.dQ, p.delta, rnorm, p.N, p.H, kv_group, n_qtiles, (int)wg_q);
     if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
     hipLaunchKernelGGL(kkv, dim3((unsigned)wg_kv), dim3(kThreads), lds_dkv, p.stream,
-                       p.Q, p.K, p.V, p.mult, p.dO, p.Z, (const float*)p.delta, p.dK, p.dV,
+                       p.Q, p.K, p.V, p.mult, p.dO, (const float*)rnorm, (const float*)p.delta, p.dK, p.dV,
                        p.N, p.H, kv_group, n_ktiles, (int)wg_kv);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
@@ -667,7 +669,7 @@ int sphattn_grn_bwd(const void* Q, const void* K, const void* V, const float* mu
     const void* ins[7] = {Q, K, V, O, dO, Z, mult};
     const size_t in_bytes[7] = {tq, tkv, tkv, tq, tq, rb, mult ? (size_t)B * N * 4 : 0};
     void* outs[4] = {dQ, dK, dV, delta};
-    const size_t out_bytes[4] = {tq, tkv, tkv, rb};
+    const size_t out_bytes[4] = {tq, tkv, tkv, 2 * rb};
     for (int o = 0; o < 4; ++o) {
         for (int i = 0; i < 7; ++i)
             if (ins[i] && overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return SPHATTN_ERR_ALIAS;

@@ -12,7 +12,9 @@
 // kernels, no atomics, so the result does not depend on the launch:
 //   bwd_dq_kernel   a workgroup owns 256 query rows and streams the keys: S^T = K Q^T,
 //                   G^T = V dO^T, dS^T / r_i = G^T - delta_i r_i S^T in registers,
-//                   dQ^T += K^T dS^T / r_i, times r_i at the end.  Also writes delta_i r_i^2.
+//                   dQ^T += K^T dS^T / r_i, times r_i at the end.  Also writes, per row,
+//                   delta_i r_i^2 and r_i for the other kernel (which would otherwise take the
+//                   reciprocal square root of every z_i once per wave and key tile).
 //   bwd_dkv_kernel  a workgroup owns 128 keys and streams the queries: S = Q K^T, G = dO V^T,
 //                   W and dS in registers, dV^T += dO^T W, dK^T += Q^T dS.
 // Both use the forward's building blocks: 16x16x32 matrix instructions with the product
@@ -61,7 +63,7 @@ __global__ __launch_bounds__(kThreads, 1)
 void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, const void* __restrict__ Vv,
                    const float* __restrict__ mult,
                    const void* __restrict__ Ov, const void* __restrict__ dOv, const float* __restrict__ Z,
-                   void* __restrict__ dQv, float* __restrict__ delta,
+                   void* __restrict__ dQv, float* __restrict__ delta, float* __restrict__ rnorm,
                    int N, int H, int kv_group, int n_qtiles, int n_wg)
 {
     constexpr int BC = kBC, NQ = 4, BR = kWaves * 16 * NQ;
@@ -106,8 +108,11 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
         const float r = z > 0.f ? 1.0f / __builtin_sqrtf(z) : 0.f;
         c1[qb] = r;
         c3[qb] = dsum * r;
-        // for the dK/dV kernel: delta_i r_i^2, the factor of s_ij in ds_ij, so that it need not form it
-        if (live && g == 0) delta[(size_t)bh * N + row] = c3[qb] * r;
+        // for the dK/dV kernel: r_i and delta_i r_i^2, the factors of G_ij and s_ij in ds_ij
+        if (live && g == 0) {
+            delta[(size_t)bh * N + row] = c3[qb] * r;
+            rnorm[(size_t)bh * N + row] = r;
+        }
     }
 
     f32x4 dq[DB][NQ];
@@ -230,7 +235,7 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
 
 // ---------------------------------------------------------------------------
 // dK and dV.  Workgroup = 4 waves x 32 keys (two blocks of 16).  Streams Q/dO tiles of 64
-// queries together with their z and delta.
+// queries together with their r and delta r^2.
 // ---------------------------------------------------------------------------
 // NK = key blocks of 16 per wave.  Every LDS fragment feeds NK matrix instructions of each
 // product, so NK sets the LDS instructions per matrix instruction (0.75 at NK = 2; 0.5 at 3;
@@ -244,14 +249,14 @@ template <int D, bool HALF, bool MULT, int NK>
 __global__ __launch_bounds__(kThreads, NK == 2 ? 2 : 1)
 void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, const void* __restrict__ Vv,
                     const float* __restrict__ mult,
-                    const void* __restrict__ dOv, const float* __restrict__ Z, const float* __restrict__ delta,
+                    const void* __restrict__ dOv, const float* __restrict__ rnorm, const float* __restrict__ delta,
                     void* __restrict__ dKv, void* __restrict__ dVv,
                     int N, int H, int kv_group, int n_ktiles, int n_wg)
 {
     constexpr int BC = kBC, BKEYS = kWaves * 16 * NK;
     constexpr int ROWB = D * 2, TILE = BC * ROWB;
     constexpr int KK = D / 32, DB = D / 16, KBLK = ROWB / 64;
-    constexpr int GLDS = TILE, ZLDS = 2 * TILE, DLDS = 2 * TILE + BC * 4;   // Q tile, dO tile, z, delta
+    constexpr int GLDS = TILE, ZLDS = 2 * TILE, DLDS = 2 * TILE + BC * 4;   // Q tile, dO tile, r, delta r^2
     constexpr int BUF_BYTES = 2 * TILE + 2 * BC * 4;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -297,14 +302,14 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
         const size_t qh = (size_t)(bidx * H + h0 + hq);
         const i32x4 qrw = rsrc_words((const unsigned char*)Qv + qh * N * D * 2, (uint32_t)N * ROWB);
         const i32x4 grw = rsrc_words((const unsigned char*)dOv + qh * N * D * 2, (uint32_t)N * ROWB);
-        const i32x4 zrw = rsrc_words(Z + qh * N, (uint32_t)N * 4);
+        const i32x4 zrw = rsrc_words(rnorm + qh * N, (uint32_t)N * 4);
         const i32x4 drw = rsrc_words(delta + qh * N, (uint32_t)N * 4);
 #pragma unroll
         for (int c = 0; c < KBLK; ++c) {
             copy_to_lds(qrw, buf + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
             copy_to_lds(grw, buf + GLDS + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
         }
-        // 64 z and 64 delta values: 16 lanes x 16 bytes each; queries past N arrive as 0
+        // 64 r and 64 delta r^2 values: 16 lanes x 16 bytes each; queries past N arrive as 0
         if (wave == 0 && lane < BC / 4) copy_to_lds(zrw, buf + ZLDS, lane * 16, tile * BC * 4);
         if (wave == 1 && lane < BC / 4) copy_to_lds(drw, buf + DLDS, lane * 16, tile * BC * 4);
     };
@@ -353,14 +358,9 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
         // W and dS of query block qb of sub-step sub: registers 2qb, 2qb+1 of wp and dsp
         auto finish_block = [&](int sub, int qb) {
             const int qoff = (32 * sub + 16 * qb + 4 * g) * 4;
-            const f32x4 zq = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + ZLDS + qoff));
-            const f32x4 dq_ = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + DLDS + qoff));
-            f32x4 r, c;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                r[t] = zq[t] > 0.f ? __builtin_amdgcn_rsqf(zq[t]) : 0.f;   // v_rsq_f32, 1 ulp
-                c[t] = dq_[t];                     // delta_i r_i^2, as the dQ kernel left it
-            }
+            // r_i and delta_i r_i^2 of the lane's four queries, as the dQ kernel left them
+            const f32x4 r = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + ZLDS + qoff));
+            const f32x4 c = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + DLDS + qoff));
 #pragma unroll
             for (int kb = 0; kb < NK; ++kb) {
                 const f32x4 sm = MULT ? s[qb][kb] * mk[kb] : s[qb][kb];

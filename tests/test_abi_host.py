@@ -194,6 +194,7 @@ def test_backward_argument_errors(lib):
     assert call(dQ=0x1000000) == -7            # dQ is Q
     assert call(dV=0x8000000) == -7            # dV is dK
     assert call(delta=0x6000000) == -7         # delta is Z
+    assert call(delta=0x6000000 - 2400) == -7  # [2,B,H,N]: the second plane of delta lies over Z
 
     def grn(mult=0xB000000, H_kv=1, **over):
         a = dict(base, **over)

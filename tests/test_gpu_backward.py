@@ -128,13 +128,13 @@ def test_backward_does_not_write_outside_its_outputs(pkg):
     pad = 4096
     bufs = [torch.full((n + 2 * pad,), 7.0, dtype=torch.bfloat16, device=DEV) for _ in range(3)]
     outs = [b[pad:pad + n].view(B, H, N, d) for b in bufs]
-    dbuf = torch.full((B * H * N + 2 * pad,), 7.0, dtype=torch.float32, device=DEV)
+    dbuf = torch.full((2 * B * H * N + 2 * pad,), 7.0, dtype=torch.float32, device=DEV)
     pkg.sphattn_bwd(qd, kd, vd, O, gd, Z, dQ=outs[0], dK=outs[1], dV=outs[2],
-                    delta=dbuf[pad:pad + B * H * N].view(B, H, N), dtype="bf16")
+                    delta=dbuf[pad:pad + 2 * B * H * N].view(2, B, H, N), dtype="bf16")
     torch.cuda.synchronize()
     for b in bufs:
         assert bool((b[:pad] == 7.0).all()) and bool((b[pad + n:] == 7.0).all())
-    assert bool((dbuf[:pad] == 7.0).all()) and bool((dbuf[pad + B * H * N:] == 7.0).all())
+    assert bool((dbuf[:pad] == 7.0).all()) and bool((dbuf[pad + 2 * B * H * N:] == 7.0).all())
 
 
 GRN_BWD_CASES = [

@@ -42,7 +42,7 @@ def test_graph_replay_forward_splitkv_and_backward(pkg):
     out, out_s = torch.empty_like(v), torch.empty_like(v)
     Z = torch.empty(B, H, N, dtype=torch.float32, device=DEV)
     dQ, dK, dV = (torch.empty_like(q) for _ in range(3))
-    delta = torch.empty_like(Z)
+    delta = torch.empty(2, B, H, N, dtype=torch.float32, device=DEV)
     ws = torch.empty(pkg.sphattn_splitkv_workspace_bytes(B, H, N, d, 4), dtype=torch.uint8, device=DEV)
 
     def step():
