@@ -21,9 +21,12 @@
 // arranged so that the accumulator registers of the first contraction are, after the
 // elementwise step, directly a B operand of the second (k-slot e of lane group g = key or
 // query 4g + e, or 16 + 4g + e - 4); the streamed operand's tiles copied from HBM/L2 straight
-// into LDS as 1 KB blocks of 16 rows x 64 bytes, which serve both as row-major A operands
-// (lane reads 16 bytes at 64 n16 + 16 g) and, through ds_read_b64_tr_b16, as transposed A
-// operands; two LDS buffers, one barrier per streamed tile.
+// into LDS as 512-byte blocks of 16 rows x 32 bytes (the forward's V blocks), which serve both
+// as row-major A operands (lane (n16, g) reads piece g % 2 of row n16 of block g / 2 of a pair)
+// and, through ds_read_b64_tr_b16 at 8 bytes per lane in lane order, as transposed A operands;
+// the LDS banks serve both reads at full rate (blocks of 16 rows x 64 bytes read the same way
+// cost every 16-byte read twice its cycles: see block_piece_offset).  Two LDS buffers, one
+// barrier per streamed tile.
 //
 // Gene-regulatory-network options (MULT, kv_group), as in the forward: s_ij = m_j (q_i . k_j),
 // so dQ_i = sum_j ds_ij m_j k_j and dK_j = m_j sum_i ds_ij q_i (the multiplicities are data and
@@ -126,7 +129,8 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
     const i32x4 vrw = rsrc_words((const unsigned char*)Vv + kv_off * 2, (uint32_t)N * ROWB);
     const i32x4 mrw = rsrc_words(MULT ? mult + (size_t)bidx * N : nullptr, MULT ? (uint32_t)N * 4 : 0);
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const int ld_lane = (16 * wave + (lane >> 2)) * ROWB + (lane & 3) * 16;
+    // a 1 KB copy fills two blocks: lane l lands in block l / 32, row (l % 32) / 2, piece l % 2
+    const int ld_lane = (16 * wave + ((lane & 31) >> 1)) * ROWB + (lane >> 5) * 32 + (lane & 1) * 16;
     auto copy_tile = [&](int tile, uint32_t buf) {
 #pragma unroll
         for (int c = 0; c < KBLK; ++c) {
@@ -135,8 +139,8 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
         }
         if (MULT && wave == 0 && lane < BC / 4) copy_to_lds(mrw, buf + MLDS, lane * 16, tile * BC * 4);
     };
-    const int alane = n16 * 64 + g * 16;                           // row-major A operand
-    const int tlane = (4 * g + (n16 >> 2)) * 64 + (n16 & 3) * 8;   // transposed A operand
+    const int alane = (g >> 1) * 512 + n16 * 32 + (g & 1) * 16;    // row-major A operand
+    const int tlane = lane * 8;                                    // transposed A operand
 
     const int n_tiles = (N + BC - 1) / BC;
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
@@ -168,7 +172,7 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
                 fb[st & 1] = lds_read_b128(vb_ + (rb * KBLK + kk) * 1024 + alane);
             } else {
                 const int db = u - QG;
-                const SPH_LDS unsigned char* a = kb_ + (2 * sub * KBLK + db / 2) * 1024 + (db & 1) * 32 + tlane;
+                const SPH_LDS unsigned char* a = kb_ + 2 * sub * KBLK * 1024 + db * 512 + tlane;
                 const i32x2 lo = lds_read_tr64(a);
                 const i32x2 hi = lds_read_tr64(a + KBLK * 1024);
                 fa[st & 1] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
@@ -294,7 +298,8 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
         for (int kb = 0; kb < NK; ++kb) { dk[db][kb] = f32x4{0, 0, 0, 0}; dv[db][kb] = f32x4{0, 0, 0, 0}; }
 
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const int ld_lane = (16 * wave + (lane >> 2)) * ROWB + (lane & 3) * 16;
+    // a 1 KB copy fills two blocks: lane l lands in block l / 32, row (l % 32) / 2, piece l % 2
+    const int ld_lane = (16 * wave + ((lane & 31) >> 1)) * ROWB + (lane >> 5) * 32 + (lane & 1) * 16;
     const int n_tiles = (N + BC - 1) / BC;
     // streamed tile `it` = tile it % n_tiles of query head h0 + it / n_tiles; each head has its
     // own descriptors, so that rows past the end of a head arrive as zeros
@@ -313,8 +318,8 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
         if (wave == 0 && lane < BC / 4) copy_to_lds(zrw, buf + ZLDS, lane * 16, tile * BC * 4);
         if (wave == 1 && lane < BC / 4) copy_to_lds(drw, buf + DLDS, lane * 16, tile * BC * 4);
     };
-    const int alane = n16 * 64 + g * 16;
-    const int tlane = (4 * g + (n16 >> 2)) * 64 + (n16 & 3) * 8;
+    const int alane = (g >> 1) * 512 + n16 * 32 + (g & 1) * 16;
+    const int tlane = lane * 8;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     copy_tile(0, 0, lds0);
@@ -345,7 +350,7 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
                 fb[st & 1] = lds_read_b128(gb_ + (rb * KBLK + kk) * 1024 + alane);
             } else {
                 const int db = u - QG;
-                const int boff = (2 * sub * KBLK + db / 2) * 1024 + (db & 1) * 32 + tlane;
+                const int boff = 2 * sub * KBLK * 1024 + db * 512 + tlane;
                 const i32x2 qlo = lds_read_tr64(qb_ + boff), qhi = lds_read_tr64(qb_ + boff + KBLK * 1024);
                 const i32x2 glo = lds_read_tr64(gb_ + boff), ghi = lds_read_tr64(gb_ + boff + KBLK * 1024);
                 fa[st & 1] = __builtin_shufflevector(qlo, qhi, 0, 1, 2, 3);

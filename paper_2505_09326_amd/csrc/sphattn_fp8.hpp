@@ -28,7 +28,8 @@
 // and lane (n16, g) of an A or B operand holds 32 of the 128 k-slots of row or column n16.
 // Which 32 is free as long as A and B agree; here group g takes bytes 16g .. 16g+15 and
 // 64+16g .. 64+16g+15 of the 128-byte row (every LDS read then takes one 16-byte piece from
-// each row of a 1 KB block, which the banks serve at full rate).  In the accumulator lane
+// each row of a 1 KB block; with the pieces of a row permuted as block_piece_offset says, the
+// banks serve it at full rate).  In the accumulator lane
 // (n16, g) holds query n16 and, in register t, row 4g + t of the block.  The 16 rows of score
 // block kb are therefore chosen to be the keys
 //     key(kb, p) = 64 (kb / 4) + 16 (p / 4) + 4 (kb % 4) + (p % 4),    p = 0..15,
@@ -212,17 +213,18 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     // at (KH kb + h) KB, V^T block (db, h) behind the K tile at (2 db + h) KB.  The 32 k-slots of
     // lane group g are the bytes 16g .. 16g+15 of both halves of the row (see the key order
     // above), so each of a fragment's 16-byte reads takes one piece from every row of one block:
-    // the 64 lanes cover the block's 1 KB exactly once.
-    const int flane = n16 * 64 + g * 16;
+    // the 64 lanes cover the block's 1 KB exactly once (piece c of row r sits in slot
+    // c ^ ((r >> 1) & 3), which keeps the lanes that the LDS serves together on different banks).
+    const int flane = block_piece_offset(n16, g);
     constexpr int HALF1 = 1024;                    // second half of the rows: the next block
-    // copies: lane l fills row l/4, bytes 16 (l%4) of a block
-    //   K   block (kb, h): tile row key(kb, l/4), bytes 64 h + 16 (l%4) of the key row;
+    // copies: lane l fills row l/4, slot l%4 of a block, with piece p = block_piece_in_slot(l)
+    //   K   block (kb, h): tile row key(kb, l/4), bytes 64 h + 16 p of the key row;
     //                      wave w copies the block rows kb = 2w, 2w+1
-    //   V^T block (db, h): row 16db + l/4 of V^T, keys 64 h + 16 (l%4) of the tile;
+    //   V^T block (db, h): row 16db + l/4 of V^T, keys 64 h + 16 p of the tile;
     //                      wave w copies the fragments db = VPW w .. VPW w + VPW - 1
     const int p = lane >> 2;
-    const int kld_lane = (16 * (p >> 2) + (p & 3) + 64 * (wave >> 1) + 8 * (wave & 1)) * D + (lane & 3) * 16;
-    const int vld_lane = (int)((16 * VPW * wave + p) * Np) + (lane & 3) * 16;
+    const int kld_lane = (16 * (p >> 2) + (p & 3) + 64 * (wave >> 1) + 8 * (wave & 1)) * D + block_piece_in_slot(lane) * 16;
+    const int vld_lane = (int)((16 * VPW * wave + p) * Np) + block_piece_in_slot(lane) * 16;
 
     // ---- Q fragments and the row factors a_i.  Q is read once and O written once by this
     // workgroup only: non-temporal, so that the L2 keeps the K/V stream instead.

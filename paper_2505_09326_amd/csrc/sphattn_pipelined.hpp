@@ -134,8 +134,8 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
     constexpr int VROWB = D * 2, VCH = VROWB / 16, VTILE = BC * VROWB;
     constexpr int DB = D / 16;                     // 16-column blocks of the head dimension
     // LDS image of a tile: fragment-sized blocks, each contiguous, so that a wave's 1 KB
-    // global->LDS copy fills whole blocks and every fragment read is linear in the lane id
-    // (no padding, no swizzle, no bank conflicts):
+    // global->LDS copy fills whole blocks (no padding; no bank conflicts: the K blocks with the
+    // pieces of a row permuted, see block_piece_offset, the V blocks read linearly in the lane id):
     //   K block (rb, c): key rows 16rb..16rb+15 x bytes 64c..64c+63, row-major, 1 KB
     //   V block (rb, db): key rows 16rb..16rb+15 x bytes 32db..32db+31, row-major, 512 B
     constexpr int KBLK = KROWB / 64;               // K blocks per 16 rows
@@ -192,20 +192,21 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
     const int q0 = qt * BR + wave * 16 * NQ;
 
     // ---- per-lane LDS byte offsets inside a tile; everything else is an immediate
-    // K fragment, 16-bit (kb, kk): row 16kb + n16, bytes 64kk + 16g .. +15: block (kb, kk), offset
-    //                              64 n16 + 16 g
-    // K fragment, fp8    (kb)    : row 16kb + n16, bytes 32g .. 32g+31 (two 16-byte reads): block
-    //                              (kb, g/2), offset 64 n16 + 32 (g%2); groups without data (d = 64)
-    //                              read the only block and are zeroed afterwards
-    const int klane = FP8 ? ((g >> 1) % KBLK) * 1024 + n16 * 64 + (g & 1) * 32 : n16 * 64 + g * 16;
+    // K fragment, 16-bit (kb, kk): row 16kb + n16, bytes 64kk + 16g .. +15: piece g of row n16 of
+    //                              block (kb, kk)
+    // K fragment, fp8    (kb)    : row 16kb + n16, bytes 16g .. 16g+15 and 64 + 16g .. (any
+    //                              assignment of the 128 k-slots to lanes works if Q agrees): piece
+    //                              g of row n16 of blocks (kb, 0) and (kb, 1); at d = 64 there is
+    //                              no second block and the upper 16 k-slots of every lane are zero
+    const int klane = block_piece_offset(n16, g);
     // V^T fragment db: rows 4g + (n16>>2) [+16], 8 bytes at column 16db + 4(n16&3): block
     // (0 [1], db), offset 32 (4g + (n16>>2)) + 8 (n16&3) = 8 lane.  Within a 16-lane block, lane i
     // supplies the 8-byte piece row (i>>2), columns 4(i&3)..+3 and receives column i of all 4 rows.
     const int vlane = KLDS + lane * 8;
     // global -> LDS copies: lane l of a copy lands at LDS byte 16 l of the copy's 1 KB
-    //   K copy c of wave w: block (w, c): row 16w + l/4, bytes 64c + 16 (l%4)
+    //   K copy c of wave w: block (w, c): row 16w + l/4, bytes 64c + 16 p, p = the piece of slot l%4
     //   V copy c of wave w: blocks (w, 2c), (w, 2c+1): row 16w + (l%32)/2, bytes 64c + 32 (l/32) + 16 (l%2)
-    const int kld_lane = (16 * wave + (lane >> 2)) * KROWB + (lane & 3) * 16;
+    const int kld_lane = (16 * wave + (lane >> 2)) * KROWB + block_piece_in_slot(lane) * 16;
     const int vld_lane = (16 * wave + ((lane & 31) >> 1)) * VROWB + (lane >> 5) * 32 + (lane & 1) * 16;
 
     // Q is read once and O written once by this workgroup and by no other: both go past the L2's
@@ -214,25 +215,22 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
     // 32 workgroups move at a batch boundary flush a 4 MB L2 completely).
     // ---- Q fragments (B operands of S^T = K Q^T), held for the whole kernel: lane holds
     // Q[q0 + 16qb + n16][k-slots of group g].  fp8 with d = 64 fills half of the k = 128 of
-    // the instruction: groups 2 and 3 hold zeros on both sides.
+    // the instruction: the upper 16 k-slots of every lane hold zeros on both sides.
     constexpr int QREGS = FP8 ? 8 : 4;
     constexpr int QSTEPS = FP8 ? 1 : KK;
     typedef __attribute__((ext_vector_type(QREGS))) int qfrag_t;
-    const bool k_live = !FP8 || D == 128 || g < 2;
     qfrag_t qf[NQ][QSTEPS];
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
         int row = q0 + qb * 16 + n16;
         row = row < Nq ? row : Nq - 1;             // rows past the end are computed and dropped
-        const unsigned char* src = Qh + (size_t)row * KROWB + (FP8 ? 32 : 16) * g;
+        const unsigned char* src = Qh + (size_t)row * KROWB + 16 * g;
 #pragma unroll
         for (int kk = 0; kk < QSTEPS; ++kk) {
             if constexpr (FP8) {
-                i32x4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
-                if (k_live) {
-                    lo = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(src));
-                    hi = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(src + 16));
-                }
+                const i32x4 lo = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(src));
+                i32x4 hi = {0, 0, 0, 0};
+                if constexpr (D == 128) hi = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(src + 64));
                 qf[qb][kk] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             } else {
                 qf[qb][kk] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(src + kk * 64));
@@ -322,11 +320,14 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
         else
             return mfma16x16<HALF>(a, b, c);
     };
-    // the two 16-byte halves of an fp8 K fragment; groups without data (d = 64) supply zeros
+    // the two 16-byte halves of an fp8 K fragment; the second comes from the row's second block
+    // (d = 128 only)
     auto k8frag = [&](i32x4 lo, i32x4 hi) -> i32x8 {
-        const i32x4 zero4 = {0, 0, 0, 0};
-        if (!k_live) { lo = zero4; hi = zero4; }
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+    auto k8hi = [&](const SPH_LDS unsigned char* a) -> i32x4 {
+        if constexpr (D == 128) return lds_read_b128(a + 1024);
+        else return i32x4{0, 0, 0, 0};
     };
 
     // S0 = scores of sub-step 0
@@ -334,7 +335,7 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
     for (int kb = 0; kb < 2; ++kb) {
         if constexpr (FP8) {
             const SPH_LDS unsigned char* a = smem + klane + kb * KBLK * 1024;
-            const qfrag_t kfr = k8frag(lds_read_b128(a), lds_read_b128(a + 16));
+            const qfrag_t kfr = k8frag(lds_read_b128(a), k8hi(a));
 #pragma unroll
             for (int qb = 0; qb < NQ; ++qb) S0[kb][qb] = mfma_qk(kfr, qf[qb][0], S0[kb][qb]);
         } else {
@@ -373,7 +374,7 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
             if (i % (SLOTS / 2) == 0) {
                 const int kb = i / (SLOTS / 2);
                 kf8[hh & 1][kb][0] = lds_read_b128(kp + klane + kb * KBLK * 1024);
-                kf8[hh & 1][kb][1] = lds_read_b128(kp + klane + kb * KBLK * 1024 + 16);
+                kf8[hh & 1][kb][1] = k8hi(kp + klane + kb * KBLK * 1024);
             }
         } else {
             const int kb = i / KK, kk = i % KK;
