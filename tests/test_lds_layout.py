@@ -1,0 +1,108 @@
+"""LDS layouts of the kernels against a model of the gfx950 LDS banks (host logic, no GPU).
+
+The model is what a probe kernel measured on the device (one read pattern per launch, counters
+SQ_LDS_IDX_ACTIVE and SQ_LDS_BANK_CONFLICT per instruction, and one lane of a linear pattern
+moved onto another lane's banks to find out which lanes are served together): 64 banks of
+4 bytes; ds_read_b128 is served in four passes of 16 lanes, a pass holding the lane quads
+q = lane / 4 with the same bit 3 and the same parity of bits 0..2; ds_read_b64_tr_b16 is served
+as lanes 0-31, then 32-63.  It reproduced the conflict degree of all 16 patterns measured.
+
+The formulas below restate the per-lane offsets of csrc/ (block_piece_offset and
+block_piece_in_slot in sphattn_device.hpp; alane, tlane, ld_lane in sphattn_backward.hpp; vlane
+in sphattn_pipelined.hpp): the tests check that every fragment read is conflict-free under
+the model, that the layout used before was not, and that the global -> LDS copies put every
+piece where its reader looks for it."""
+BANKS = 64
+
+
+def passes_b128():
+    groups = {}
+    for lane in range(64):
+        q = lane >> 2
+        groups.setdefault((q >> 3, (q ^ (q >> 1) ^ (q >> 2)) & 1), []).append(lane)
+    return list(groups.values())
+
+
+def passes_tr64():
+    return [list(range(32)), list(range(32, 64))]
+
+
+def conflict_degree(offset_of_lane, width, passes):
+    """Largest number of different addresses that one pass sends to one bank."""
+    worst = 0
+    for lanes in passes:
+        banks = {}
+        for lane in lanes:
+            o = offset_of_lane(lane)
+            for word in range(o // 4, (o + width) // 4):
+                banks.setdefault(word % BANKS, set()).add(word)
+        worst = max(worst, max(len(v) for v in banks.values()))
+    return worst
+
+
+def block_piece_offset(row, piece):
+    return row * 64 + ((piece ^ (row >> 1)) & 3) * 16
+
+
+def block_piece_in_slot(lane):
+    return (lane ^ (lane >> 3)) & 3
+
+
+def test_the_passes_of_the_16_byte_read_are_the_measured_ones():
+    p = passes_b128()
+    assert sorted(p[0]) == list(range(0, 4)) + list(range(12, 16)) + list(range(20, 28))
+    assert sorted(sum(p, [])) == list(range(64)) and all(len(x) == 16 for x in p)
+
+
+def test_linear_reads_are_conflict_free_and_row_major_blocks_are_not():
+    assert conflict_degree(lambda l: 16 * l, 16, passes_b128()) == 1
+    assert conflict_degree(lambda l: 8 * l, 8, passes_tr64()) == 1
+    # piece g of row n16 at 64 n16 + 16 g: the layout of the first builds, 8 LDS cycles per read
+    assert conflict_degree(lambda l: (l & 15) * 64 + (l >> 4) * 16, 16, passes_b128()) == 2
+    # ... and its transposing read in the backward kernels, 4 cycles instead of 2
+    for half in (0, 32):
+        assert conflict_degree(lambda l: (4 * (l >> 4) + ((l & 15) >> 2)) * 64 + half + (l & 3) * 8,
+                               8, passes_tr64()) == 2
+
+
+def test_permuted_pieces_serve_the_row_major_fragment_read_at_full_rate():
+    """Forward K blocks, all-E4M3 K and V^T blocks: lane (n16, g) reads piece g of row n16."""
+    assert conflict_degree(lambda l: block_piece_offset(l & 15, l >> 4), 16, passes_b128()) == 1
+    # the same blocks would also serve the transposing read (two address registers, not used)
+    for half in (0, 2):
+        def tr(l):
+            row, n16 = 4 * (l >> 4) + ((l & 15) >> 2), l & 15
+            return block_piece_offset(row, half + ((n16 & 3) >> 1)) + (n16 & 1) * 8
+        assert conflict_degree(tr, 8, passes_tr64()) == 1
+
+
+def test_copy_slots_hold_the_pieces_their_readers_look_for():
+    """Lane l of a 1 KB copy lands at byte 16 l: row l / 4, slot l % 4, and fetches the piece
+    block_piece_in_slot(l) of that row; every (row, piece) appears once."""
+    seen = set()
+    for lane in range(64):
+        row, piece = lane >> 2, block_piece_in_slot(lane)
+        assert block_piece_offset(row, piece) == 16 * lane
+        seen.add((row, piece))
+    assert len(seen) == 64
+
+
+def test_backward_blocks_serve_both_reads_at_full_rate():
+    """Backward tiles: 512-byte blocks of 16 rows x 32 bytes, two per 1 KB copy."""
+    def alane(l):
+        n16, g = l & 15, l >> 4
+        return (g >> 1) * 512 + n16 * 32 + (g & 1) * 16
+    assert conflict_degree(alane, 16, passes_b128()) == 1
+    assert conflict_degree(lambda l: 8 * l, 8, passes_tr64()) == 1
+    # copy lane l: block l / 32, row (l % 32) / 2, piece l % 2 of the 64-byte row segment,
+    # i.e. bytes 32 (l / 32) + 16 (l % 2); the reader of bytes 16 g .. of row n16 finds them there
+    landed = {}
+    for lane in range(64):
+        row, byte = (lane & 31) >> 1, 32 * (lane >> 5) + 16 * (lane & 1)
+        landed[(row, byte)] = 16 * lane
+    for l in range(64):
+        assert landed[(l & 15, 16 * (l >> 4))] == alane(l)
+    # transposing read: lane l supplies row l / 4, columns 4 (l % 4) .. +3 of a block's 16 columns
+    for l in range(64):
+        row, byte_in_block_row = l >> 2, 8 * (l & 3)
+        assert row * 32 + byte_in_block_row == 8 * l
