@@ -354,8 +354,12 @@ int launch_bwd(const BwdProblem& p)
 template <bool MULT>
 int dispatch_bwd(const BwdProblem& p, int d, int dtype)
 {
-    if (dtype == SPHATTN_F16) return d == 128 ? launch_bwd<128, true, MULT, 2>(p) : launch_bwd<64, true, MULT, 2>(p);
-    return d == 128 ? launch_bwd<128, false, MULT, 2>(p) : launch_bwd<64, false, MULT, 2>(p);
+    // keys per wave in the dK/dV kernel: 32 (two workgroups per CU) wherever that fits the
+    // registers; with multiplicities at d = 128 it does not (468 bytes of scratch per lane, 30
+    // reloads per tile, 3.6 times the time), so that case takes 48 keys and one workgroup per CU
+    constexpr int NK128 = MULT ? 3 : 2;
+    if (dtype == SPHATTN_F16) return d == 128 ? launch_bwd<128, true, MULT, NK128>(p) : launch_bwd<64, true, MULT, 2>(p);
+    return d == 128 ? launch_bwd<128, false, MULT, NK128>(p) : launch_bwd<64, false, MULT, 2>(p);
 }
 
 size_t workspace_bytes(int B, int H, int N, int d, int n_splits)

@@ -366,11 +366,14 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
             // r_i and delta_i r_i^2 of the lane's four queries, as the dQ kernel left them
             const f32x4 r = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + ZLDS + qoff));
             const f32x4 c = __builtin_bit_cast(f32x4, lds_read_b128(smem + cur + DLDS + qoff));
+            // s holds q_i . k_j without the multiplicity m_j of the lane's key j = n16: m_j is a
+            // factor of the whole row j of dV and dK and is applied once, at the end; inside the
+            // sums only the second term of dS carries one more
 #pragma unroll
             for (int kb = 0; kb < NK; ++kb) {
-                const f32x4 sm = MULT ? s[qb][kb] * mk[kb] : s[qb][kb];
-                const f32x4 w = sm * r;
-                const f32x4 ds = gg[qb][kb] * r - sm * c;
+                const f32x4 cm = MULT ? c * mk[kb] : c;
+                const f32x4 w = s[qb][kb] * r;
+                const f32x4 ds = gg[qb][kb] * r - s[qb][kb] * cm;
                 wp[kb][2 * qb] = pack2<HALF>(w[0], w[1]);
                 wp[kb][2 * qb + 1] = pack2<HALF>(w[2], w[3]);
                 dsp[kb][2 * qb] = pack2<HALF>(ds[0], ds[1]);
@@ -413,7 +416,7 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
         if (row < N) {
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                if constexpr (MULT) dk[db][kb] *= mk[kb];
+                if constexpr (MULT) { dk[db][kb] *= mk[kb]; dv[db][kb] *= mk[kb]; }
                 const i32x2 k4 = {pack2<HALF>(dk[db][kb][0], dk[db][kb][1]), pack2<HALF>(dk[db][kb][2], dk[db][kb][3])};
                 const i32x2 v4 = {pack2<HALF>(dv[db][kb][0], dv[db][kb][1]), pack2<HALF>(dv[db][kb][2], dv[db][kb][3])};
                 *reinterpret_cast<i32x2*>(dKh + (size_t)row * D + 4 * g + db * 16) = k4;
