@@ -255,13 +255,14 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
         apend[qb] = anext[qb] = 1.f;
     }
 
-    // multipliers of the lane's 8 keys (16kb + 4g + t) of a sub-step, double-buffered by parity.
-    // They travel with their tile: copied into LDS behind K and V, read from there one sub-step
-    // ahead of their use.
-    f32x4 mreg[MULT ? 2 : 1][2];
-    auto mload = [&](int par, int kb, const SPH_LDS unsigned char* buf, int sub) {
+    // multipliers of the lane's 4 keys (16kb + 4g + t) of key block kb of the sub-step whose scores
+    // stage B works on.  A sub-step's slots take block 0 first, then block 1, so each register
+    // quad is reloaded half a sub-step (SLOTS / 2 slots) before its next use.  The multipliers
+    // travel with their tile: copied into LDS behind K and V.
+    f32x4 mreg[2];
+    auto mload = [&](int kb, const SPH_LDS unsigned char* buf, int sub) {
         if constexpr (MULT)
-            mreg[par][kb] = __builtin_bit_cast(f32x4, lds_read_b128(buf + MLDS + (32 * sub + 16 * kb + 4 * g) * 4));
+            mreg[kb] = __builtin_bit_cast(f32x4, lds_read_b128(buf + MLDS + (32 * sub + 16 * kb + 4 * g) * 4));
     };
 
     const int n_tiles = (N + BC - 1) / BC;
@@ -301,7 +302,7 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's copies have landed
     __syncthreads();
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) mload(0, kb, smem, 0);
+    for (int kb = 0; kb < 2; ++kb) mload(kb, smem, 0);
 
     // scores of a sub-step: [key block][query block]; P of a sub-step: one B operand per query block
     f32x4 S0[2][NQ], S1[2][NQ];
@@ -488,8 +489,8 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
                 const int blkid = p / 2, c = p % 2, kb = blkid / NQ, qb = blkid % NQ;
                 float a = Sc[kb][qb][2 * c], b = Sc[kb][qb][2 * c + 1];
                 if constexpr (MULT) {
-                    a *= mreg[hf][kb][2 * c];
-                    b *= mreg[hf][kb][2 * c + 1];
+                    a *= mreg[kb][2 * c];
+                    b *= mreg[kb][2 * c + 1];
                 }
                 if constexpr (NORM == Norm::Spherical) {           // a2 = x^2, a1 = x
                     zacc[qb][0] = __builtin_fmaf(a, a, zacc[qb][0]);
@@ -522,8 +523,10 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
                     for (int qb = 0; qb < NQ; ++qb) apend[qb] = anext[qb];
                 }
             }
-            // multipliers of the next sub-step: second half of tile j, or first half of tile j+1
-            if (MULT && i < 2) mload(hf ^ 1, i, hf == 0 ? bcur : bnxt, hf ^ 1);
+            // multipliers: block 1 of this sub-step while block 0 is in use, block 0 of the next
+            // sub-step (second half of tile j, or first half of tile j+1) once block 1 is
+            if (MULT && i == 0) mload(1, bcur, hf);
+            if (MULT && i == SLOTS / 2) mload(0, hf == 0 ? bcur : bnxt, hf ^ 1);
             // copies of tile j+2 out of HBM/L2 into the free buffer, one per slot, right after
             // the barrier: they have a whole tile's time to land
             constexpr int FIRST_COPY = SLOTS - PD + 1;
@@ -637,8 +640,11 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
 // fp32 rounding).  O goes past the L2's retention (non-temporal stores) only when later batches
 // follow; a one-batch launch gains nothing from that, and its last stores would complete later
 // (measured on 256 workgroups of 32 tiles: 30.9 against 28.9 us).
+// At d = 64 two workgroups share a CU (64 KB of LDS each; two waves per SIMD, which fill each
+// other's waits): the 16-bit spherical kernels are held to the 256 registers that this takes
+// (they need 258 otherwise, and one workgroup per CU costs 5 % on 8 x 32768 x 64).
 template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
-__global__ __launch_bounds__(kThreads, 1)
+__global__ __launch_bounds__(kThreads, (D == 64 && QKT != QKType::Fp8 && NORM == Norm::Spherical) ? 2 : 1)
 void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv,
                           const void* __restrict__ Vv, void* __restrict__ Ov,
                           const float* __restrict__ mult, float* __restrict__ Zv,
