@@ -263,7 +263,7 @@ def main() -> int:
         ms_t = sum(per_t) / len(per_t)
         result["softmax_twin"] = {"kernel_ms_avg": ms_t, "tflops": w.flops / (ms_t * 1e-3) / 1e12,
                                   "spherical_speedup": ms_t / ms_kernel,
-                                  "form": "32x32x16 MFMA, the fastest SoftMax form here", "shares_the_spherical_kernels_data_path": False,
+                                  "form": "32x32x16 MFMA kernel of its own (the faster SoftMax form at d = 128)", "shares_the_spherical_kernels_data_path": False,
                                   "note": "own data path (register-staged, padded LDS rows): the ratio mixes that "
                                           "difference into the exponential's cost; softmax_twin_same_instructions is like for like"}
 
