@@ -164,8 +164,10 @@ __global__ void fp8_clear_kernel(float* __restrict__ p, int n)
 // the row sums come from the matrix cores as well (an all-ones A fragment against P).  A row
 // whose largest score is more than about 12 sqrt(d) below its bound underflows to zero weights
 // and gives 0: a twin for timing on inputs of moderate size, not a general SoftMax.
+// d = 64: two workgroups per CU (64 KB of LDS each) where the registers allow it without
+// spilling much (not with multiplicities: 624 bytes of scratch per lane)
 template <int D, bool SOFTMAX, bool MULT>
-__global__ __launch_bounds__(kThreads, 1)
+__global__ __launch_bounds__(kThreads, (D == 64 && !MULT) ? 2 : 1)
 void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __restrict__ K,
                     const unsigned char* __restrict__ VT, const float* __restrict__ kmax,
                     const float* __restrict__ mult,
