@@ -137,7 +137,7 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
             copy_to_lds(krw, buf + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
             copy_to_lds(vrw, buf + VLDS + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
         }
-        if (MULT && wave == 0 && lane < BC / 4) copy_to_lds(mrw, buf + MLDS, lane * 16, tile * BC * 4);
+        if constexpr (MULT) copy_to_lds_b32(mrw, buf + MLDS, lane * 4, tile * BC * 4);   // by every wave
     };
     const int alane = (g >> 1) * 512 + n16 * 32 + (g & 1) * 16;    // row-major A operand
     const int tlane = lane * 8;                                    // transposed A operand
@@ -314,7 +314,10 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
             copy_to_lds(qrw, buf + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
             copy_to_lds(grw, buf + GLDS + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
         }
-        // 64 r and 64 delta r^2 values: 16 lanes x 16 bytes each; queries past N arrive as 0
+        // 64 r and 64 delta r^2 values: 16 lanes x 16 bytes each; queries past N arrive as 0.
+        // (Under a branch, unlike the multiplicities of the other kernels: this kernel gains
+        // nothing from the all-wave form, and its 48-key variant, at 512 registers, came out
+        // of the compiler with 196 bytes of scratch and wrong dK with it.)
         if (wave == 0 && lane < BC / 4) copy_to_lds(zrw, buf + ZLDS, lane * 16, tile * BC * 4);
         if (wave == 1 && lane < BC / 4) copy_to_lds(drw, buf + DLDS, lane * 16, tile * BC * 4);
     };

@@ -289,8 +289,9 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
             copy_to_lds(vrw, base + KTILE + ((wave_u * VPW + f) * 2 + h) * 1024, vld_lane,
                         tile * BC + (int)(f * 16 * Np) + h * 64);
         } else if (MULT && c == NCOPY) {
-            if (wave == 0 && lane < BC / 4)        // 32 lanes x 4 multiplicities
-                copy_to_lds(mrw, base + MLDS, lane * 16, tile * BC * 4);
+            // the tile's 128 multiplicities: two 256-byte copies, by every wave (no branch)
+            copy_to_lds_b32(mrw, base + MLDS, lane * 4, tile * BC * 4);
+            copy_to_lds_b32(mrw, base + MLDS + 256, lane * 4, tile * BC * 4 + 256);
         }
     };
 

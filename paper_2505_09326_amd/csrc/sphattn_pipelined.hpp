@@ -114,6 +114,18 @@ __device__ __forceinline__ void copy_to_lds(i32x4 rsrc, uint32_t lds, int voff, 
                  :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
 
+// The same with 4 bytes per lane: 256 bytes per wave instruction, lane l landing at LDS byte
+// lds + 4 l.  For the per-key and per-query fp32 rows that travel with a tile (64 values): every
+// wave of the workgroup issues the same copy, instead of one wave or a part of its lanes under a
+// branch.  The bytes are the same whoever's copy lands last, and the tile loops stay one basic
+// block (with the branch the register allocator loses track of the accumulators across the
+// blocks and moves them around: 78 register moves per tile in the forward with multiplicities).
+__device__ __forceinline__ void copy_to_lds_b32(i32x4 rsrc, uint32_t lds, int voff, int soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+
 // One work item: the query tile (and key slice) number `item` of the launch's n_items, streamed
 // forwards or backwards over its keys.  Called by every thread of the workgroup.
 template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL>
@@ -284,8 +296,8 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
             copy_to_lds(krw, base + (wave_u * KBLK + c) * 1024, kld_lane, tile * KTILE + c * 64);
         else if (c < LDK + LDV)
             copy_to_lds(vrw, base + KLDS + (wave_u * DB + 2 * (c - LDK)) * 512, vld_lane, tile * VTILE + (c - LDK) * 64);
-        else if (wave == 0 && lane < BC / 4)       // 16 lanes x 4 multiplicities
-            copy_to_lds(mrw, base + MLDS, lane * 16, tile * BC * 4);
+        else                                       // the tile's 64 multiplicities, by every wave
+            copy_to_lds_b32(mrw, base + MLDS, lane * 4, tile * BC * 4);
     };
 
     // ---- prologue: buffer 3 plays "tile -1" (zeros) for the first stage C; tiles 0 and 1 go
