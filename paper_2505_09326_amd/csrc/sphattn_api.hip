@@ -330,7 +330,7 @@ template <int D, bool HALF, bool MULT, int NK>
 int launch_bwd(const BwdProblem& p)
 {
     constexpr int tile = kBC * D * 2;
-    constexpr int lds_dq = 2 * (2 * tile + (MULT ? kBC * 4 : 0)), lds_dkv = 2 * (2 * tile + 2 * kBC * 4);
+    constexpr int lds_dq = 2 * (2 * tile + (MULT ? kBC * 4 : 0)), lds_dkv = 2 * (2 * tile + 2 * kBC * 4) + (MULT ? kWaves * NK * 16 * 4 : 0);
     auto kq = bwd_dq_kernel<D, HALF, MULT>;
     auto kkv = bwd_dkv_kernel<D, HALF, MULT, NK>;
     static std::atomic<uint64_t> done_q{0}, done_kv{0};
@@ -354,10 +354,7 @@ int launch_bwd(const BwdProblem& p)
 template <bool MULT>
 int dispatch_bwd(const BwdProblem& p, int d, int dtype)
 {
-    // keys per wave in the dK/dV kernel: 32 (two workgroups per CU) wherever that fits the
-    // registers; with multiplicities at d = 128 it does not (468 bytes of scratch per lane, 30
-    // reloads per tile, 3.6 times the time), so that case takes 48 keys and one workgroup per CU
-    constexpr int NK128 = MULT ? 3 : 2;
+    constexpr int NK128 = 2;
     if (dtype == SPHATTN_F16) return d == 128 ? launch_bwd<128, true, MULT, NK128>(p) : launch_bwd<64, true, MULT, 2>(p);
     return d == 128 ? launch_bwd<128, false, MULT, NK128>(p) : launch_bwd<64, false, MULT, 2>(p);
 }

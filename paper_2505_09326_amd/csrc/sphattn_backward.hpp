@@ -278,12 +278,18 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
 
     // own keys: K and V as B operands (lane: key k0 + 16kb + n16, elements 32kk + 8g .. +7)
     i32x4 kf[NK][KK], vf[NK][KK];
-    float mk[NK];                                  // the lane's keys' multiplicities
+    // The lane's keys' multiplicities wait in LDS behind the tile buffers (one float per key of
+    // the workgroup, written and read by the same lanes): held in registers for the whole kernel
+    // they are what pushes the d = 128 kernel out of the 256 registers of two workgroups per CU.
+    constexpr int MKLDS = 2 * BUF_BYTES;
+    const SPH_LDS unsigned char* mk_own = smem + MKLDS + (wave * NK * 16 + n16) * 4;
+    auto mk = [&](int kb) { return MULT ? lds_read_f32(mk_own + kb * 64) : 1.f; };
 #pragma unroll
     for (int kb = 0; kb < NK; ++kb) {
         int row = k0 + kb * 16 + n16;
         row = row < N ? row : N - 1;               // keys past the end are computed and dropped
-        mk[kb] = MULT ? mult[(size_t)bidx * N + row] : 1.f;
+        if constexpr (MULT)
+            *reinterpret_cast<SPH_LDS float*>(smem + MKLDS + (wave * NK * 16 + kb * 16 + n16) * 4) = mult[(size_t)bidx * N + row];
         const size_t off = (head_off + (size_t)row * D) * 2 + 16 * g;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
@@ -374,7 +380,7 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
             // sums only the second term of dS carries one more
 #pragma unroll
             for (int kb = 0; kb < NK; ++kb) {
-                const f32x4 cm = MULT ? c * mk[kb] : c;
+                const f32x4 cm = MULT ? c * mk(kb) : c;
                 const f32x4 w = s[qb][kb] * r;
                 const f32x4 ds = gg[qb][kb] * r - s[qb][kb] * cm;
                 wp[kb][2 * qb] = pack2<HALF>(w[0], w[1]);
@@ -396,7 +402,13 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
                     s[qb][kb] = mfma16x16<HALF>(fa[st & 1], kf[kb][kk], kk == 0 ? zero : s[qb][kb]);
                     gg[qb][kb] = mfma16x16<HALF>(fb[st & 1], vf[kb][kk], kk == 0 ? zero : gg[qb][kb]);
                 }
-                if (qb == 1 && kk == 0) finish_block(sub, 0);      // behind the next block's first step
+                // W and dS of a query block are formed right behind its last score step, so that its
+                // S and G are dead before the next block's are written (16 registers that this
+                // kernel, which sits at the 256 of two workgroups per CU, does not have: with them
+                // alive across the next block's first step the d = 128 kernel spills, 28 bytes
+                // per lane without and 324 with multiplicities); the other wave of the SIMD
+                // covers the wait for the matrix pipeline
+                if (qb == 0 && kk == KK - 1) finish_block(sub, 0);
                 if (u == QG - 1) finish_block(sub, 1);             // the output steps need it now
             } else {
                 const int db = u - QG;
@@ -416,10 +428,11 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
 #pragma unroll
     for (int kb = 0; kb < NK; ++kb) {
         const int row = k0 + kb * 16 + n16;
+        const float mk_row = mk(kb);
         if (row < N) {
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                if constexpr (MULT) { dk[db][kb] *= mk[kb]; dv[db][kb] *= mk[kb]; }
+                if constexpr (MULT) { dk[db][kb] *= mk_row; dv[db][kb] *= mk_row; }
                 const i32x2 k4 = {pack2<HALF>(dk[db][kb][0], dk[db][kb][1]), pack2<HALF>(dk[db][kb][2], dk[db][kb][3])};
                 const i32x2 v4 = {pack2<HALF>(dv[db][kb][0], dv[db][kb][1]), pack2<HALF>(dv[db][kb][2], dv[db][kb][3])};
                 *reinterpret_cast<i32x2*>(dKh + (size_t)row * D + 4 * g + db * 16) = k4;

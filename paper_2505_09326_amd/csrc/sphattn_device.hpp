@@ -62,6 +62,11 @@ __device__ __forceinline__ i32x4 lds_read_b128(const SPH_LDS unsigned char* p)
     return *reinterpret_cast<const SPH_LDS i32x4*>(p);
 }
 
+__device__ __forceinline__ float lds_read_f32(const SPH_LDS unsigned char* p)
+{
+    return *reinterpret_cast<const SPH_LDS float*>(p);
+}
+
 // Fragment blocks in LDS: 16 rows x 64 bytes = 1 KB, filled by one direct global -> LDS copy
 // (lane l lands at byte 16 l: row l / 4, slot l % 4) and read as matrix operands, lane (n16, g)
 // taking the 16-byte piece g of row n16.  The LDS has 64 banks of 4 bytes; a 16-byte read
