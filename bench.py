@@ -377,6 +377,19 @@ def main() -> int:
             "tflops_executed_14N2d": 3.5 * w.flops / (ms_b * 1e-3) / 1e12,   # scores recomputed in both kernels
             "vs_forward": ms_b / ms_kernel,
         }
+        if args.grn:
+            # the same with gene multiplicities and args.grn shared K/V heads (sphattn_grn_bwd);
+            # O and z of that forward come from sphattn_cross_fwd
+            gm = torch.Generator(device="cpu").manual_seed(w.seed + 1000)
+            mult = torch.poisson(torch.full((w.B, w.N), 1.5), generator=gm).to(torch.float32).to(dev)
+            kg, vg = kd[:, :args.grn].contiguous(), vd[:, :args.grn].contiguous()
+            pkg.sphattn_cross_fwd(qd, kg, vg, mult, O=out, Z=Zf, dtype=w.dtype)
+            dKg, dVg = torch.empty_like(kg), torch.empty_like(vg)
+            _, per_g = time_launches(lambda: pkg.sphattn_grn_bwd(qd, kg, vg, mult, out, dO, Zf, dQ, dKg, dVg, delta, dtype=w.dtype),
+                                     max(30, args.steps // 2), max(10, args.warmup // 2))
+            ms_gb = sum(per_g) / len(per_g)
+            result["backward"]["grn_variant"] = {"H_kv": args.grn, "multiplicities": "Poisson(1.5)", "ms_avg": ms_gb,
+                                                 "vs_plain_backward": ms_gb / ms_b}
 
     if args.copy_reference:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
