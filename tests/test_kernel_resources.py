@@ -1,0 +1,102 @@
+"""Register, scratch and occupancy figures of the hot kernels, from the compiler's own report
+(hipcc -Rpass-analysis=kernel-resource-usage, device code only: no GPU needed).
+
+Several kernels are built for a given number of workgroups per CU (two waves per SIMD at d = 64,
+two workgroups of the dK/dV kernel at d = 128).  Two registers more and the hardware runs half as
+many, with nothing failing: the d = 64 forward once grew from 236 to 258 registers and ran 5 %
+slower for it; the dK/dV kernel with multiplicities spilled 468 bytes per lane and took 3.6 times
+as long.  These tests pin the figures that the measured numbers rest on."""
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2505_09326_amd._build import CSRC, HIPCC_FLAGS
+
+API = os.path.join(CSRC, "sphattn_api.hip")
+
+
+@pytest.fixture(scope="module")
+def usage(tmp_path_factory):
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not os.path.exists(hipcc):
+        pytest.skip("no hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    out = tmp_path_factory.mktemp("res") / "dev.o"
+    res = subprocess.run([hipcc, *flags, "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage",
+                          "-c", "-o", str(out), API], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    kernels, cur = {}, None
+    for line in res.stderr.splitlines():
+        m = re.search(r"remark:\s+(.*?) \[-Rpass", line)
+        if not m:
+            continue
+        t = m.group(1).strip()
+        if t.startswith("Function Name:"):
+            cur = t.split("Function Name:")[1].strip()
+            kernels[cur] = {}
+        elif cur and ":" in t:
+            k, v = t.split(":", 1)
+            kernels[cur][k.strip()] = v.strip()
+    assert kernels, "no resource remarks in the compiler's output"
+    return kernels
+
+
+def _find(usage, *parts):
+    """The kernels whose mangled name contains every part."""
+    hits = {k: v for k, v in usage.items() if all(p in k for p in parts)}
+    assert hits, parts
+    return hits
+
+
+def _num(v, key):
+    return int(v[key])
+
+
+# mangled template arguments: Li<D>E, Li<NQ>E, QKType E0 bf16 / E1 fp8 / E2 f16, Norm E0 spherical /
+# E1 SoftMax / E2 L1 / E3 squared ReLU, Lb<MULT>E, Lb<PARTIAL>E
+FWD = "fwd_pipelined_kernel"
+
+
+def test_forward_kernels_do_not_spill(usage):
+    for d in (64, 128):
+        for qk in (0, 1, 2):
+            for name, v in _find(usage, FWD, f"ILi{d}ELi4ELNS_6QKTypeE{qk}ELNS_4NormE0E").items():
+                limit = 8 if d == 64 else 0        # d = 64 with multiplicities: two registers' worth
+                assert _num(v, "ScratchSize [bytes/lane]") <= limit, name
+
+
+def test_d64_16bit_forward_fits_two_workgroups_per_cu(usage):
+    for qk in (0, 2):
+        for norm in ((0, 1, 2, 3) if qk == 0 else (0,)):      # fp16 storage: spherical only
+            for name, v in _find(usage, FWD, f"ILi64ELi4ELNS_6QKTypeE{qk}ELNS_4NormE{norm}E").items():
+                assert _num(v, "Occupancy [waves/SIMD]") >= 2, name
+                assert _num(v, "VGPRs") + _num(v, "AGPRs") <= 256, name
+
+
+def test_d128_forward_is_one_wave_per_simd_without_scratch(usage):
+    for name, v in _find(usage, FWD, "ILi128ELi4ELNS_6QKTypeE0ELNS_4NormE0ELb0ELb0E").items():
+        assert _num(v, "ScratchSize [bytes/lane]") == 0, name
+        assert _num(v, "VGPRs") + _num(v, "AGPRs") <= 512, name
+
+
+def test_backward_kernels(usage):
+    # dK/dV: two workgroups per CU at d = 128, with and without multiplicities, (almost) no scratch
+    for name, v in _find(usage, "bwd_dkv_kernelILi128E").items():
+        assert _num(v, "Occupancy [waves/SIMD]") >= 2, name
+        assert _num(v, "ScratchSize [bytes/lane]") <= 32, name
+    for name, v in _find(usage, "bwd_dkv_kernelILi64E").items():
+        assert _num(v, "Occupancy [waves/SIMD]") >= 2 and _num(v, "ScratchSize [bytes/lane]") == 0, name
+    for name, v in _find(usage, "bwd_dq_kernelILi64E").items():
+        assert _num(v, "Occupancy [waves/SIMD]") >= 2 and _num(v, "ScratchSize [bytes/lane]") == 0, name
+    for name, v in _find(usage, "bwd_dq_kernelILi128E").items():
+        assert _num(v, "ScratchSize [bytes/lane]") == 0, name
+
+
+def test_all_e4m3_kernels(usage):
+    for name, v in _find(usage, "fwd_fp8_kernelILi128E").items():
+        assert _num(v, "ScratchSize [bytes/lane]") == 0, name
+    # d = 64 without multiplicities: two workgroups per CU
+    for name, v in _find(usage, "fwd_fp8_kernelILi64ELb0ELb0E").items():
+        assert _num(v, "Occupancy [waves/SIMD]") >= 2 and _num(v, "ScratchSize [bytes/lane]") == 0, name
