@@ -76,6 +76,60 @@ def load_mfma_probe():
     return probe
 
 
+LDS_PATTERNS = (
+    (0, "ds_read_b128", "linear: 16 bytes per lane in lane order"),
+    (1, "ds_read_b128", "piece g of row n16, rows of 64 bytes (the fragment blocks' first layout)"),
+    (2, "ds_read_b128", "the same with the pieces of a row permuted (forward K tiles, all-E4M3 tiles)"),
+    (3, "ds_read_b128", "two blocks of 16 rows x 32 bytes (backward tiles)"),
+    (10, "ds_read_b64_tr_b16", "linear: 8 bytes per lane in lane order (V tiles, backward tiles)"),
+    (11, "ds_read_b64_tr_b16", "the transposed operand on rows of 64 bytes (the backward's first layout)"),
+    (12, "ds_read_b64_tr_b16", "the same on rows with permuted pieces"),
+)
+
+
+def lds_probe(dev):
+    """--lds-probe: launches of the benchmark's LDS probe, one read pattern each (one workgroup of
+    four waves, 16 reads in flight per wave): shader clocks per wave instruction here; the LDS
+    counters of `rocprofv3 --pmc SQ_LDS_IDX_ACTIVE SQ_LDS_BANK_CONFLICT SQ_INSTS_LDS` attach to the
+    same launches and give the LDS cycles and the conflict cycles per instruction."""
+    import ctypes
+    import torch
+    path = os.path.join(ROOT, "libbench_lds_probe.so")
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+    fn = ctypes.CDLL(path).bench_lds_probe
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    clk = torch.zeros(4, dtype=torch.int64, device=dev)
+    iters = 2000
+
+    def run(pattern):
+        for _ in range(2):
+            rc = fn(clk.data_ptr(), pattern, iters, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+            if rc != 0:
+                raise RuntimeError(f"bench_lds_probe({pattern}) returned {rc}")
+        torch.cuda.synchronize()
+        return max(clk.cpu().tolist()) / (iters * 16.0 + 8.0)
+
+    out = {"patterns": [{"pattern": p, "instruction": ins, "layout": what, "clocks_per_wave_instruction": run(p)}
+                        for p, ins, what in LDS_PATTERNS]}
+    # Which lanes the LDS serves in the same pass: lane 1 of a linear pattern reads lane j's
+    # address instead of its own.  Served in the same pass the two are one address (a broadcast,
+    # no conflict); otherwise lane 1 collides with the lane of its own pass that owns those banks
+    # (j = 1, 17, 33, 49, or 1, 33 for the 8-byte read, are lane 1's own banks: no conflict either
+    # way).  One launch per j; the clocks barely move (the probe is bound by instruction issue),
+    # so this part is for the counters only.
+    for base in (100, 200):
+        for j in range(64):
+            rc = fn(clk.data_ptr(), base + j, 200, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+            if rc != 0:
+                raise RuntimeError(f"bench_lds_probe({base + j}) returned {rc}")
+    torch.cuda.synchronize()
+    out["dispatch_order"] = ("two launches per pattern above, in that order; then ds_read_b128 with lane 1 on the "
+                             "address of lane j = 0..63, then ds_read_b64_tr_b16 likewise, one launch each")
+    return out
+
+
 def measure_mfma_ceiling(args, si, dev):
     """Loops of nothing but matrix instructions on Gaussian operands: TFLOP/s and shader clock
     per instruction form (the fp8 forms only with --fp8-all)."""
@@ -153,6 +207,8 @@ def main() -> int:
                     help="also time the all-E4M3 forward (sphattn_fp8_fwd: V and the scores in E4M3, too) on "
                          "the workload's shape")
     ap.add_argument("--bwd", action="store_true", help="also time the backward pass (sphattn_bwd) on the workload")
+    ap.add_argument("--lds-probe", action="store_true",
+                    help="run only the LDS read-pattern probe (libbench_lds_probe.so) and print its table as JSON")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run a plain 256 MiB device copy (untimed), as the known-size "
                          "reference that HBM byte counters are scaled by when profiling")
@@ -166,6 +222,10 @@ def main() -> int:
     import torch
     import paper_2505_09326_amd as pkg
     import synthetic_inputs as si
+
+    if args.lds_probe:
+        print(json.dumps(lds_probe(torch.device("cuda:0"))))
+        return 0
 
     pkg.load_library()                       # fail loudly if the HIP library is not built
     w, (q, k, v) = si.make_workload(args.workload)
