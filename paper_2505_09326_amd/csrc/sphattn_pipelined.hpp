@@ -652,12 +652,13 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
 // fp32 rounding).  O goes past the L2's retention (non-temporal stores) only when later batches
 // follow; a one-batch launch gains nothing from that, and its last stores would complete later
 // (measured on 256 workgroups of 32 tiles: 30.9 against 28.9 us).
-// At d = 64 two workgroups share a CU (64 KB of LDS each; two waves per SIMD, which fill each
-// other's waits): the 16-bit kernels are held to the 256 registers that this takes.  The
+// At d = 64 two workgroups share a CU (64 KB of LDS each, 48 KB with fp8 Q/K; two waves per SIMD,
+// which fill each other's waits): the kernels are held to the 256 registers that this takes.  The
 // spherical one needs 258 otherwise, and one workgroup per CU costs it 5 % on 8 x 32768 x 64; the
-// SoftMax normalizer, whose stage B is the longer, gains 21 % (with 32 bytes of scratch per lane).
+// SoftMax normalizer, whose stage B is the longer, gains 21 % (with 32 bytes of scratch per lane),
+// the fp8 Q/K kernel 4.5 % (20 to 68 bytes).
 template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
-__global__ __launch_bounds__(kThreads, (D == 64 && QKT != QKType::Fp8) ? 2 : 1)
+__global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1)
 void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv,
                           const void* __restrict__ Vv, void* __restrict__ Ov,
                           const float* __restrict__ mult, float* __restrict__ Zv,

@@ -63,13 +63,15 @@ def test_forward_kernels_do_not_spill(usage):
     for d in (64, 128):
         for qk in (0, 1, 2):
             for name, v in _find(usage, FWD, f"ILi{d}ELi4ELNS_6QKTypeE{qk}ELNS_4NormE0E").items():
-                limit = 8 if d == 64 else 0        # d = 64 with multiplicities: two registers' worth
+                # d = 64: held to 256 registers for two workgroups per CU, which costs two registers'
+                # worth of scratch with multiplicities and 20 to 68 bytes with fp8 Q/K
+                limit = 0 if d == 128 else 72 if qk == 1 else 8
                 assert _num(v, "ScratchSize [bytes/lane]") <= limit, name
 
 
-def test_d64_16bit_forward_fits_two_workgroups_per_cu(usage):
-    for qk in (0, 2):
-        for norm in ((0, 1, 2, 3) if qk == 0 else (0,)):      # fp16 storage: spherical only
+def test_d64_forward_fits_two_workgroups_per_cu(usage):
+    for qk in (0, 1, 2):
+        for norm in ((0, 1, 2, 3) if qk == 0 else (0, 1) if qk == 1 else (0,)):   # fp8 Q/K: spherical and SoftMax; fp16: spherical
             for name, v in _find(usage, FWD, f"ILi64ELi4ELNS_6QKTypeE{qk}ELNS_4NormE{norm}E").items():
                 assert _num(v, "Occupancy [waves/SIMD]") >= 2, name
                 assert _num(v, "VGPRs") + _num(v, "AGPRs") <= 256, name
