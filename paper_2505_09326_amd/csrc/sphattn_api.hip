@@ -354,9 +354,8 @@ int launch_bwd(const BwdProblem& p)
 template <bool MULT>
 int dispatch_bwd(const BwdProblem& p, int d, int dtype)
 {
-    constexpr int NK128 = 2;
-    if (dtype == SPHATTN_F16) return d == 128 ? launch_bwd<128, true, MULT, NK128>(p) : launch_bwd<64, true, MULT, 2>(p);
-    return d == 128 ? launch_bwd<128, false, MULT, NK128>(p) : launch_bwd<64, false, MULT, 2>(p);
+    if (dtype == SPHATTN_F16) return d == 128 ? launch_bwd<128, true, MULT, 2>(p) : launch_bwd<64, true, MULT, 2>(p);
+    return d == 128 ? launch_bwd<128, false, MULT, 2>(p) : launch_bwd<64, false, MULT, 2>(p);
 }
 
 size_t workspace_bytes(int B, int H, int N, int d, int n_splits)
