@@ -30,7 +30,7 @@ MEASURED_HBM_BYTES = {
     "C1": (1.28e6, "profiles/fwd_f32_d64_C1.md"),
     "C2": (33.7e6, "profiles/fwd_pipelined_bf16_d64_C2.md"),
     "C3": (268.7e6, "profiles/fwd_pipelined_bf16_d128_C3.md"),
-    "C4": (260.8e6, "profiles/fwd_pipelined_bf16_d64_C4.md"),
+    "C4": (258.9e6, "profiles/fwd_pipelined_bf16_d64_C4.md"),
     "C5": (1020.3e6, "profiles/fwd_pipelined_fp8qk_d128_C5.md"),
 }
 HBM_PEAK_GBS = 8000.0
