@@ -30,7 +30,7 @@ MEASURED_HBM_BYTES = {
     "C1": (1.28e6, "profiles/fwd_f32_d64_C1.md"),
     "C2": (33.7e6, "profiles/fwd_pipelined_bf16_d64_C2.md"),
     "C3": (268.7e6, "profiles/fwd_pipelined_bf16_d128_C3.md"),
-    "C4": (258.9e6, "profiles/fwd_pipelined_bf16_d64_C4.md"),
+    "C4": (175.8e6, "profiles/fwd_pipelined_bf16_d64_C4.md"),
     "C5": (1020.3e6, "profiles/fwd_pipelined_fp8qk_d128_C5.md"),
 }
 HBM_PEAK_GBS = 8000.0
@@ -209,6 +209,10 @@ def main() -> int:
     ap.add_argument("--bwd", action="store_true", help="also time the backward pass (sphattn_bwd) on the workload")
     ap.add_argument("--lds-probe", action="store_true",
                     help="run only the LDS read-pattern probe (libbench_lds_probe.so) and print its table as JSON")
+    ap.add_argument("--cross-launches", nargs=5, type=int, metavar=("B", "H", "NQ", "NK", "D"),
+                    help="run only four untimed bf16 launches of sphattn_cross_fwd on this shape and exit: the "
+                         "dispatches that an HBM byte counter (rocprofv3 --pmc FETCH_SIZE) is read on when "
+                         "the query and key counts have to differ")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run a plain 256 MiB device copy (untimed), as the known-size "
                          "reference that HBM byte counters are scaled by when profiling")
@@ -228,6 +232,19 @@ def main() -> int:
         return 0
 
     pkg.load_library()                       # fail loudly if the HIP library is not built
+    if args.cross_launches:
+        B, H, Nq, Nk, d = args.cross_launches
+        dev = torch.device("cuda:0")
+        g = torch.Generator(device="cpu").manual_seed(3)
+        qd = (torch.randn(B, H, Nq, d, generator=g) / 8).to(torch.bfloat16).to(dev)
+        kd, vd = ((torch.randn(B, H, Nk, d, generator=g) / 8).to(torch.bfloat16).to(dev) for _ in range(2))
+        out = torch.empty_like(qd)
+        for _ in range(4):
+            pkg.sphattn_cross_fwd(qd, kd, vd, None, O=out, dtype="bf16")
+        torch.cuda.synchronize()
+        print(json.dumps({"cross_launches": 4, "shape": [B, H, Nq, Nk, d],
+                          "min_read_bytes": 2 * B * H * d * (Nq + 2 * Nk)}))
+        return 0
     w, (q, k, v) = si.make_workload(args.workload)
     dev = torch.device("cuda:0")
     qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)

@@ -146,6 +146,7 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     copy_tile(0, lds0);
     for (int j = 0; j < n_tiles; ++j) {
+        if constexpr (D == 64) priority_by_tile(j);   // two workgroups per CU: keep them at the same tile
         const uint32_t cur = (j & 1) * BUF_BYTES;
         // tile j has landed (own copies), every wave is done with the other buffer
         asm volatile("" ::: "memory");

@@ -67,6 +67,26 @@ __device__ __forceinline__ float lds_read_f32(const SPH_LDS unsigned char* p)
     return *reinterpret_cast<const SPH_LDS float*>(p);
 }
 
+// Keeps the workgroups that share a CU at the same place of the stream they all read.  With two
+// waves per SIMD the arbiter prefers the older one, so one workgroup of a pair pulls ahead until
+// the tiles it streamed have left the L2 by the time the other asks for them (measured on the
+// forward at d = 64, N = 32768: 32 workgroups per XCD read K and V from HBM once, 64 read them
+// 1.6 times).  Called at the top of tile j: the wave priority falls with the tile index in steps
+// of 8 tiles, modulo 4, so whichever wave is behind, by up to three steps, holds the higher
+// priority and catches up.  s_setprio takes an immediate, hence the switch; it sits in front of
+// the tile's instruction sequence, which stays one basic block.
+__device__ __forceinline__ void priority_by_tile(int j)
+{
+    if ((j & 7) == 0) {
+        switch ((j >> 3) & 3) {
+        case 0: __builtin_amdgcn_s_setprio(3); break;
+        case 1: __builtin_amdgcn_s_setprio(2); break;
+        case 2: __builtin_amdgcn_s_setprio(1); break;
+        default: __builtin_amdgcn_s_setprio(0); break;
+        }
+    }
+}
+
 // Fragment blocks in LDS: 16 rows x 64 bytes = 1 KB, filled by one direct global -> LDS copy
 // (lane l lands at byte 16 l: row l / 4, slot l % 4) and read as matrix operands, lane (n16, g)
 // taking the 16-byte piece g of row n16.  The LDS has 64 banks of 4 bytes; a 16-byte read

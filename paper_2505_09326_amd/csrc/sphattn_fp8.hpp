@@ -402,6 +402,7 @@ void fwd_fp8_kernel(const unsigned char* __restrict__ Q, const unsigned char* __
     // end has zero keys and adds nothing
     const int n_pairs = (n_tiles + 1) / 2;
     for (int jj = 0; jj < n_pairs; ++jj) {
+        if constexpr (D == 64 && !MULT) priority_by_tile(jj);   // two workgroups per CU: keep them together
 #pragma unroll
         for (int s = 0; s < 2 * SLOTS; ++s) {
             const int par = s / SLOTS, i = s % SLOTS;

@@ -403,7 +403,8 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
 #pragma unroll
     for (int u = 0; u < PD; ++u) issue_reads(u, bprv, bcur, bnxt);
 
-    for (int j = 0; j < n_tiles; ++j) {
+    auto run_tiles = [&](const int j_begin, const int j_end) __attribute__((always_inline)) {
+      for (int j = j_begin; j < j_end; ++j) {
 #pragma unroll
         for (int s = 0; s < 2 * SLOTS; ++s) {
             const int hf = s / SLOTS, i = s % SLOTS;
@@ -558,6 +559,20 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
             }
         }
         SPH_LDS unsigned char* t = bprv; bprv = bcur; bcur = bnxt; bnxt = bnn; bnn = t;
+      }
+    };
+    if constexpr (D == 64) {
+        // Two workgroups share a CU: tiles in groups of 8, the wave priority set per group
+        // (priority_by_tile) outside the loop over tiles, which stays free of branches.  Up to
+        // 128 tiles a head's K and V (2 MB) stay in the 4 MB L2 however far the workgroups
+        // drift apart, and the tiles run as one group (a group boundary costs about 40 ns).
+        const int group = n_tiles > 128 ? 8 : n_tiles;
+        for (int j0 = 0; j0 < n_tiles; j0 += group) {
+            priority_by_tile(j0);
+            run_tiles(j0, j0 + group < n_tiles ? j0 + group : n_tiles);
+        }
+    } else {
+        run_tiles(0, n_tiles);
     }
     __builtin_amdgcn_sched_barrier(0);
     // the copies of the two tiles past the end (all zeros) must not outlive the workgroup's LDS

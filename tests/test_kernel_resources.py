@@ -63,9 +63,10 @@ def test_forward_kernels_do_not_spill(usage):
     for d in (64, 128):
         for qk in (0, 1, 2):
             for name, v in _find(usage, FWD, f"ILi{d}ELi4ELNS_6QKTypeE{qk}ELNS_4NormE0E").items():
-                # d = 64: held to 256 registers for two workgroups per CU, which costs two registers'
-                # worth of scratch with multiplicities and 20 to 68 bytes with fp8 Q/K
-                limit = 0 if d == 128 else 72 if qk == 1 else 8
+                # d = 64: held to 256 registers for two workgroups per CU, which costs up to four
+                # registers' worth of scratch with multiplicities (written and read once per query
+                # tile, outside the loop over key tiles) and 20 to 68 bytes with fp8 Q/K
+                limit = 0 if d == 128 else 72 if qk == 1 else 16
                 assert _num(v, "ScratchSize [bytes/lane]") <= limit, name
 
 
