@@ -65,6 +65,21 @@ def test_bf16_small_full_compare(pkg, oracle, B, H, N, d, tile_rows):
     assert _rel_err(got, ref) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp8qk_bf16v"])
+def test_d64_more_than_128_key_tiles(pkg, oracle, dtype):
+    """At d = 64 the forward runs more than 128 key tiles in groups of 8, the wave priority set
+    between the groups: 132 tiles (a last group of 4) with a ragged last tile, compared element
+    by element."""
+    B, H, N, d = 1, 2, 64 * 131 + 17, 64
+    print(f"case d64 long {dtype} N={N}", flush=True)
+    q, k, v = si.make_qkv(B, H, N, d, dtype, seed=77)
+    got = _gpu(pkg, q, k, v, dtype).to(torch.float64).numpy()
+    bits, kinds = _kinds(q, k, v)
+    ref = oracle.spherical_attention(*bits, kinds=kinds)
+    assert np.all(np.isfinite(got))
+    assert _rel_err(got, ref) <= TOL[dtype]
+
+
 FP8_SHAPES = [(1, 1, 1, 128), (1, 2, 33, 128), (2, 2, 300, 64), (1, 3, 257, 128), (1, 1, 1000, 64),
               (1, 2, 2048, 128), (2, 1, 512, 64)]
 
