@@ -131,12 +131,14 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     // a 1 KB copy fills two blocks: lane l lands in block l / 32, row (l % 32) / 2, piece l % 2
     const int ld_lane = (16 * wave + ((lane & 31) >> 1)) * ROWB + (lane >> 5) * 32 + (lane & 1) * 16;
-    auto copy_tile = [&](int tile, uint32_t buf) {
-#pragma unroll
-        for (int c = 0; c < KBLK; ++c) {
-            copy_to_lds(krw, buf + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
-            copy_to_lds(vrw, buf + VLDS + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
-        }
+    // piece 0 .. 2 KBLK - 1 of this wave's share of a tile: its 16 rows of K (even) or V (odd),
+    // 64-byte column block piece / 2
+    auto copy_piece = [&](int piece, int tile, uint32_t buf) {
+        const int c = piece >> 1;
+        copy_to_lds((piece & 1) ? vrw : krw, buf + ((piece & 1) ? VLDS : 0) + (wave_u * KBLK + c) * 1024, ld_lane,
+                    tile * TILE + c * 64);
+    };
+    auto copy_mult = [&](int tile, uint32_t buf) {
         if constexpr (MULT) copy_to_lds_b32(mrw, buf + MLDS, lane * 4, tile * BC * 4);   // by every wave
     };
     const int alane = (g >> 1) * 512 + n16 * 32 + (g & 1) * 16;    // row-major A operand
@@ -144,7 +146,9 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
 
     const int n_tiles = (N + BC - 1) / BC;
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    copy_tile(0, lds0);
+    copy_mult(0, lds0);
+#pragma unroll
+    for (int piece = 0; piece < 2 * KBLK; ++piece) copy_piece(piece, 0, lds0);
     for (int j = 0; j < n_tiles; ++j) {
         if constexpr (D == 64) priority_by_tile(j);   // two workgroups per CU: keep them at the same tile
         const uint32_t cur = (j & 1) * BUF_BYTES;
@@ -153,7 +157,10 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
         __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0)
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        copy_tile(j + 1, lds0 + BUF_BYTES - cur);
+        // tile j + 1 goes to the other buffer: its big copies one per step below, where their
+        // scalar instructions issue while the matrix pipe works
+        const uint32_t nxt = lds0 + BUF_BYTES - cur;
+        copy_mult(j + 1, nxt);
         const SPH_LDS unsigned char* kb_ = smem + cur;
         const SPH_LDS unsigned char* vb_ = smem + cur + VLDS;
         // The tile is worked off in a fixed sequence of steps, each with its own fragments:
@@ -202,6 +209,7 @@ void bwd_dq_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, con
         for (int st = 0; st < STEPS; ++st) {
             const int sub = st / PER_SUB, u = st % PER_SUB;
             if (st + 1 < STEPS) load_step(st + 1);
+            if (st < 2 * KBLK) copy_piece(st, j + 1, nxt);
             if (u < QG) {
                 const int kb = u / KK, kk = u % KK;
                 const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -310,30 +318,38 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
     const int n_tiles = (N + BC - 1) / BC;
     // streamed tile `it` = tile it % n_tiles of query head h0 + it / n_tiles; each head has its
     // own descriptors, so that rows past the end of a head arrive as zeros
-    auto copy_tile = [&](int hq, int tile, uint32_t buf) {
+    struct HeadSource { i32x4 q, g, r, c; };       // buffer descriptors of Q, dO, r and delta r^2 of one query head
+    auto head_source = [&](int hq) {
         const size_t qh = (size_t)(bidx * H + h0 + hq);
-        const i32x4 qrw = rsrc_words((const unsigned char*)Qv + qh * N * D * 2, (uint32_t)N * ROWB);
-        const i32x4 grw = rsrc_words((const unsigned char*)dOv + qh * N * D * 2, (uint32_t)N * ROWB);
-        const i32x4 zrw = rsrc_words(rnorm + qh * N, (uint32_t)N * 4);
-        const i32x4 drw = rsrc_words(delta + qh * N, (uint32_t)N * 4);
-#pragma unroll
-        for (int c = 0; c < KBLK; ++c) {
-            copy_to_lds(qrw, buf + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
-            copy_to_lds(grw, buf + GLDS + (wave_u * KBLK + c) * 1024, ld_lane, tile * TILE + c * 64);
-        }
-        // 64 r and 64 delta r^2 values: 16 lanes x 16 bytes each; queries past N arrive as 0.
-        // (Under a branch, unlike the multiplicities of the other kernels: this kernel gains
-        // nothing from the all-wave form, and its 48-key variant, at 512 registers, came out
-        // of the compiler with 196 bytes of scratch and wrong dK with it.)
-        if (wave == 0 && lane < BC / 4) copy_to_lds(zrw, buf + ZLDS, lane * 16, tile * BC * 4);
-        if (wave == 1 && lane < BC / 4) copy_to_lds(drw, buf + DLDS, lane * 16, tile * BC * 4);
+        return HeadSource{rsrc_words((const unsigned char*)Qv + qh * N * D * 2, (uint32_t)N * ROWB),
+                          rsrc_words((const unsigned char*)dOv + qh * N * D * 2, (uint32_t)N * ROWB),
+                          rsrc_words(rnorm + qh * N, (uint32_t)N * 4), rsrc_words(delta + qh * N, (uint32_t)N * 4)};
+    };
+    // piece 0 .. 2 KBLK - 1 of this wave's share of a tile: its 16 rows of Q (even) or dO (odd), 64-byte column block piece / 2
+    auto copy_piece = [&](const HeadSource& hs, int piece, int tile, uint32_t buf) {
+        const int c = piece >> 1;
+        copy_to_lds((piece & 1) ? hs.g : hs.q, buf + ((piece & 1) ? GLDS : 0) + (wave_u * KBLK + c) * 1024, ld_lane,
+                    tile * TILE + c * 64);
+    };
+    // 64 r and 64 delta r^2 values: 16 lanes x 16 bytes each; queries past N arrive as 0.
+    // (Under a branch, unlike the multiplicities of the other kernels: this kernel gains
+    // nothing from the all-wave form, and its 48-key variant, at 512 registers, came out
+    // of the compiler with 196 bytes of scratch and wrong dK with it.)
+    auto copy_planes = [&](const HeadSource& hs, int tile, uint32_t buf) {
+        if (wave == 0 && lane < BC / 4) copy_to_lds(hs.r, buf + ZLDS, lane * 16, tile * BC * 4);
+        if (wave == 1 && lane < BC / 4) copy_to_lds(hs.c, buf + DLDS, lane * 16, tile * BC * 4);
     };
     const int alane = (g >> 1) * 512 + n16 * 32 + (g & 1) * 16;
     const int tlane = lane * 8;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    copy_tile(0, 0, lds0);
-    int next_hq = 0, next_tile = 0;                // head and tile of the copy issued in iteration j
+    {
+        const HeadSource hs = head_source(0);
+        copy_planes(hs, 0, lds0);
+#pragma unroll
+        for (int piece = 0; piece < 2 * KBLK; ++piece) copy_piece(hs, piece, 0, lds0);
+    }
+    int next_hq = 0, next_tile = 0;                // head and tile of the copies issued in iteration j
     for (int j = 0; j < kv_group * n_tiles; ++j) {
         const uint32_t cur = (j & 1) * BUF_BYTES;
         asm volatile("" ::: "memory");
@@ -341,8 +357,13 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         if (++next_tile == n_tiles) { next_tile = 0; ++next_hq; }
-        // past the last head: the first head's first tile again, unused
-        copy_tile(next_hq < kv_group ? next_hq : 0, next_tile, lds0 + BUF_BYTES - cur);
+        // The next tile goes to the other buffer, which every wave has left: the two small copies
+        // here, the 2 KBLK big ones one per step below, where their scalar instructions (LDS
+        // base into M0, source offset) issue while the matrix pipe works.  Past the last head:
+        // the first head's first tile again, unused.
+        const HeadSource hs = head_source(next_hq < kv_group ? next_hq : 0);
+        const uint32_t nxt = lds0 + BUF_BYTES - cur;
+        copy_planes(hs, next_tile, nxt);
         const SPH_LDS unsigned char* qb_ = smem + cur;
         const SPH_LDS unsigned char* gb_ = smem + cur + GLDS;
         // Fixed sequence of steps, each with a Q-side and a dO-side fragment and 2 NK matrix
@@ -395,6 +416,7 @@ void bwd_dkv_kernel(const void* __restrict__ Qv, const void* __restrict__ Kv, co
         for (int st = 0; st < STEPS; ++st) {
             const int sub = st / PER_SUB, u = st % PER_SUB;
             if (st + 1 < STEPS) load_step(st + 1);
+            if (st < 2 * KBLK) copy_piece(hs, st, next_tile, nxt);
             if (u < QG) {
                 const int qb = u / KK, kk = u % KK;
                 const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
