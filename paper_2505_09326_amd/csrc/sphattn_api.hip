@@ -250,13 +250,18 @@ int launch_softmax32(const Problem& p)
 
 // Query rows per workgroup: 256 (64 per wave) is the efficient shape; 128 (32 per wave) reads
 // K/V fragments twice as often per flop (measured 15-25 % slower per row) but doubles the
-// number of workgroups.  It pays when 256-row tiles would leave CUs without any workgroup
-// (measured: B=H=1, N=32768, d=128: 0.46 ms against 0.57 ms); partly filled last rounds do
-// not justify it, because the part is power-bound and idle CUs give their share to the rest.
-bool narrow_tiles_pay(const Problem& p)
+// number of workgroups.  It pays when the 128-row workgroups still run all at once (one per CU
+// at d = 128, two at d = 64) and 256-row tiles would leave CUs without any: measured, one head
+// of 32768 x 128: 0.42 against 0.51 ms; 4 heads of 8192 x 64: 65 against 84 us.  With more items
+// than that the 128-row launch takes two rounds and loses (5 heads of 8192 x 128, 160 tiles:
+// 182 against 151 us; 3 x 16384 x 128, 192 tiles: 368 against 290 us): a partly filled single
+// round costs less than its share of idle CUs suggests, because the part is power-bound and
+// idle CUs give their share of the budget to the rest.
+bool narrow_tiles_pay(const Problem& p, int d)
 {
     if (p.tile_rows != 0) return p.tile_rows == 128;
-    return (long long)p.B * p.H * ((p.Nq + 255) / 256) < cu_count();
+    const long long heads = (long long)p.B * p.H, cus = cu_count();
+    return heads * ((p.Nq + 255) / 256) < cus && heads * ((p.Nq + 127) / 128) <= cus * (d == 64 ? 2 : 1);
 }
 
 template <Norm NORM, bool MULT>
@@ -264,7 +269,7 @@ int dispatch(const Problem& p, int d, int dtype)
 {
     if (dtype == SPHATTN_BF16) {
         if constexpr (NORM == Norm::Spherical && !MULT) {
-            if (narrow_tiles_pay(p)) {
+            if (narrow_tiles_pay(p, d)) {
                 if (d == 128) return launch_pipelined<128, 2, QKType::Bf16, NORM, MULT>(p);
                 return launch_pipelined<64, 2, QKType::Bf16, NORM, MULT>(p);
             }
