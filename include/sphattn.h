@@ -205,8 +205,9 @@ int sphattn_combine(const float* o_parts, const float* z_parts, int n_parts, voi
 
 /*
  * sphattn_grn_fwd with the key axis cut into n_splits slices that run as separate workgroups
- * (sphattn_partial_fwd per slice, then sphattn_combine, in two launches).  It pays when
- * B * H * N / 256 is below the number of compute units, i.e. few heads of moderate length.
+ * (sphattn_partial_fwd per slice, then sphattn_combine, in two launches; with one slice it is
+ * sphattn_grn_fwd itself and the workspace is not touched).  It pays when B * H * N / 256 is
+ * below the number of workgroups the device runs at once, i.e. few heads of moderate length.
  *
  *   n_splits       : slices asked for; 0 lets sphattn_splitkv_heuristic choose.  Slices are
  *                    whole 64-key tiles of equal size, so fewer than asked may be used (any
@@ -248,8 +249,11 @@ int sphattn_splitkv_fwd_noalloc(const void* Q, const void* K, const void* V, con
 size_t sphattn_splitkv_workspace_bytes(int B, int H, int N, int d, int n_splits);
 
 /* Number of slices sphattn_splitkv_fwd uses when asked for 0: 1 when whole-key-axis workgroups
- * already cover the compute units of the current device (256 when no device can be asked),
- * otherwise enough to cover them with slices of at least 8 tiles.  Launches nothing. */
+ * already cover the compute units of the current device (256 when no device can be asked) or
+ * when cutting is not expected to gain at least 3 %; otherwise the count, in slices of at least
+ * 8 tiles, with the lowest estimated run time: rounds of workgroups, how full they are, the
+ * slices' prologues and the combine step are priced from measurements on one MI355X.
+ * Launches nothing. */
 int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype);
 
 /*

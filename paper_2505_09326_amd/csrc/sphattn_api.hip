@@ -392,6 +392,10 @@ size_t workspace_bytes(int B, int H, int N, int d, int n_splits)
 int run_splitkv(const void* Q, const void* K, const void* V, const float* mult, void* O, float* Z,
                 int B, int H, int H_kv, int N, int d, int dtype, SplitPlan plan, void* workspace, hipStream_t stream)
 {
+    if (plan.n_splits == 1) {                      // nothing to combine: the unsplit launch
+        const Problem whole{Q, K, V, O, mult, Z, B, H, H_kv, N, N, stream};
+        return mult ? dispatch<Norm::Spherical, true>(whole, d, dtype) : dispatch<Norm::Spherical, false>(whole, d, dtype);
+    }
     const size_t rows = (size_t)B * H * N;
     float* o_parts = (float*)workspace;
     float* z_parts = o_parts + (size_t)plan.n_splits * rows * d;
@@ -618,19 +622,53 @@ size_t sphattn_splitkv_workspace_bytes(int B, int H, int N, int d, int n_splits)
 int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype)
 {
     if (B <= 0 || H <= 0 || N <= 0 || (d != 64 && d != 128)) return 1;
-    const long long kCus = cu_count();
-    const int rows_per_wg = dtype == SPHATTN_F32 ? 32 : 256;
-    const long long wg = (long long)B * H * (((long long)N + rows_per_wg - 1) / rows_per_wg);
-    if (wg >= kCus) return 1;
-    // Half-filled launches run on 128-row workgroups instead (twice as many, 15-25 % slower per
-    // row); two slices of 256-row workgroups beat that only when the combine step is small
-    // against a slice (measured: N = 32768 yes, N = 4096 and 8192 no).
-    if (dtype != SPHATTN_F32 && 2 * wg >= kCus && N < 16384) return 1;
-    // enough slices to give every CU a workgroup, but no slice shorter than 8 tiles
-    const long long want = (kCus + wg - 1) / wg;
-    const long long most = (((long long)N + kBC - 1) / kBC + 7) / 8;
-    const long long s = want < most ? want : most;
-    return plan_splits(N, (int)(s < 1 ? 1 : s)).n_splits;
+    const long long cus = cu_count();
+    const long long tiles = ((long long)N + kBC - 1) / kBC;
+    const long long most = (tiles + 7) / 8;        // no slice shorter than 8 tiles
+    if (dtype == SPHATTN_F32) {
+        // the fp32 kernel's workgroups hold 32 query rows: enough slices to give every CU one
+        const long long wg = (long long)B * H * (((long long)N + 31) / 32);
+        if (wg >= cus) return 1;
+        const long long want = (cus + wg - 1) / wg;
+        return plan_splits(N, (int)(want < most ? want : most)).n_splits;
+    }
+    // 256-row workgroups, `resident` of them at once (two per CU at d = 64).  A launch of wg S
+    // items takes rounds = ceil(wg S / resident) rounds, run equally full (balanced_grid); a round
+    // filled to the fraction f of the chip takes about 0.5 + 0.5 f of a full round's time (the
+    // part is power-bound: idle CUs give their share of the budget to the rest), and an item
+    // spends about 3.5 tile times on its prologue and tail.  In units of one full round over all
+    // keys: main(S) = (0.5 rounds / S + 0.5 wg / resident) (1 + 3.5 / tiles per slice); the combine
+    // step adds its launch (about 3 tile times) and S passes over wg / resident of the rows, 300 / N
+    // of a round each.  Unsplit, a launch of at most `resident` 128-row workgroups costs
+    // 0.6 (0.5 + wg / resident) on the same scale.  Measured against these (bf16, one GPU):
+    // 1 x 8192 x 128: S = 8 44 us (4: 57, unsplit 99); 2 x 8192 x 128: S = 4; 1 x 32768 x 128: S = 2;
+    // 8 x 4096 x 128: unsplit; 1 x 40000 x 128 (157 tiles): S = 3 533 us (2: 645, unsplit 629);
+    // 3 x 16384 x 128 (192 tiles): S = 4 291 us (2: 300, unsplit 298); 5 x 16384 x 64: S = 3 251 (unsplit 285).
+    const long long wg = (long long)B * H * (((long long)N + 255) / 256);
+    const long long resident = cus * (d == 64 ? 2 : 1);
+    if (wg >= resident) return 1;
+    const double share = (double)wg / (double)resident;
+    const double edge = 3.5;
+    double best = (0.5 + 0.5 * share) * (1.0 + edge / (double)tiles);
+    if ((long long)B * H * (((long long)N + 127) / 128) <= resident) {
+        const double narrow = 0.6 * (0.5 + share) * (1.0 + edge / (double)tiles);
+        best = narrow < best ? narrow : best;
+    }
+    best *= 0.97;                                  // split only for a gain of at least 3 %
+    int pick = 1;
+    for (long long S = 2; S <= most && S <= 32; ++S) {
+        const SplitPlan plan = plan_splits(N, (int)S);
+        if (plan.n_splits != S) continue;          // this count does not divide the tiles: same as a smaller one
+        const long long rounds = (wg * S + resident - 1) / resident;
+        const double per = (double)(plan.keys_per_split / kBC);
+        const double cost = (0.5 * (double)rounds / (double)S + 0.5 * share) * (1.0 + edge / per)
+                            + 3.0 / (double)tiles + (double)S * share * 300.0 / (double)N;
+        if (cost < best) {
+            best = cost;
+            pick = (int)S;
+        }
+    }
+    return pick;
 }
 
 int sphattn_splitkv_fwd(const void* Q, const void* K, const void* V, const float* mult, void* O, float* Z,

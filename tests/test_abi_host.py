@@ -165,7 +165,10 @@ def test_splitkv_heuristic_splits_only_underfilled_launches(lib):
     assert h(2, 16, 8192, 128, 1) == 1                # 1024 workgroups already
     assert h(1, 1, 65536, 128, 1) == 1                # 256 workgroups
     assert h(1, 1, 8192, 128, 1) == 8                 # 32 workgroups -> 8 slices of 16 tiles
-    assert h(1, 2, 4096, 64, 1) == 8                  # 32 workgroups; 64 tiles / 8 per slice
+    assert h(1, 2, 4096, 64, 1) in (7, 8)             # 32 workgroups; 64 tiles in slices of 8 to 10
+    assert h(1, 1, 40000, 128, 1) == 3                # 157 workgroups: 471 items = two rounds of 236, not 2 x 157
+    assert h(1, 3, 16384, 128, 1) == 4                # 192 workgroups: 768 items = three full rounds
+    assert h(1, 5, 16384, 64, 1) == 3                 # d = 64: 512 resident workgroups; 960 items = two rounds
     assert h(1, 8, 4096, 128, 1) == 1                 # 128 workgroups: 128-row tiles fill the CUs instead
     assert h(1, 1, 32768, 128, 1) == 2                # 128 workgroups, long: two slices of 256-row tiles
     assert h(1, 1, 300, 128, 1) == 1                  # 5 tiles: too short to cut
