@@ -235,6 +235,7 @@ int sphattn_splitkv_fwd(const void* Q, const void* K, const void* V, const float
  *   - A problem whose slices need more, sphattn_splitkv_workspace_bytes(B,H,N,d,n_splits) >
  *     SPHATTN_NOALLOC_SCRATCH_BYTES (n_splits as used: the heuristic's value when 0 is passed,
  *     never more than the number of 64-key tiles), returns SPHATTN_ERR_SCRATCH; nothing is enqueued.
+ *     One slice is the unsplit launch, uses no scratch and has no such limit.
  *   - Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU
  *     (different streams, different threads) race on it and must be ordered by the caller.
  *     Nothing in the array has to start at zero: each call writes every partial it reads.

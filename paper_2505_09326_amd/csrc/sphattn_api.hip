@@ -703,6 +703,8 @@ int sphattn_splitkv_fwd_noalloc(const void* Q, const void* K, const void* V, con
     if (n_splits < 0) return SPHATTN_ERR_SHAPE;
     if (n_splits == 0) n_splits = sphattn_splitkv_heuristic(B, H, N, d, dtype);
     const SplitPlan plan = plan_splits(N, n_splits);
+    // one slice is the unsplit launch and needs no scratch
+    if (plan.n_splits == 1) return run_splitkv(Q, K, V, mult, O, Z, B, H, H_kv, N, d, dtype, plan, nullptr, (hipStream_t)stream);
     const size_t need = sphattn_splitkv_workspace_bytes(B, H, N, d, plan.n_splits);
     if (need == 0 || need > (size_t)SPHATTN_NOALLOC_SCRATCH_BYTES) return SPHATTN_ERR_SCRATCH;
     void* ws = scratch_address();

@@ -90,3 +90,22 @@ def test_noalloc_refuses_what_does_not_fit(pkg):
     assert e.value.code == -10
     torch.cuda.synchronize()
     assert torch.all(O == 3.0)                   # nothing was enqueued
+
+
+def test_one_slice_is_the_unsplit_launch_without_scratch(pkg):
+    """One slice: both split entry points run the plain forward (bit-equal to sphattn_fwd_z),
+    and the no-allocation one has no size limit then: 2 x 16 x 8192 x 128 in one slice would
+    need 135 MB of partial pairs."""
+    B, H, N, d = 2, 16, 8192, 128
+    assert pkg.sphattn_splitkv_workspace_bytes(B, H, N, d, 1) > pkg.NOALLOC_SCRATCH_BYTES
+    assert pkg.sphattn_splitkv_heuristic(B, H, N, d, "bf16") == 1
+    q, k, v = (t.to(DEV) for t in si.make_qkv(B, H, N, d, "bf16", seed=5))
+    want, zw = pkg.sphattn_fwd_z(q, k, v, dtype="bf16")
+    O = torch.empty_like(q)
+    Z = torch.empty((B, H, N), dtype=torch.float32, device=DEV)
+    for n_splits in (0, 1):
+        O.zero_()
+        Z.zero_()
+        pkg.sphattn_splitkv_fwd_noalloc(q, k, v, O, Z=Z, n_splits=n_splits, dtype="bf16")
+        torch.cuda.synchronize()
+        assert torch.equal(O, want) and torch.equal(Z, zw)
