@@ -189,8 +189,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C3", help="C1..C5, or P1 = the paper's own point (fp16, d=128, N=3x13824); "
-                         "default C3: the configuration the target is quoted on")
+    ap.add_argument("--workload", default="C3", help="C1..C5, or P1 = the paper's own point (fp16, d=128, N=3x13824), "
+                         "or a shape of one's own as B,H,N,d[,dtype]; default C3: the configuration the target is quoted on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-twin", action="store_true")
     ap.add_argument("--no-after-idle", action="store_true", help="skip the second timing taken after 1 s of idle")

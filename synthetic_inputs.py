@@ -100,7 +100,14 @@ def make_qkv(B, H, N, d, dtype, seed, factor=1.0):
 
 
 def make_workload(name: str):
-    w = WORKLOADS[name]
+    """A named workload, or a shape of one's own written "B,H,N,d" or "B,H,N,d,dtype" (bf16
+    when not given; seed BASE_SEED + 99)."""
+    if "," in name:
+        parts = name.split(",")
+        B, H, N, d = (int(x) for x in parts[:4])
+        w = Workload(name, 99, B, H, N, d, parts[4] if len(parts) > 4 else "bf16")
+    else:
+        w = WORKLOADS[name]
     return w, make_qkv(w.B, w.H, w.N, w.d, w.dtype, w.seed, w.factor)
 
 
