@@ -235,7 +235,8 @@ int sphattn_splitkv_fwd(const void* Q, const void* K, const void* V, const float
  *   - A problem whose slices need more, sphattn_splitkv_workspace_bytes(B,H,N,d,n_splits) >
  *     SPHATTN_NOALLOC_SCRATCH_BYTES (n_splits as used: the heuristic's value when 0 is passed,
  *     never more than the number of 64-key tiles), returns SPHATTN_ERR_SCRATCH; nothing is enqueued.
- *     One slice is the unsplit launch, uses no scratch and has no such limit.
+ *     One slice is the unsplit launch, uses no scratch and has no such limit; when 0 is passed
+ *     and the heuristic's slices would not fit, one slice is used instead of an error.
  *   - Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU
  *     (different streams, different threads) race on it and must be ordered by the caller.
  *     Nothing in the array has to start at zero: each call writes every partial it reads.
@@ -250,8 +251,8 @@ int sphattn_splitkv_fwd_noalloc(const void* Q, const void* K, const void* V, con
 size_t sphattn_splitkv_workspace_bytes(int B, int H, int N, int d, int n_splits);
 
 /* Number of slices sphattn_splitkv_fwd uses when asked for 0: 1 when whole-key-axis workgroups
- * already cover the compute units of the current device (256 when no device can be asked) or
- * when cutting is not expected to gain at least 3 %; otherwise the count, in slices of at least
+ * fill their rounds on the compute units of the current device (256 when no device can be
+ * asked) or when cutting is not expected to gain at least 3 %; otherwise the count, in slices of at least
  * 8 tiles, with the lowest estimated run time: rounds of workgroups, how full they are, the
  * slices' prologues and the combine step are priced from measurements on one MI355X.
  * Launches nothing. */

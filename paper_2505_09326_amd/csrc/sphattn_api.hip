@@ -644,13 +644,14 @@ int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype)
     // 1 x 8192 x 128: S = 8 44 us (4: 57, unsplit 99); 2 x 8192 x 128: S = 4; 1 x 32768 x 128: S = 2;
     // 8 x 4096 x 128: unsplit; 1 x 40000 x 128 (157 tiles): S = 3 533 us (2: 645, unsplit 629);
     // 3 x 16384 x 128 (192 tiles): S = 4 291 us (2: 300, unsplit 298); 5 x 16384 x 64: S = 3 251 (unsplit 285).
+    // The same holds above one round: 8 x 20000 x 128 (632 tiles, 2.47 rounds): S = 2 1080 us, unsplit 1174.
     const long long wg = (long long)B * H * (((long long)N + 255) / 256);
     const long long resident = cus * (d == 64 ? 2 : 1);
-    if (wg >= resident) return 1;
     const double share = (double)wg / (double)resident;
     const double edge = 3.5;
-    double best = (0.5 + 0.5 * share) * (1.0 + edge / (double)tiles);
-    if ((long long)B * H * (((long long)N + 127) / 128) <= resident) {
+    const long long rounds1 = (wg + resident - 1) / resident;
+    double best = (0.5 * (double)rounds1 + 0.5 * share) * (1.0 + edge / (double)tiles);
+    if (wg < resident && (long long)B * H * (((long long)N + 127) / 128) <= resident) {
         const double narrow = 0.6 * (0.5 + share) * (1.0 + edge / (double)tiles);
         best = narrow < best ? narrow : best;
     }
@@ -663,7 +664,8 @@ int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype)
         const double per = (double)(plan.keys_per_split / kBC);
         const double cost = (0.5 * (double)rounds / (double)S + 0.5 * share) * (1.0 + edge / per)
                             + 3.0 / (double)tiles + (double)S * share * 300.0 / (double)N;
-        if (cost < best) {
+        // above one round the workspace is large: more slices only for more than 1 %
+        if (cost < (wg >= resident ? 0.99 : 1.0) * best) {
             best = cost;
             pick = (int)S;
         }
@@ -701,7 +703,11 @@ int sphattn_splitkv_fwd_noalloc(const void* Q, const void* K, const void* V, con
     const int rc = check_args(Q, K, V, O, out_bytes_of(B, H, N, d, dtype), mult, Z, B, H, H_kv, N, N, d, dtype);
     if (rc != SPHATTN_OK) return rc;
     if (n_splits < 0) return SPHATTN_ERR_SHAPE;
-    if (n_splits == 0) n_splits = sphattn_splitkv_heuristic(B, H, N, d, dtype);
+    if (n_splits == 0) {                           // the library's choice, if the array holds it
+        n_splits = sphattn_splitkv_heuristic(B, H, N, d, dtype);
+        if (sphattn_splitkv_workspace_bytes(B, H, N, d, plan_splits(N, n_splits).n_splits) > (size_t)SPHATTN_NOALLOC_SCRATCH_BYTES)
+            n_splits = 1;
+    }
     const SplitPlan plan = plan_splits(N, n_splits);
     // one slice is the unsplit launch and needs no scratch
     if (plan.n_splits == 1) return run_splitkv(Q, K, V, mult, O, Z, B, H, H_kv, N, d, dtype, plan, nullptr, (hipStream_t)stream);

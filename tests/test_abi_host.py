@@ -169,6 +169,8 @@ def test_splitkv_heuristic_splits_only_underfilled_launches(lib):
     assert h(1, 1, 40000, 128, 1) == 3                # 157 workgroups: 471 items = two rounds of 236, not 2 x 157
     assert h(1, 3, 16384, 128, 1) == 4                # 192 workgroups: 768 items = three full rounds
     assert h(1, 5, 16384, 64, 1) == 3                 # d = 64: 512 resident workgroups; 960 items = two rounds
+    assert h(1, 8, 20000, 128, 1) == 2                # 632 workgroups = 2.47 rounds: 1264 half-length items = 5 rounds
+    assert h(1, 8, 40960, 128, 1) == 1                # 1280 workgroups = five full rounds
     assert h(1, 8, 4096, 128, 1) == 1                 # 128 workgroups: 128-row tiles fill the CUs instead
     assert h(1, 1, 32768, 128, 1) == 2                # 128 workgroups, long: two slices of 256-row tiles
     assert h(1, 1, 300, 128, 1) == 1                  # 5 tiles: too short to cut
