@@ -188,6 +188,35 @@ long long balanced_grid(long long n_items, long long resident)
     return grid < resident ? grid : resident;
 }
 
+// Storage types for which the 128-row kernel exists (fp8 Q/K needs whole score instructions per slot).
+template <QKType QKT>
+constexpr bool p_tile_rows_free() { return QKT == QKType::Bf16 || QKT == QKType::F16; }
+
+// The 128-row kernel on the second half of a launch whose items do not fill their last round
+// (launch_pipelined): items item_begin .. n_items - 1 of the 256-row numbering, one half of an
+// item per workgroup.  resident_only: configure the kernel and return how many of its
+// workgroups run at once (0: unknown) without launching.
+template <int D, QKType QKT>
+long long launch_halves(const Problem& p, int n_qtiles, int n_items, int item_begin, bool backwards, bool resident_only)
+{
+    constexpr int EQ = QKT == QKType::Fp8 ? 1 : 2;
+    constexpr int lds_bytes = kNBuf * kBC * (D * EQ + D * 2);
+    auto kern = fwd_pipelined_kernel<D, 2, QKT, Norm::Spherical, false, false>;
+    static std::atomic<uint64_t> done{0};
+    static std::atomic<int> period[64];
+    if (!raise_lds_limit(kern, lds_bytes, done)) return 0;
+    const long long resident = (long long)kXcds * stream_period(kern, lds_bytes, period);
+    if (resident_only) return resident;
+    const int rest = n_items - item_begin;
+    const unsigned grid = 2u * kXcds * (unsigned)((rest + kXcds - 1) / kXcds);
+    const float scale_log2 = 1.4426950408889634f / __builtin_sqrtf((float)D);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds_bytes, p.stream,
+                       p.Q, p.K, p.V, p.O, p.mult, p.Z,
+                       p.Nq, p.Nk, p.H, p.H / p.H_kv, n_qtiles, n_items, 1, 0, scale_log2,
+                       item_begin, n_items, backwards ? 2 : 1);
+    return hipGetLastError() == hipSuccess ? resident : -1;
+}
+
 template <int D, int NQ, QKType QKT, Norm NORM, bool MULT, bool PARTIAL = false>
 int launch_pipelined(const Problem& p)
 {
@@ -205,11 +234,36 @@ int launch_pipelined(const Problem& p)
     // persistent workgroups: as many as the chip runs at once (a multiple of the XCD count), or
     // one per item if that is fewer
     const long long resident = (long long)kXcds * stream_period(kern, lds_bytes, period);
+    // d = 64, a remainder of at most half a round behind at least one full round: the full rounds
+    // run here and the remaining tiles as two 128-row halves each in a launch of their own, which
+    // fills twice as many CUs for 0.6 of the time.  In full rounds, with f = remainder / resident:
+    // rounds + 0.3 + 0.6 f against 0.5 (rounds + 1) + 0.5 (rounds + f) for the balanced grid (a
+    // round filled to the fraction x takes about 0.5 + 0.5 x of a full one).  Measured: 20 heads of
+    // 8192 x 64 (640 tiles, 1.25 rounds) 273 against 306 us, 12 x 12345 x 64 387 against 425 us.
+    // At d = 128 the 128-row kernel is too much slower per row for this (8 x 41472 x 128: 4.84
+    // against 4.66 ms, 4 x 20000 x 128: 649 against 632 us), and the balanced grid stays.
+    constexpr bool HAS_HALVES = D == 64 && NQ == 4 && !PARTIAL && !MULT && NORM == Norm::Spherical && p_tile_rows_free<QKT>();
+    if constexpr (HAS_HALVES) {
+        const long long full = resident > 0 ? n_wg / resident : 0, rem = resident > 0 ? n_wg % resident : 0;
+        if (p.tile_rows == 0 && full >= 1 && rem > 0) {
+            const long long narrow = launch_halves<D, QKT>(p, n_qtiles, (int)n_wg, 0, false, true);
+            const double f = (double)rem / (double)resident;
+            if (2 * rem <= narrow && (double)full + 0.3 + 0.6 * f < 0.97 * ((double)full + 0.5 + 0.5 * f)) {
+                const int n_main = (int)(full * resident);
+                hipLaunchKernelGGL(kern, dim3((unsigned)resident), dim3(kThreads), lds_bytes, p.stream,
+                                   p.Q, p.K, p.V, p.O, p.mult, p.Z,
+                                   p.Nq, p.Nk, p.H, p.H / p.H_kv, n_qtiles, (int)n_wg,
+                                   p.n_splits, p.keys_per_split, scale_log2, 0, n_main, 0);
+                if (hipGetLastError() != hipSuccess) return SPHATTN_ERR_LAUNCH;
+                return launch_halves<D, QKT>(p, n_qtiles, (int)n_wg, n_main, full % 2 == 1, false) >= 0 ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
+            }
+        }
+    }
     const long long grid = balanced_grid(n_wg, resident);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds_bytes, p.stream,
                        p.Q, p.K, p.V, p.O, p.mult, p.Z,
                        p.Nq, p.Nk, p.H, p.H / p.H_kv, n_qtiles, (int)n_wg,
-                       p.n_splits, p.keys_per_split, scale_log2);
+                       p.n_splits, p.keys_per_split, scale_log2, 0, (int)n_wg, 0);
     return hipGetLastError() == hipSuccess ? SPHATTN_OK : SPHATTN_ERR_LAUNCH;
 }
 

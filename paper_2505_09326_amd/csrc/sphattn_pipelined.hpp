@@ -135,7 +135,7 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
                         const float* __restrict__ mult, float* __restrict__ Zv,
                         int Nq, int Nk, int H, int kv_group, int n_qtiles, int n_items,
                         int n_splits, int keys_per_split, float scale_log2,
-                        int item, bool backwards, bool stream_out)
+                        int item, bool backwards, bool stream_out, int tile_rows, int row_off)
 {
     constexpr bool FP8 = QKT == QKType::Fp8;
     constexpr bool HALF = QKT == QKType::F16;      // 16-bit type of V, O and P
@@ -201,7 +201,8 @@ void fwd_pipelined_item(const void* __restrict__ Qv, const void* __restrict__ Kv
     const size_t kv_off = ((size_t)(bidx * (H / kv_group) + (bh % H) / kv_group) * Nk + k0) * D;
     const unsigned char* Qh = (const unsigned char*)Qv + head_off * EQ;
     const unsigned short* V = (const unsigned short*)Vv;
-    const int q0 = qt * BR + wave * 16 * NQ;
+    // query tiles are tile_rows apart (BR, or twice BR when the item is one half, row_off, of a wider tile)
+    const int q0 = qt * tile_rows + row_off + wave * 16 * NQ;
 
     // ---- per-lane LDS byte offsets inside a tile; everything else is an immediate
     // K fragment, 16-bit (kb, kk): row 16kb + n16, bytes 64kk + 16g .. +15: piece g of row n16 of
@@ -678,16 +679,34 @@ void fwd_pipelined_kernel(const void* __restrict__ Qv, const void* __restrict__ 
                           const void* __restrict__ Vv, void* __restrict__ Ov,
                           const float* __restrict__ mult, float* __restrict__ Zv,
                           int Nq, int Nk, int H, int kv_group, int n_qtiles, int n_items,
-                          int n_splits, int keys_per_split, float scale_log2)
+                          int n_splits, int keys_per_split, float scale_log2,
+                          int item_begin, int item_end, int halves)
 {
-    const bool several_batches = n_items > (int)gridDim.x;
+    constexpr int BR = kWaves * 16 * NQ;
+    if (halves) {
+        // Remainder launch: the items item_begin .. item_end - 1 of a launch whose tiles are
+        // 2 BR rows (n_qtiles and n_items count those), one half of an item per workgroup.
+        // Workgroups 16u .. 16u+7 take the first halves of items item_begin + 8u .. +7,
+        // workgroups 16u+8 .. 16u+15 the second halves: a workgroup stays on the XCD that owns
+        // its item's range (item_begin is a multiple of the XCD count).
+        const int t = blockIdx.x, half = (t / kXcds) & 1;
+        const int item = item_begin + (t / (2 * kXcds)) * kXcds + t % kXcds;
+        if (item >= item_end) return;
+        const int qt = xcd_contiguous_id(item, n_items) % n_qtiles;
+        if (qt * 2 * BR + half * BR >= Nq) return;     // the tile's second half lies past the last row
+        fwd_pipelined_item<D, NQ, QKT, NORM, MULT, PARTIAL>(Qv, Kv, Vv, Ov, mult, Zv, Nq, Nk, H, kv_group, n_qtiles, n_items,
+                                                            n_splits, keys_per_split, scale_log2,
+                                                            item, halves == 2, true, 2 * BR, half * BR);
+        return;
+    }
+    const bool several_batches = item_end - item_begin > (int)gridDim.x || item_end < n_items;
     int batch = 0;
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x, ++batch) {
+    for (int item = item_begin + blockIdx.x; item < item_end; item += gridDim.x, ++batch) {
         // the LDS buffers change hands: every wave must be done with the previous item's tiles
         if (batch > 0) __syncthreads();
         fwd_pipelined_item<D, NQ, QKT, NORM, MULT, PARTIAL>(Qv, Kv, Vv, Ov, mult, Zv, Nq, Nk, H, kv_group, n_qtiles, n_items,
                                                             n_splits, keys_per_split, scale_log2,
-                                                            item, batch % 2 == 1, several_batches);
+                                                            item, batch % 2 == 1, several_batches, BR, 0);
     }
 }
 

@@ -80,12 +80,14 @@ def test_d64_more_than_128_key_tiles(pkg, oracle, dtype):
     assert _rel_err(got, ref) <= TOL[dtype]
 
 
-@pytest.mark.parametrize("B,H,N,d", [(1, 33, 2048, 128), (1, 65, 2000, 64), (1, 20, 2100, 128)])
+@pytest.mark.parametrize("B,H,N,d", [(1, 33, 2048, 128), (1, 65, 2000, 64), (1, 65, 1900, 64), (1, 20, 2100, 128)])
 def test_more_items_than_resident_workgroups_with_a_remainder(pkg, oracle, B, H, N, d):
     """264 query tiles for 256 CUs (d = 128), 520 for 512 resident workgroups (d = 64): the items
     take two rounds, which the library runs with a grid of half the items, rounded up to the
     XCD count, instead of a full round and a nearly empty one; every workgroup then has a
-    second, backwards item, some of them none.  Third case: 180 tiles of 256 rows, which 128-row
+    second, backwards item, some of them none.  At d = 64 the remainder (8 tiles) runs as 128-row
+    halves in a launch of its own; with N = 1900 the last tile's second half is empty.  Last case:
+    180 tiles of 256 rows, which 128-row
     tiles would turn into 340 workgroups and two rounds: one partly filled round of 256-row tiles."""
     print(f"case remainder B={B} H={H} N={N} d={d}", flush=True)
     q, k, v = si.make_qkv(B, H, N, d, "bf16", seed=500 + H)
