@@ -705,6 +705,13 @@ int sphattn_splitkv_heuristic(int B, int H, int N, int d, int dtype)
     const double edge = 3.5;
     const long long rounds1 = (wg + resident - 1) / resident;
     double best = (0.5 * (double)rounds1 + 0.5 * share) * (1.0 + edge / (double)tiles);
+    if (d == 64 && (dtype == SPHATTN_BF16 || dtype == SPHATTN_F16) && wg > resident && wg % resident != 0 &&
+        2 * (wg % resident) <= resident) {
+        // the unsplit launch runs this remainder as 128-row halves (launch_pipelined)
+        const double halves = ((double)(wg / resident) + 0.3 + 0.6 * (double)(wg % resident) / (double)resident) *
+                              (1.0 + edge / (double)tiles);
+        best = halves < best ? halves : best;
+    }
     if (wg < resident && (long long)B * H * (((long long)N + 127) / 128) <= resident) {
         const double narrow = 0.6 * (0.5 + share) * (1.0 + edge / (double)tiles);
         best = narrow < best ? narrow : best;
