@@ -254,7 +254,10 @@ def test_splitkv_few_heads_at_full_length(pkg, oracle):
 
 CROSS_SHAPES = [(1, 2, 2, 1, 700, 128, "bf16", False), (2, 4, 2, 300, 77, 64, "bf16", True),
                 (1, 2, 1, 513, 2049, 128, "f16", True), (1, 3, 3, 64, 1000, 64, "fp8qk_bf16v", False),
-                (2, 2, 1, 257, 130, 128, "f32", True), (1, 1, 1, 1000, 1, 64, "bf16", False)]
+                (2, 2, 1, 257, 130, 128, "f32", True), (1, 1, 1, 1000, 1, 64, "bf16", False),
+                # 528 query tiles of d = 64 for 512 resident workgroups, shared K/V heads: one full
+                # round, then the 16 remaining tiles as 128-row halves (the last ones half empty)
+                (1, 66, 33, 1900, 300, 64, "f16", False)]
 
 
 @pytest.mark.parametrize("B,H,H_kv,Nq,Nk,d,dtype,with_mult", CROSS_SHAPES)
