@@ -190,9 +190,9 @@ long long balanced_grid(long long n_items, long long resident)
 
 // Storage types for which the 128-row kernel exists (fp8 Q/K needs whole score instructions per slot).
 template <QKType QKT>
-constexpr bool p_tile_rows_free() { return QKT == QKType::Bf16 || QKT == QKType::F16; }
+constexpr bool has_narrow_kernel() { return QKT == QKType::Bf16 || QKT == QKType::F16; }
 
-// The 128-row kernel on the second half of a launch whose items do not fill their last round
+// The 128-row kernel on the remainder of a launch whose items do not fill their last round
 // (launch_pipelined): items item_begin .. n_items - 1 of the 256-row numbering, one half of an
 // item per workgroup.  resident_only: configure the kernel and return how many of its
 // workgroups run at once (0: unknown) without launching.
@@ -242,7 +242,7 @@ int launch_pipelined(const Problem& p)
     // 8192 x 64 (640 tiles, 1.25 rounds) 273 against 306 us, 12 x 12345 x 64 387 against 425 us.
     // At d = 128 the 128-row kernel is too much slower per row for this (8 x 41472 x 128: 4.84
     // against 4.66 ms, 4 x 20000 x 128: 649 against 632 us), and the balanced grid stays.
-    constexpr bool HAS_HALVES = D == 64 && NQ == 4 && !PARTIAL && !MULT && NORM == Norm::Spherical && p_tile_rows_free<QKT>();
+    constexpr bool HAS_HALVES = D == 64 && NQ == 4 && !PARTIAL && !MULT && NORM == Norm::Spherical && has_narrow_kernel<QKT>();
     if constexpr (HAS_HALVES) {
         const long long full = resident > 0 ? n_wg / resident : 0, rem = resident > 0 ? n_wg % resident : 0;
         if (p.tile_rows == 0 && full >= 1 && rem > 0) {
