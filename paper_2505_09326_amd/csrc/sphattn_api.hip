@@ -16,7 +16,7 @@ namespace {
 
 using namespace sphattn;
 
-constexpr int kVersion = 500;   // 0.5.0
+constexpr int kVersion = 510;   // 0.5.1
 
 // [a, a+an) and [b, b+bn) share a byte.  Written with differences, so that a range reaching the
 // top of the address space cannot wrap the comparison.
